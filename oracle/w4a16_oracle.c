@@ -1,0 +1,263 @@
+/*
+ * CPU oracle for the fused W4A16 skinny GEMM  C[m,n] = A[m,k] . dequant(Wq)[k,n].
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP kernels are
+ * checked against.  Nothing in the product path may call it; it shares no code, header,
+ * table or helper with the HIP sources.
+ *
+ * What it follows (paper: "Accelerating a Triton Fused Kernel for W4A16 Quantized Inference
+ * with SplitK work decomposition"):
+ *   - Section 2, first paragraph: inputs are an fp16 activation matrix, a packed int32
+ *     weight matrix and scale / zero parameters; the weights are unpacked with bitwise
+ *     operations, shifted by the zero point and scaled (GPTQ-style int4).
+ *   - Algorithm 1: an fp32 accumulator tile, a loop over k-blocks that adds dot products,
+ *     and one final addition of every program's partial tile into C.  SplitK and the
+ *     data-parallel tiling only change where and in which order partial sums are formed,
+ *     so the result is the plain matrix product; this file is that product written out.
+ *
+ * Readings of points the paper leaves open (each is exercised by a test):
+ *   - field i of a packed word is bits [4i, 4i+3]; in qweight field i of word row r is
+ *     k = 8r + i; in qzeros field i of word column c is output column 8c + i;
+ *   - w[kk][j] = (q[kk][j] - z[kk/g][j]) * s[kk/g][j], no "+1" zero-point offset;
+ *   - groups are contiguous runs of g rows along k;
+ *   - fp32 -> fp16 conversion rounds to nearest, ties to even.
+ *
+ * Accumulation modes: 0 = fp64 accumulator (every product a*w is exact in fp64, so this is
+ * the definition up to one rounding per addition at 2^-53), 1 = fp32 accumulator with fp32
+ * products, the precision Algorithm 1 names.  Summation order is ascending k inside each
+ * partial sum and ascending partition index across partial sums.
+ *
+ * Parity status: all functions below are pinned by tests/test_oracle_*.py against closed
+ * forms, exact-rational brute force, numpy's float16 and matmul, and pack/unpack bijection.
+ * Unpinned: agreement with the bit layout of the authors' own kernel and with real GPTQ
+ * checkpoints (the paper prints neither).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---------------------------------------------------------------- fp16 <-> fp32/fp64 */
+
+float w4a16_oracle_half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    uint32_t e = (h >> 10) & 0x1Fu;
+    uint32_t f = h & 0x3FFu;
+    uint32_t bits;
+    if (e == 0) {
+        if (f == 0) {
+            bits = sign;
+        } else { /* subnormal: value = f * 2^-24, normalise */
+            int shift = 0;
+            while (!(f & 0x400u)) { f <<= 1; ++shift; }
+            f &= 0x3FFu;
+            bits = sign | ((uint32_t)(127 - 15 + 1 - shift) << 23) | (f << 13);
+        }
+    } else if (e == 31) {
+        bits = sign | 0x7F800000u | (f << 13);
+    } else {
+        bits = sign | ((e + 127 - 15) << 23) | (f << 13);
+    }
+    float out;
+    memcpy(&out, &bits, 4);
+    return out;
+}
+
+/* Round a double to the nearest fp16, ties to even, in one rounding. */
+uint16_t w4a16_oracle_double_to_half(double x)
+{
+    uint64_t bits;
+    memcpy(&bits, &x, 8);
+    uint16_t sign = (uint16_t)((bits >> 63) << 15);
+    int exp = (int)((bits >> 52) & 0x7FF);
+    uint64_t man = bits & ((1ULL << 52) - 1);
+    if (exp == 0x7FF) return (uint16_t)(sign | (man ? 0x7E00 : 0x7C00));
+    if (exp == 0) return sign; /* zero or double subnormal: far below half's range */
+    int e = exp - 1023;
+    if (e > 15) return (uint16_t)(sign | 0x7C00);
+    uint64_t sig = (1ULL << 52) | man; /* value = sig * 2^(e-52) */
+    int shift = 42;                     /* keep 11 significant bits */
+    if (e < -14) shift += (-14 - e);    /* half subnormal: fixed exponent -14 */
+    if (shift > 63) return sign;
+    uint64_t q = sig >> shift;
+    uint64_t rem = sig & ((1ULL << shift) - 1);
+    uint64_t halfway = 1ULL << (shift - 1);
+    if (rem > halfway || (rem == halfway && (q & 1))) ++q;
+    uint32_t out;
+    if (e < -14) out = (uint32_t)q;                            /* q == 1024 becomes the least normal */
+    else out = ((uint32_t)(e + 15) << 10) + (uint32_t)(q - 1024); /* q == 2048 carries into the exponent */
+    return (uint16_t)(sign | out);
+}
+
+uint16_t w4a16_oracle_float_to_half(float x) { return w4a16_oracle_double_to_half((double)x); }
+
+/* ---------------------------------------------------------------- pack / unpack */
+
+/* q[kk][j] = field (kk % 8) of qweight[kk / 8][j];  q is uint8 [k, n]. */
+void w4a16_oracle_unpack_qweight(const int32_t* qweight, uint8_t* q, int n, int k)
+{
+    for (int kk = 0; kk < k; ++kk)
+        for (int j = 0; j < n; ++j) {
+            uint32_t word = (uint32_t)qweight[(size_t)(kk / 8) * n + j];
+            q[(size_t)kk * n + j] = (uint8_t)((word >> (4 * (kk % 8))) & 0xFu);
+        }
+}
+
+/* z[gi][j] = field (j % 8) of qzeros[gi][j / 8];  z is uint8 [groups, n]. */
+void w4a16_oracle_unpack_qzeros(const int32_t* qzeros, uint8_t* z, int n, int groups)
+{
+    for (int gi = 0; gi < groups; ++gi)
+        for (int j = 0; j < n; ++j) {
+            uint32_t word = (uint32_t)qzeros[(size_t)gi * (n / 8) + j / 8];
+            z[(size_t)gi * n + j] = (uint8_t)((word >> (4 * (j % 8))) & 0xFu);
+        }
+}
+
+void w4a16_oracle_pack_qweight(const uint8_t* q, int32_t* qweight, int n, int k)
+{
+    for (int r = 0; r < k / 8; ++r)
+        for (int j = 0; j < n; ++j) {
+            uint32_t word = 0;
+            for (int i = 0; i < 8; ++i)
+                word |= (uint32_t)(q[(size_t)(8 * r + i) * n + j] & 0xFu) << (4 * i);
+            qweight[(size_t)r * n + j] = (int32_t)word;
+        }
+}
+
+void w4a16_oracle_pack_qzeros(const uint8_t* z, int32_t* qzeros, int n, int groups)
+{
+    for (int gi = 0; gi < groups; ++gi)
+        for (int c = 0; c < n / 8; ++c) {
+            uint32_t word = 0;
+            for (int i = 0; i < 8; ++i)
+                word |= (uint32_t)(z[(size_t)gi * n + 8 * c + i] & 0xFu) << (4 * i);
+            qzeros[(size_t)gi * (n / 8) + c] = (int32_t)word;
+        }
+}
+
+/* ---------------------------------------------------------------- dequantisation */
+
+static inline int field_of(const int32_t* words, size_t word_index, int field)
+{
+    return (int)(((uint32_t)words[word_index] >> (4 * field)) & 0xFu);
+}
+
+/* W[kk][j] = (q - z) * s as fp32; exact: |q - z| <= 15 and an fp16 scale has 11 bits. */
+void w4a16_oracle_dequant(const int32_t* qweight, const uint16_t* scales, const int32_t* qzeros,
+                          float* W, int n, int k, int group_size)
+{
+    for (int kk = 0; kk < k; ++kk) {
+        int gi = kk / group_size;
+        for (int j = 0; j < n; ++j) {
+            int q = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);
+            int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);
+            float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);
+            W[(size_t)kk * n + j] = (float)(q - z) * s;
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- the product */
+
+/* Which partial sum a k index belongs to.
+ * block_k == 0: split_k contiguous chunks of k / split_k.
+ * block_k  > 0: Algorithm 1's walk: program pid_k starts at k-block pid_k and advances by
+ *               block_k * split_k, so k-block b belongs to partial sum b % split_k. */
+static inline int partition_of(int kk, int k, int split_k, int block_k)
+{
+    if (split_k == 1) return 0;
+    if (block_k == 0) return kk / (k / split_k);
+    return (kk / block_k) % split_k;
+}
+
+/*
+ * Cref (fp64 [m,n], required) and C16 (fp16 [m,n], may be NULL) <- A . dequant(Wq).
+ * acc_mode 0: fp64 accumulators; 1: fp32 products and accumulators.
+ * split_k >= 1 partial sums are formed separately from zero and then added in ascending
+ * partition order, as the final additions into C of Algorithm 1 do in some order.
+ * threads: OpenMP threads over blocks of output columns (each output element is still
+ * computed by one thread with the same operation order); <= 0 means the runtime default.
+ * Returns the number of threads used, or a negative number on bad arguments.
+ */
+int w4a16_oracle_gemm(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
+                      const int32_t* qzeros, double* Cref, uint16_t* C16,
+                      int m, int n, int k, int group_size,
+                      int split_k, int block_k, int acc_mode, int threads)
+{
+    if (!A || !qweight || !scales || !qzeros || !Cref) return -1;
+    if (m < 1 || n < 8 || n % 8 || group_size < 8 || group_size % 8 || k < group_size || k % group_size) return -2;
+    if (split_k < 1 || (block_k == 0 && k % split_k) || block_k < 0) return -3;
+    if (acc_mode != 0 && acc_mode != 1) return -4;
+
+    const int col_block = 128;
+    const int n_blocks = (n + col_block - 1) / col_block;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+
+#pragma omp parallel for schedule(static)
+    for (int blk = 0; blk < n_blocks; ++blk) {
+        const int j0 = blk * col_block;
+        const int j1 = (j0 + col_block < n) ? j0 + col_block : n;
+        const int w = j1 - j0;
+        /* part[p][i][jj]: partial sum p of output (i, j0 + jj) */
+        double* part64 = NULL;
+        float* part32 = NULL;
+        if (acc_mode == 0) part64 = (double*)calloc((size_t)split_k * m * w, sizeof(double));
+        else part32 = (float*)calloc((size_t)split_k * m * w, sizeof(float));
+        float* wrow = (float*)malloc((size_t)w * sizeof(float));
+
+        for (int kk = 0; kk < k; ++kk) {
+            const int gi = kk / group_size;
+            const int p = partition_of(kk, k, split_k, block_k);
+            for (int jj = 0; jj < w; ++jj) {
+                const int j = j0 + jj;
+                int q = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);
+                int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);
+                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);
+                wrow[jj] = (float)(q - z) * s; /* exact */
+            }
+            for (int i = 0; i < m; ++i) {
+                const float a = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
+                if (acc_mode == 0) {
+                    double* acc = part64 + ((size_t)p * m + i) * w;
+                    for (int jj = 0; jj < w; ++jj) acc[jj] += (double)a * (double)wrow[jj];
+                } else {
+                    float* acc = part32 + ((size_t)p * m + i) * w;
+                    for (int jj = 0; jj < w; ++jj) {
+                        float prod = a * wrow[jj];
+                        acc[jj] += prod;
+                    }
+                }
+            }
+        }
+        for (int i = 0; i < m; ++i)
+            for (int jj = 0; jj < w; ++jj) {
+                double total;
+                if (acc_mode == 0) {
+                    double t = 0.0;
+                    for (int p = 0; p < split_k; ++p) t += part64[((size_t)p * m + i) * w + jj];
+                    total = t;
+                } else {
+                    float t = 0.0f;
+                    for (int p = 0; p < split_k; ++p) t += part32[((size_t)p * m + i) * w + jj];
+                    total = (double)t;
+                }
+                Cref[(size_t)i * n + j0 + jj] = total;
+                if (C16) C16[(size_t)i * n + j0 + jj] = w4a16_oracle_double_to_half(total);
+            }
+        free(part64);
+        free(part32);
+        free(wrow);
+    }
+    return used;
+}

@@ -1,0 +1,205 @@
+"""ctypes binding of the C oracle (oracle/w4a16_oracle.c).  Test infrastructure only.
+
+Every function takes and returns numpy host arrays.  The shared library is built by
+oracle/build.py (also run by __graft_entry__.build()); if it is missing or older than
+its source it is compiled on first use, which needs only gcc.
+
+`Oracle(path)` binds any build of the C file (the mutation tests bind deliberately
+broken copies); the module-level functions use the committed source.
+"""
+from __future__ import annotations
+
+import ctypes
+import pathlib
+
+import numpy as np
+
+_HERE = pathlib.Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libw4a16_oracle.so"
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+class Oracle:
+    def __init__(self, lib_path):
+        lib = ctypes.CDLL(str(lib_path))
+        lib.w4a16_oracle_half_to_float.argtypes = [ctypes.c_uint16]
+        lib.w4a16_oracle_half_to_float.restype = ctypes.c_float
+        lib.w4a16_oracle_float_to_half.argtypes = [ctypes.c_float]
+        lib.w4a16_oracle_float_to_half.restype = ctypes.c_uint16
+        lib.w4a16_oracle_double_to_half.argtypes = [ctypes.c_double]
+        lib.w4a16_oracle_double_to_half.restype = ctypes.c_uint16
+        lib.w4a16_oracle_unpack_qweight.argtypes = [_i32p, _u8p, ctypes.c_int, ctypes.c_int]
+        lib.w4a16_oracle_unpack_qweight.restype = None
+        lib.w4a16_oracle_unpack_qzeros.argtypes = [_i32p, _u8p, ctypes.c_int, ctypes.c_int]
+        lib.w4a16_oracle_unpack_qzeros.restype = None
+        lib.w4a16_oracle_pack_qweight.argtypes = [_u8p, _i32p, ctypes.c_int, ctypes.c_int]
+        lib.w4a16_oracle_pack_qweight.restype = None
+        lib.w4a16_oracle_pack_qzeros.argtypes = [_u8p, _i32p, ctypes.c_int, ctypes.c_int]
+        lib.w4a16_oracle_pack_qzeros.restype = None
+        lib.w4a16_oracle_dequant.argtypes = [_i32p, _u16p, _i32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.w4a16_oracle_dequant.restype = None
+        lib.w4a16_oracle_gemm.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 8
+        lib.w4a16_oracle_gemm.restype = ctypes.c_int
+        self.lib = lib
+
+    # ---- fp16 conversions (round to nearest even; the paper does not name a mode)
+    def half_to_float(self, bits: int) -> float:
+        return float(self.lib.w4a16_oracle_half_to_float(int(bits)))
+
+    def float_to_half(self, x) -> int:
+        return int(self.lib.w4a16_oracle_float_to_half(float(np.float32(x))))
+
+    def double_to_half(self, x) -> int:
+        return int(self.lib.w4a16_oracle_double_to_half(float(x)))
+
+    # ---- pack / unpack (paper Section 2: packed int32 weights, bitwise unpacking)
+    def unpack_qweight(self, qweight: np.ndarray) -> np.ndarray:
+        """int32 [k/8, n] -> uint8 [k, n]."""
+        qweight = _c(qweight, np.int32)
+        r, n = qweight.shape
+        q = np.empty((r * 8, n), np.uint8)
+        self.lib.w4a16_oracle_unpack_qweight(_ptr(qweight, ctypes.c_int32), _ptr(q, ctypes.c_uint8), n, r * 8)
+        return q
+
+    def unpack_qzeros(self, qzeros: np.ndarray) -> np.ndarray:
+        """int32 [groups, n/8] -> uint8 [groups, n]."""
+        qzeros = _c(qzeros, np.int32)
+        g, c = qzeros.shape
+        z = np.empty((g, c * 8), np.uint8)
+        self.lib.w4a16_oracle_unpack_qzeros(_ptr(qzeros, ctypes.c_int32), _ptr(z, ctypes.c_uint8), c * 8, g)
+        return z
+
+    def pack_qweight(self, q: np.ndarray) -> np.ndarray:
+        q = _c(q, np.uint8)
+        k, n = q.shape
+        assert k % 8 == 0
+        out = np.empty((k // 8, n), np.int32)
+        self.lib.w4a16_oracle_pack_qweight(_ptr(q, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, k)
+        return out
+
+    def pack_qzeros(self, z: np.ndarray) -> np.ndarray:
+        z = _c(z, np.uint8)
+        g, n = z.shape
+        assert n % 8 == 0
+        out = np.empty((g, n // 8), np.int32)
+        self.lib.w4a16_oracle_pack_qzeros(_ptr(z, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, g)
+        return out
+
+    # ---- dequantisation (paper Section 2: scale and shift)
+    def dequant(self, qweight, scales, qzeros, group_size: int) -> np.ndarray:
+        """fp32 W [k, n] with W = (q - z) * s, exact."""
+        qweight = _c(qweight, np.int32)
+        scales = _c(scales, np.float16)
+        qzeros = _c(qzeros, np.int32)
+        r, n = qweight.shape
+        k = r * 8
+        if scales.shape != (k // group_size, n) or qzeros.shape != (k // group_size, n // 8):
+            raise OracleError("scales / qzeros shapes do not match k, n, group_size")
+        W = np.empty((k, n), np.float32)
+        self.lib.w4a16_oracle_dequant(_ptr(qweight, ctypes.c_int32), _ptr(scales.view(np.uint16), ctypes.c_uint16),
+                                      _ptr(qzeros, ctypes.c_int32), _ptr(W, ctypes.c_float), n, k, group_size)
+        return W
+
+    # ---- the product (paper Algorithm 1; Section 3 first paragraph for the DP variant)
+    def gemm(self, A, qweight, scales, qzeros, group_size: int, split_k: int = 1, block_k: int = 0,
+             acc: str = "f64", threads: int = 0, return_threads: bool = False):
+        """Cref (float64 [m, n]) and its fp16 rounding C16 (float16 [m, n]).
+
+        acc = "f64": fp64 accumulators (the definition); "f32": Algorithm 1's fp32 accumulator.
+        split_k partial sums: contiguous chunks of k (block_k = 0) or Algorithm 1's strided
+        walk over k-blocks of block_k.
+        """
+        A = _c(A, np.float16)
+        qweight = _c(qweight, np.int32)
+        scales = _c(scales, np.float16)
+        qzeros = _c(qzeros, np.int32)
+        m, k = A.shape
+        r, n = qweight.shape
+        if r * 8 != k:
+            raise OracleError("qweight rows must be k / 8")
+        if group_size <= 0 or k % group_size or scales.shape != (k // group_size, n) \
+                or qzeros.shape != (k // group_size, n // 8):
+            raise OracleError("scales / qzeros shapes do not match k, n, group_size")
+        Cref = np.empty((m, n), np.float64)
+        C16 = np.empty((m, n), np.float16)
+        rc = self.lib.w4a16_oracle_gemm(
+            _ptr(A.view(np.uint16), ctypes.c_uint16), _ptr(qweight, ctypes.c_int32),
+            _ptr(scales.view(np.uint16), ctypes.c_uint16), _ptr(qzeros, ctypes.c_int32),
+            _ptr(Cref, ctypes.c_double), _ptr(C16.view(np.uint16), ctypes.c_uint16),
+            m, n, k, group_size, split_k, block_k, {"f64": 0, "f32": 1}[acc], threads)
+        if rc < 0:
+            raise OracleError(f"w4a16_oracle_gemm rejected its arguments (code {rc})")
+        if return_threads:
+            return Cref, C16, rc
+        return Cref, C16
+
+
+_default = None
+
+
+def default() -> Oracle:
+    """The oracle built from the committed source, compiled on demand."""
+    global _default
+    if _default is None:
+        src = _HERE / "w4a16_oracle.c"
+        if not _LIB_PATH.exists() or _LIB_PATH.stat().st_mtime < src.stat().st_mtime:
+            from . import build as _build
+            _build.build()
+        _default = Oracle(_LIB_PATH)
+    return _default
+
+
+def half_to_float(bits):
+    return default().half_to_float(bits)
+
+
+def float_to_half(x):
+    return default().float_to_half(x)
+
+
+def double_to_half(x):
+    return default().double_to_half(x)
+
+
+def unpack_qweight(qweight):
+    return default().unpack_qweight(qweight)
+
+
+def unpack_qzeros(qzeros):
+    return default().unpack_qzeros(qzeros)
+
+
+def pack_qweight(q):
+    return default().pack_qweight(q)
+
+
+def pack_qzeros(z):
+    return default().pack_qzeros(z)
+
+
+def dequant(qweight, scales, qzeros, group_size):
+    return default().dequant(qweight, scales, qzeros, group_size)
+
+
+def gemm(A, qweight, scales, qzeros, group_size, **kw):
+    return default().gemm(A, qweight, scales, qzeros, group_size, **kw)

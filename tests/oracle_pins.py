@@ -1,0 +1,316 @@
+"""Pins of the CPU oracle: every check compares the oracle with something that is not the
+oracle (numpy's float16 and matmul, exact rational arithmetic, closed forms, hand-written
+digits).  Each pin is a function of an `Oracle` binding so the mutation tests can run the
+same pins against deliberately broken builds of the C source.
+"""
+from __future__ import annotations
+
+import pathlib
+from fractions import Fraction
+
+import numpy as np
+
+GOLDEN = pathlib.Path(__file__).resolve().parent / "golden"
+
+
+# --------------------------------------------------------------------------- helpers
+def np_unpack_qweight(qweight: np.ndarray) -> np.ndarray:
+    """numpy restatement used as a second, independently written unpacker:
+    view each word as 4 little-endian bytes, low nibble first."""
+    r, n = qweight.shape
+    by = np.ascontiguousarray(qweight).view(np.uint8).reshape(r, n, 4)      # byte b = bits 8b..8b+7
+    nib = np.stack([by & 0xF, by >> 4], axis=-1).reshape(r, n, 8)           # field 2b, 2b+1
+    return np.ascontiguousarray(nib.transpose(0, 2, 1)).reshape(r * 8, n)
+
+
+def np_unpack_qzeros(qzeros: np.ndarray) -> np.ndarray:
+    g, c = qzeros.shape
+    by = np.ascontiguousarray(qzeros).view(np.uint8).reshape(g, c, 4)
+    nib = np.stack([by & 0xF, by >> 4], axis=-1).reshape(g, c * 8)
+    return nib
+
+
+def np_dense_weight(qweight, scales, qzeros, group_size) -> np.ndarray:
+    """float64 W [k, n] from the numpy unpackers."""
+    q = np_unpack_qweight(qweight).astype(np.int64)
+    z = np.repeat(np_unpack_qzeros(qzeros).astype(np.int64), group_size, axis=0)
+    s = np.repeat(scales.astype(np.float64), group_size, axis=0)
+    return (q - z) * s
+
+
+def random_case(m, n, k, g, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    qw = rng.integers(0, 1 << 32, size=(k // 8, n), dtype=np.uint32).view(np.int32)
+    s = rng.uniform(0.001, 0.01, size=(k // g, n)).astype(np.float16)
+    qz = rng.integers(0, 1 << 32, size=(k // g, n // 8), dtype=np.uint32).view(np.int32)
+    return A, qw, s, qz
+
+
+# --------------------------------------------------------------------------- fp16 conversions
+def pin_half_to_float_exhaustive(o):
+    """All 65536 fp16 bit patterns against numpy's float16 -> float32."""
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float32)
+    got = np.array([o.half_to_float(int(b)) for b in bits], dtype=np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+def pin_double_to_half_rounding(o):
+    """Round-to-nearest-even from fp64 in one rounding, against numpy's float64 -> float16:
+    every representable half, every midpoint between neighbours, the neighbours of the
+    midpoints, overflow, subnormals and random doubles."""
+    halves = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    mids = (halves[:-1] + halves[1:]) / 2
+    pts = np.concatenate([halves, mids, np.nextafter(mids, np.inf), np.nextafter(mids, -np.inf),
+                          [65504.0, 65519.9, 65520.0, 65520.1, 1e9, 2.0 ** -25, 2.0 ** -24 * 0.5000001,
+                           2.0 ** -26, 1e-300, 0.0]])
+    rng = np.random.Generator(np.random.Philox(7))
+    pts = np.concatenate([pts, rng.standard_normal(4000) * 10.0 ** rng.integers(-8, 5, 4000)])
+    pts = np.concatenate([pts, -pts])
+    with np.errstate(over="ignore"):
+        ref = pts.astype(np.float16).view(np.uint16)
+    got = np.array([o.double_to_half(float(x)) for x in pts], dtype=np.uint16)
+    bad = np.nonzero(got != ref)[0]
+    assert bad.size == 0, (pts[bad[:5]], got[bad[:5]], ref[bad[:5]])
+    # float32 entry point
+    f = pts.astype(np.float32)
+    with np.errstate(over="ignore"):
+        ref32 = f.astype(np.float16).view(np.uint16)
+    got32 = np.array([o.float_to_half(x) for x in f[:3000]], dtype=np.uint16)
+    assert np.array_equal(got32, ref32[:3000])
+
+
+# --------------------------------------------------------------------------- pack / unpack
+def pin_unpack_known_words(o):
+    """Hand-written words whose fields are read off their hex digits."""
+    words = np.array([[0x76543210, 0x89ABCDEF - (1 << 32), 0, -1]], dtype=np.int64).astype(np.int32)
+    q = o.unpack_qweight(words)             # [8, 4]
+    assert q[:, 0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert q[:, 1].tolist() == [15, 14, 13, 12, 11, 10, 9, 8]
+    assert q[:, 2].tolist() == [0] * 8 and q[:, 3].tolist() == [15] * 8
+    z = o.unpack_qzeros(words)              # [1, 32]
+    assert z[0, :8].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert z[0, 8:16].tolist() == [15, 14, 13, 12, 11, 10, 9, 8]
+    assert z[0, 24:].tolist() == [15] * 8
+
+
+def pin_pack_unpack_bijection(o):
+    rng = np.random.Generator(np.random.Philox(11))
+    q = rng.integers(0, 16, size=(64, 40), dtype=np.uint8)
+    assert np.array_equal(o.unpack_qweight(o.pack_qweight(q)), q)
+    words = rng.integers(0, 1 << 32, size=(8, 40), dtype=np.uint32).view(np.int32)
+    assert (words < 0).any()
+    assert np.array_equal(o.pack_qweight(o.unpack_qweight(words)), words)
+    z = rng.integers(0, 16, size=(5, 48), dtype=np.uint8)
+    assert np.array_equal(o.unpack_qzeros(o.pack_qzeros(z)), z)
+    zw = rng.integers(0, 1 << 32, size=(5, 6), dtype=np.uint32).view(np.int32)
+    assert np.array_equal(o.pack_qzeros(o.unpack_qzeros(zw)), zw)
+    # against the byte-view numpy unpackers (written differently: bytes and nibbles, no shifts by 4*i)
+    assert np.array_equal(o.unpack_qweight(words), np_unpack_qweight(words))
+    assert np.array_equal(o.unpack_qzeros(zw), np_unpack_qzeros(zw))
+
+
+# --------------------------------------------------------------------------- tiny brute force
+def load_tiny_fixture():
+    sections, cur = {}, None
+    for line in (GOLDEN / "tiny_m2_n16_k16_g8.txt").read_text().splitlines():
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("["):
+            cur = line[1:line.index("]")]
+            sections[cur] = []
+        else:
+            sections[cur].append(line)
+    q = [[int(c, 16) for c in row] for row in sections["q"]]
+    z = [[int(c, 16) for c in row] for row in sections["z"]]
+    se = [[int(t) for t in row.split()] for row in sections["scale_exponent"]]
+    A = [[int(t) for t in row.split()] for row in sections["A"]]
+    qweight = [[int(t, 16) for t in row.split()] for row in sections["qweight"]]
+    qzeros = [[int(t, 16) for t in row.split()] for row in sections["qzeros"]]
+    return q, z, se, A, qweight, qzeros
+
+
+def pin_tiny_exact_rationals(o):
+    """m=2, n=k=16, g=8: packed words go to the oracle, the unpacked digits go to an exact
+    rational expansion of every dot product.  All values are dyadic and small, so the fp32
+    and fp64 oracles must both be exactly equal to the rational result."""
+    q, z, se, A, qweight, qzeros = load_tiny_fixture()
+    m, k, n, g = 2, 16, 16, 8
+    expect = [[sum(Fraction(A[i][kk]) * (q[kk][j] - z[kk // g][j]) * Fraction(2) ** se[kk // g][j]
+                   for kk in range(k)) for j in range(n)] for i in range(m)]
+    A_np = np.array(A, dtype=np.float16)
+    s_np = np.array([[2.0 ** e for e in row] for row in se], dtype=np.float16)
+    qw_np = np.array(qweight, dtype=np.uint32).view(np.int32)
+    qz_np = np.array(qzeros, dtype=np.uint32).view(np.int32)
+    assert np.array_equal(o.unpack_qweight(qw_np), np.array(q, dtype=np.uint8))
+    assert np.array_equal(o.unpack_qzeros(qz_np), np.array(z, dtype=np.uint8))
+    for acc in ("f64", "f32"):
+        for split_k, block_k in ((1, 0), (2, 0), (2, 4)):
+            Cref, C16 = o.gemm(A_np, qw_np, s_np, qz_np, g, split_k=split_k, block_k=block_k, acc=acc)
+            for i in range(m):
+                for j in range(n):
+                    assert Fraction(float(Cref[i, j])) == expect[i][j], (acc, split_k, i, j)
+                    assert Fraction(float(C16[i, j])) == expect[i][j]   # exactly representable in fp16 too
+    W = o.dequant(qw_np, s_np, qz_np, g)
+    for kk in range(k):
+        for j in range(n):
+            assert Fraction(float(W[kk, j])) == (q[kk][j] - z[kk // g][j]) * Fraction(2) ** se[kk // g][j]
+
+
+def pin_random_tiny_vs_fractions(o):
+    """Random tiny case against exact rationals built from the numpy byte-view unpackers."""
+    m, n, k, g = 2, 16, 16, 8
+    A, qw, s, qz = random_case(m, n, k, g, seed=3)
+    q = np_unpack_qweight(qw)
+    z = np_unpack_qzeros(qz)
+    Cref, _ = o.gemm(A, qw, s, qz, g)
+    for i in range(m):
+        for j in range(n):
+            ex = sum(Fraction(float(A[i, kk])) * (int(q[kk, j]) - int(z[kk // g, j])) * Fraction(float(s[kk // g, j]))
+                     for kk in range(k))
+            assert abs(Fraction(float(Cref[i, j])) - ex) <= abs(ex) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+
+
+# --------------------------------------------------------------------------- closed forms
+def pin_closed_forms(o):
+    m, n, k, g = 3, 64, 256, 128
+    rng = np.random.Generator(np.random.Philox(5))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    s_col = rng.uniform(0.001, 0.01, size=n).astype(np.float16)
+    scales = np.tile(s_col, (k // g, 1))
+    rowsum = A.astype(np.float64).sum(axis=1)
+    for q0, z0 in ((11, 4), (2, 9), (15, 0)):
+        qw = np.full((k // 8, n), (q0 * 0x11111111) & 0xFFFFFFFF, dtype=np.uint32).view(np.int32)
+        qz = np.full((k // g, n // 8), (z0 * 0x11111111) & 0xFFFFFFFF, dtype=np.uint32).view(np.int32)
+        Cref, _ = o.gemm(A, qw, scales, qz, g)
+        expect = (q0 - z0) * s_col.astype(np.float64)[None, :] * rowsum[:, None]
+        bound = 1e-12 * np.abs(A.astype(np.float64)).sum(axis=1)[:, None] * 15 * 0.01 + 1e-300
+        assert np.all(np.abs(Cref - expect) <= bound)
+    # q == z everywhere  =>  exactly zero, also in fp32 mode
+    words = rng.integers(0, 1 << 32, size=(k // g, n // 8), dtype=np.uint32)
+    zfields = np_unpack_qzeros(words.view(np.int32))                      # [k/g, n]
+    qfields = np.repeat(zfields, g, axis=0).astype(np.uint8)              # q[kk][j] = z[kk/g][j]
+    qw = o.pack_qweight(qfields)
+    for acc in ("f64", "f32"):
+        Cref, C16 = o.gemm(A, qw, scales, words.view(np.int32), g, acc=acc)
+        assert not Cref.any() and not C16.view(np.uint16).any()
+    # A == 0  =>  exactly zero
+    A0 = np.zeros_like(A)
+    _, qw_r, s_r, qz_r = random_case(m, n, k, g, seed=6)
+    Cref, C16 = o.gemm(A0, qw_r, s_r, qz_r, g)
+    assert not Cref.any()
+
+
+def pin_matmul_library(o):
+    """Reduction to numpy's float64 matmul over the numpy-unpacked dense weight, with the
+    classical forward error bound; fp32 mode within k * 2^-24 * sum|a||w|."""
+    for (m, n, k, g, seed) in ((5, 96, 512, 128, 1), (16, 64, 1024, 64, 2), (1, 200, 384, 128, 3)):
+        A, qw, s, qz = random_case(m, n, k, g, seed)
+        W = np_dense_weight(qw, s, qz, g)
+        ref = A.astype(np.float64) @ W
+        absdot = np.abs(A.astype(np.float64)) @ np.abs(W)
+        Wo = o.dequant(qw, s, qz, g)
+        assert np.array_equal(Wo.astype(np.float64), W)
+        C64, C16 = o.gemm(A, qw, s, qz, g)
+        assert np.all(np.abs(C64 - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+        C32, _ = o.gemm(A, qw, s, qz, g, acc="f32")
+        assert np.all(np.abs(C32 - ref) <= k * 2.0 ** -24 * absdot + 1e-300)
+        assert np.array_equal(C16.view(np.uint16), C64.astype(np.float16).view(np.uint16))
+        for split_k, block_k in ((2, 0), (4, 0), (4, 32), (3, 64)):
+            if block_k == 0 and k % split_k:
+                continue
+            Cs, _ = o.gemm(A, qw, s, qz, g, split_k=split_k, block_k=block_k)
+            assert np.all(np.abs(Cs - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+            Cs32, _ = o.gemm(A, qw, s, qz, g, split_k=split_k, block_k=block_k, acc="f32")
+            assert np.all(np.abs(Cs32 - ref) <= k * 2.0 ** -24 * absdot + 1e-300)
+
+
+def pin_one_hot_rows(o):
+    """A row equal to a unit vector e_r selects row r of W: a single term, so the result is
+    exact in every mode and the fp16 output is the single rounding of w[r, :]."""
+    m, n, k, g = 16, 72, 512, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=9)
+    W = np_dense_weight(qw, s, qz, g)
+    rows = [0, 1, 7, 8, 9, 127, 128, 129, 255, 256, 300, 383, 384, 500, 510, 511]
+    A = np.zeros((m, k), np.float16)
+    for i, r in enumerate(rows):
+        A[i, r] = 1.0
+    for kw in (dict(), dict(acc="f32"), dict(split_k=4), dict(split_k=4, block_k=32, acc="f32")):
+        Cref, C16 = o.gemm(A, qw, s, qz, g, **kw)
+        assert np.array_equal(Cref, W[rows, :])
+        assert np.array_equal(C16.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16))
+
+
+def pin_group_boundary(o):
+    """Scale 1 in one group and 0 elsewhere leaves exactly that group's partial sum."""
+    m, n, k, g = 2, 32, 512, 128
+    A, qw, _, qz = random_case(m, n, k, g, seed=4)
+    q = np_unpack_qweight(qw).astype(np.int64)
+    z = np_unpack_qzeros(qz).astype(np.int64)
+    for gstar in range(k // g):
+        s = np.zeros((k // g, n), np.float16)
+        s[gstar] = 1.0
+        sl = slice(g * gstar, g * (gstar + 1))
+        expect = A[:, sl].astype(np.float64) @ (q[sl] - z[gstar][None, :]).astype(np.float64)
+        Cref, _ = o.gemm(A, qw, s, qz, g)
+        assert np.all(np.abs(Cref - expect) <= 1e-12 * np.abs(expect) + 1e-9)
+
+
+def pin_linearity_and_permutation(o):
+    m, n, k, g = 4, 64, 256, 128
+    A, qw, s, qz = random_case(m, n, k, g, seed=8)
+    C1, _ = o.gemm(A, qw, s, qz, g, acc="f32")
+    C2, _ = o.gemm(A, qw, (s.astype(np.float32) * 2).astype(np.float16), qz, g, acc="f32")
+    assert np.array_equal(C2, 2 * C1)                    # doubling scales is exact in binary
+    perm = np.random.Generator(np.random.Philox(1)).permutation(n // 8)
+    cols = (perm[:, None] * 8 + np.arange(8)[None, :]).reshape(-1)
+    Cp, _ = o.gemm(A, qw[:, cols], s[:, cols], qz[:, perm], g, acc="f32")
+    assert np.array_equal(Cp, C1[:, cols])
+    # row permutation of A permutes rows of C
+    Cr, _ = o.gemm(A[::-1], qw, s, qz, g, acc="f32")
+    assert np.array_equal(Cr, C1[::-1])
+
+
+def pin_splitk_invariance(o):
+    """All partitions of k give the same sum up to reassociation."""
+    m, n, k, g = 16, 128, 2048, 128
+    A, qw, s, qz = random_case(m, n, k, g, seed=12)
+    C1, _ = o.gemm(A, qw, s, qz, g)
+    scale = np.abs(C1).max()
+    for split_k, block_k in ((2, 0), (8, 0), (16, 0), (4, 32), (8, 64)):
+        Cs, _ = o.gemm(A, qw, s, qz, g, split_k=split_k, block_k=block_k)
+        assert np.abs(Cs - C1).max() <= 1e-13 * scale
+        Cs32, _ = o.gemm(A, qw, s, qz, g, split_k=split_k, block_k=block_k, acc="f32")
+        assert np.abs(Cs32 - C1).max() <= 1e-5 * scale
+
+
+def pin_distribution(o):
+    """Output statistics of the synthetic workload: Var(C) = k * Var(q - z) * E[s^2] * E[a^2]
+    with Var(q - z) = 2 * (16^2 - 1) / 12 = 42.5 and E[s^2] = (a^2 + ab + b^2) / 3."""
+    from paper_2402_00025_amd.inputs import make_inputs
+    x = make_inputs(16, 1024, 1024, 128, seed=0)
+    Cref, _ = o.gemm(x.A, x.qweight, x.scales, x.qzeros, 128)
+    es2 = (0.001 ** 2 + 0.001 * 0.01 + 0.01 ** 2) / 3
+    sigma = (1024 * 42.5 * es2) ** 0.5
+    assert abs(Cref.std() / sigma - 1) < 0.05
+    assert abs(Cref.mean()) < 0.05 * sigma
+
+
+ALL_PINS = [
+    pin_half_to_float_exhaustive,
+    pin_double_to_half_rounding,
+    pin_unpack_known_words,
+    pin_pack_unpack_bijection,
+    pin_tiny_exact_rationals,
+    pin_random_tiny_vs_fractions,
+    pin_closed_forms,
+    pin_matmul_library,
+    pin_one_hot_rows,
+    pin_group_boundary,
+    pin_linearity_and_permutation,
+    pin_splitk_invariance,
+    pin_distribution,
+]

@@ -1,0 +1,68 @@
+"""Do the pins notice a wrong oracle?  Each case plants one plausible mistake in a COPY of
+the oracle's C source (text substitution), compiles the copy on the CPU and demands that at
+least one pin fails on it.  The committed oracle itself is never modified.
+"""
+import pathlib
+import subprocess
+
+import pytest
+
+import oracle_pins
+from oracle.w4a16_oracle import Oracle
+
+SRC = pathlib.Path(__file__).resolve().parent.parent / "oracle" / "w4a16_oracle.c"
+
+# (name, text to find, replacement, which occurrence: index or "all")
+MUTATIONS = [
+    ("qweight_field_order_in_gemm",
+     "int q = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);\n                int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
+     "int q = field_of(qweight, (size_t)(kk / 8) * n + j, 7 - kk % 8);\n                int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow", 0),
+    ("qzeros_field_order_in_gemm", "j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
+     "j / 8, 7 - j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow", 0),
+    ("zero_point_plus_one", "wrow[jj] = (float)(q - z) * s;", "wrow[jj] = (float)(q - z - 1) * s;", 0),
+    ("sign_flipped", "wrow[jj] = (float)(q - z) * s;", "wrow[jj] = (float)(z - q) * s;", 0),
+    ("group_boundary_off_by_one", "const int gi = kk / group_size;\n            const int p",
+     "const int gi = (kk == k - 1 ? kk : kk + 1) / group_size;\n            const int p", 0),
+    ("A_transposed", "A[(size_t)i * k + kk]", "A[(size_t)kk * m + i]", 0),
+    ("last_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n            const int gi",
+     "for (int kk = 0; kk < k - 1; ++kk) {\n            const int gi", 0),
+    ("first_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n            const int gi",
+     "for (int kk = 1; kk < k; ++kk) {\n            const int gi", 0),
+    ("last_partial_sum_dropped_f64", "for (int p = 0; p < split_k; ++p) t += part64",
+     "for (int p = 0; p < split_k - (split_k > 1); ++p) t += part64", 0),
+    ("last_partial_sum_dropped_f32", "for (int p = 0; p < split_k; ++p) t += part32",
+     "for (int p = 0; p < split_k - (split_k > 1); ++p) t += part32", 0),
+    ("scale_column_swapped", "float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
+     "float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + (j ^ 1)]);\n                wrow", 0),
+    ("ties_away_from_zero", "(rem == halfway && (q & 1))", "(rem == halfway)", 0),
+    ("truncating_conversion", "if (rem > halfway || (rem == halfway && (q & 1))) ++q;", "", 0),
+    ("subnormal_exponent", "127 - 15 + 1 - shift", "127 - 15 - shift", 0),
+    ("unpack_qweight_field_order", "q[(size_t)kk * n + j] = (uint8_t)((word >> (4 * (kk % 8))) & 0xFu);",
+     "q[(size_t)kk * n + j] = (uint8_t)((word >> (4 * (7 - kk % 8))) & 0xFu);", 0),
+    ("unpack_qzeros_field_order", "z[(size_t)gi * n + j] = (uint8_t)((word >> (4 * (j % 8))) & 0xFu);",
+     "z[(size_t)gi * n + j] = (uint8_t)((word >> (4 * (7 - j % 8))) & 0xFu);", 0),
+    ("pack_qweight_field_order", "word |= (uint32_t)(q[(size_t)(8 * r + i) * n + j] & 0xFu) << (4 * i);",
+     "word |= (uint32_t)(q[(size_t)(8 * r + i) * n + j] & 0xFu) << (4 * (7 - i));", 0),
+    ("dequant_drops_zero_point", "W[(size_t)kk * n + j] = (float)(q - z) * s;", "W[(size_t)kk * n + j] = (float)(q) * s;", 0),
+]
+
+
+@pytest.mark.parametrize("name,old,new,_which", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_pins_catch_planted_mistake(tmp_path, name, old, new, _which):
+    text = SRC.read_text()
+    assert text.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle source"
+    mutated = text.replace(old, new, 1)
+    c = tmp_path / f"{name}.c"
+    so = tmp_path / f"lib{name}.so"
+    c.write_text(mutated)
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+                    "-o", str(so), str(c)], check=True)
+    bad = Oracle(so)
+    failed = []
+    for pin in oracle_pins.ALL_PINS:
+        try:
+            pin(bad)
+        except AssertionError:
+            failed.append(pin.__name__)
+            break
+    assert failed, f"no pin noticed the planted mistake '{name}'"
