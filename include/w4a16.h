@@ -1,0 +1,118 @@
+/*
+ * w4a16.h - C ABI of the fused W4A16 skinny GEMM for AMD MI355X (gfx950).
+ *
+ * Operation (paper "Accelerating a Triton Fused Kernel for W4A16 Quantized Inference with
+ * SplitK work decomposition", Section 2 first paragraph and Algorithm 1):
+ *
+ *     C[m, n] = A[m, k] . W[k, n],   W[kk, j] = (q[kk, j] - z[kk / g, j]) * s[kk / g, j]
+ *
+ * with q and z stored as 4-bit fields, eight per int32 word.  Dequantisation, the product and
+ * the reduction of the split-k partial sums happen inside one kernel launch.
+ *
+ * Buffers (all DEVICE pointers, row-major, contiguous, 16-byte aligned, owned by the caller;
+ * the library neither frees nor keeps them after the call's work has run):
+ *     A        fp16   [m, k]             activations
+ *     qweight  int32  [k / 8, n]         field i (bits 4i..4i+3) of word (r, j) is q[8r + i][j]
+ *     scales   fp16   [k / g, n]
+ *     qzeros   int32  [k / g, n / 8]     field i of word (gi, c) is z[gi][8c + i]
+ *     C        fp16   [m, n]             overwritten (never accumulated into)
+ * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls enqueue work on
+ * that stream and return without synchronising; results are valid once the stream is.
+ *
+ * Limits: 1 <= m <= 16; n a multiple of 8; g (group_size) one of 32, 64, 128, 256;
+ * k a multiple of g; for split-k, k / split_k a multiple of g.
+ *
+ * Return value: W4A16_OK or a negative W4A16_ERR_* code.  Argument checks run before any HIP
+ * call, so they behave the same on a machine without a GPU.  Nothing is printed, nothing
+ * aborts.
+ *
+ * Split-k scratch: the split-k entry points reduce partial sums with fp32 atomic adds into a
+ * library-owned per-device scratch buffer (16 * n floats plus one counter per column tile),
+ * allocated on the first call that needs it and kept zero between calls by the kernel itself.
+ * Two split-k calls that overlap in time on the same device (different streams) would share
+ * that scratch and must not be issued; calls on one stream are safe.
+ */
+#ifndef W4A16_H
+#define W4A16_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define W4A16_OK 0
+#define W4A16_ERR_NULL (-1)        /* a required pointer is NULL */
+#define W4A16_ERR_SHAPE (-2)       /* m < 1, n % 8, bad group_size, k % group_size */
+#define W4A16_ERR_SPLIT (-3)       /* split_k < 1, k % split_k, (k / split_k) % group_size */
+#define W4A16_ERR_UNSUPPORTED (-4) /* m > 16, group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
+#define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
+
+/* How split-k partial sums reach C (Section 2.1 of the paper discusses the atomic form). */
+#define W4A16_REDUCE_AUTO 0
+#define W4A16_REDUCE_ATOMIC_F32 1   /* fp32 atomic adds into scratch; last block of a tile rounds to fp16 */
+#define W4A16_REDUCE_ATOMIC_PK_F16 2 /* packed-fp16 atomic adds straight into C (C zeroed by a fill kernel) */
+#define W4A16_REDUCE_WORKSPACE 3    /* plain fp32 partial tiles in scratch; last block sums them in fixed order */
+
+/*
+ * SplitK kernel (Algorithm 1): the grid is (column tiles) x split_k; every workgroup owns one
+ * output tile and a contiguous 1/split_k share of k, and adds its partial tile to the result.
+ * split_k == 1 stores directly.  split_k == 0 lets the library choose.
+ */
+int w4a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+               int m, int n, int k, int group_size, int split_k, void* stream);
+
+/*
+ * Data-parallel tiled kernel (Section 3, first paragraph: one workgroup alone computes a whole
+ * output tile over all of k and stores it; no atomics, no scratch).  Deterministic.
+ */
+int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                  int m, int n, int k, int group_size, void* stream);
+
+/*
+ * Same operations with the tuning knobs exposed (0 = library default for each):
+ *   tile_cols  output columns per workgroup: 16, 32 or 64
+ *   waves      wavefronts per workgroup, 1..16; they divide the workgroup's k range
+ *   reduce     one of W4A16_REDUCE_* (ignored when split_k == 1)
+ * (k / split_k) must be divisible by waves * group_size.
+ */
+int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                  int m, int n, int k, int group_size, int split_k,
+                  int tile_cols, int waves, int reduce, void* stream);
+int w4a16_gemm_dp_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                     int m, int n, int k, int group_size, int tile_cols, int waves, void* stream);
+
+/*
+ * The launch the library would use: fills split_k, tile_cols, waves, reduce (any may be NULL)
+ * for a SplitK call (dp == 0) or a data-parallel call (dp != 0).  Host only; no HIP call.
+ * `split_k` in: the requested value (0 = choose).
+ */
+int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols, int* waves, int* reduce);
+
+/* Argument check alone (host only, no HIP call): what w4a16_gemm would return before launching. */
+int w4a16_check(int m, int n, int k, int group_size, int split_k);
+
+/*
+ * Test probes that run the same device unpack / dequantise routines as the GEMM kernels.
+ *   w4a16_unpack:  q_u8 [k, n] and z_u8 [k / g, n] (device, uint8) <- the 4-bit fields
+ *   w4a16_dequant: W fp16 [k, n] (device) <- fp16_rne((q - z) * s)
+ */
+int w4a16_unpack(const void* qweight, const void* qzeros, void* q_u8, void* z_u8,
+                 int n, int k, int group_size, void* stream);
+int w4a16_dequant(const void* qweight, const void* scales, const void* qzeros, void* W,
+                  int n, int k, int group_size, void* stream);
+
+/* Bytes every call has to move at least once: qweight + scales + qzeros + A + C. */
+long long w4a16_algorithmic_bytes(int m, int n, int k, int group_size);
+
+/* Static text for a return code. */
+const char* w4a16_strerror(int code);
+
+/* After a W4A16_ERR_HIP on this host thread: which HIP call failed and HIP's text for it. */
+const char* w4a16_last_hip_error(void);
+
+/* Release the per-device scratch of the current device (synchronises the device). */
+int w4a16_release_scratch(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A16_H */

@@ -1,0 +1,126 @@
+"""The C-ABI library without a GPU: it loads, exports what include/w4a16.h declares, and its
+argument checks and launch planning behave as the header says.  No compute call is made."""
+import ctypes
+import pathlib
+import re
+
+import pytest
+
+from paper_2402_00025_amd import binding as b
+from paper_2402_00025_amd import inputs
+
+ROOT = pathlib.Path(__file__).resolve().parent.parent
+HEADER = (ROOT / "include" / "w4a16.h").read_text()
+
+
+def declared_functions():
+    body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    return sorted(set(re.findall(r"\b(w4a16_[a-z_0-9]+)\s*\(", body)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(b.EXPORTS)
+    L = b.lib()
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_error_codes_match_header():
+    for name, val in (("W4A16_OK", b.OK), ("W4A16_ERR_NULL", b.ERR_NULL), ("W4A16_ERR_SHAPE", b.ERR_SHAPE),
+                      ("W4A16_ERR_SPLIT", b.ERR_SPLIT), ("W4A16_ERR_UNSUPPORTED", b.ERR_UNSUPPORTED),
+                      ("W4A16_ERR_HIP", b.ERR_HIP), ("W4A16_REDUCE_ATOMIC_F32", b.REDUCE_ATOMIC_F32),
+                      ("W4A16_REDUCE_ATOMIC_PK_F16", b.REDUCE_ATOMIC_PK_F16), ("W4A16_REDUCE_WORKSPACE", b.REDUCE_WORKSPACE)):
+        mt = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", HEADER)
+        assert mt and int(mt.group(1)) == val, name
+    for code in range(-6, 1):
+        assert isinstance(b.strerror(code), str) and b.strerror(code)
+
+
+@pytest.mark.parametrize("args,code", [
+    ((16, 4096, 4096, 128, 4), b.OK),
+    ((1, 1024, 1024, 128, 4), b.OK),
+    ((8, 16384, 16384, 128, 32), b.OK),
+    ((16, 4096, 4096, 128, 0), b.OK),            # 0 = let the library choose
+    ((0, 4096, 4096, 128, 1), b.ERR_SHAPE),
+    ((1, 4100, 4096, 128, 1), b.ERR_SHAPE),      # n % 8
+    ((1, 4, 4096, 128, 1), b.ERR_SHAPE),
+    ((1, 4096, 4100, 128, 1), b.ERR_SHAPE),      # k % group_size
+    ((1, 4096, 4096, 100, 1), b.ERR_SHAPE),      # group_size % 8
+    ((1, 4096, 64, 128, 1), b.ERR_SHAPE),        # k < group_size
+    ((1, 4096, 4096, 128, -1), b.ERR_SPLIT),
+    ((1, 4096, 4096, 128, 3), b.ERR_SPLIT),      # k % split_k
+    ((1, 4096, 4096, 128, 64), b.ERR_SPLIT),     # (k / split_k) % group_size
+    ((17, 4096, 4096, 128, 1), b.ERR_UNSUPPORTED),
+    ((1, 4096, 4096, 96, 1), b.ERR_SHAPE),       # 4096 % 96
+    ((1, 4096, 3840, 96, 1), b.ERR_UNSUPPORTED), # a legal GPTQ shape this build does not implement
+])
+def test_check(args, code):
+    assert b.w4a16_check(*args) == code
+
+
+def test_gemm_rejects_before_touching_hip():
+    L = b.lib()
+    p = ctypes.c_void_p(4096)       # never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(4100)
+    assert L.w4a16_gemm(None, p, p, p, p, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
+    assert L.w4a16_gemm(p, p, p, p, None, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
+    assert L.w4a16_gemm(p, p, p, p, p, 1, 1020, 1024, 128, 4, None) == b.ERR_SHAPE
+    assert L.w4a16_gemm(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
+    assert L.w4a16_gemm(p, p, p, p, p, 32, 1024, 1024, 128, 4, None) == b.ERR_UNSUPPORTED
+    assert L.w4a16_gemm(p, odd, p, p, p, 1, 1024, 1024, 128, 4, None) == b.ERR_UNSUPPORTED
+    assert L.w4a16_gemm_dp(p, p, p, None, p, 1, 1024, 1024, 128, None) == b.ERR_NULL
+    assert L.w4a16_gemm_dp(p, p, p, p, p, 1, 1024, 1000, 128, None) == b.ERR_SHAPE
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 48, 0, 0, None) == b.ERR_UNSUPPORTED   # tile_cols
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 64, 3, 0, None) == b.ERR_UNSUPPORTED   # waves
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 64, 2, 9, None) == b.ERR_UNSUPPORTED   # reduce
+    assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
+    assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
+    assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL
+
+
+def test_plan_is_consistent():
+    for m in (1, 16):
+        for nk in (1024, 4096, 8192, 16384):
+            for dp in (False, True):
+                pl = b.w4a16_plan(m, nk, nk, 128, dp=dp)
+                groups = nk // 128
+                assert groups % pl["split_k"] == 0
+                assert (groups // pl["split_k"]) % pl["waves"] == 0
+                assert pl["tile_cols"] in (16, 32, 64) and 1 <= pl["waves"] <= 16
+                if dp:
+                    assert pl["split_k"] == 1
+    # a requested split is kept
+    assert b.w4a16_plan(16, 4096, 4096, 128, split_k=8)["split_k"] == 8
+    with pytest.raises(b.W4A16Error):
+        b.w4a16_plan(16, 4096, 4096, 128, split_k=8, waves=8)   # 4 groups per workgroup cannot feed 8 waves
+
+
+def test_algorithmic_bytes():
+    """The library, the input module and the figures derived from the paper's profile agree."""
+    for (m, nk, expect) in ((1, 1024, 548864), (1, 4096, 8732672), (16, 4096, 8978432), (1, 8192, 34897920),
+                            (16, 8192, 35389440), (8, 16384, 139984896)):
+        assert b.w4a16_algorithmic_bytes(m, nk, nk, 128) == expect
+        assert inputs.algorithmic_bytes(m, nk, nk, 128) == expect
+    # Paper, Nsight Compute table (m=16, n=k=4096): throughput x latency is the traffic the
+    # profiler saw; the formula must land within 5 % of it for both kernels.
+    gold = dict(line.split() for line in (ROOT / "tests/golden/paper_nsight_m16_n4096_k4096.txt").read_text().splitlines()
+                if line and not line.startswith("#"))
+    ours = b.w4a16_algorithmic_bytes(int(gold["m"]), int(gold["n"]), int(gold["k"]), 128)
+    for kind in ("splitk", "dp"):
+        seen = float(gold[f"{kind}_throughput_GBps"]) * 1e9 * float(gold[f"{kind}_latency_us"]) * 1e-6
+        assert abs(ours / seen - 1) < 0.06
+    # and the paper's grid sizes: 4x more workgroups for SplitK at split_k = 4
+    assert int(gold["splitk_grid"]) == 4 * int(gold["dp_grid"])
+
+
+def test_input_generator_shapes_and_determinism():
+    x = inputs.make_inputs(3, 64, 256, 128, seed=5)
+    y = inputs.make_inputs(3, 64, 256, 128, seed=5)
+    assert x.A.shape == (3, 256) and x.qweight.shape == (32, 64) and x.scales.shape == (2, 64) and x.qzeros.shape == (2, 8)
+    for a, c in ((x.A, y.A), (x.qweight, y.qweight), (x.scales, y.scales), (x.qzeros, y.qzeros)):
+        assert a.tobytes() == c.tobytes()
+    assert (x.qweight < 0).any()
+    assert 0.001 <= float(x.scales.min()) and float(x.scales.max()) <= 0.01
+    z = inputs.make_inputs(3, 64, 256, 128, seed=6)
+    assert z.qweight.tobytes() != x.qweight.tobytes()

@@ -1,0 +1,269 @@
+"""HIP path against the CPU oracle on a real MI355X, through the C ABI (binding = marshalling).
+
+Tolerance (stated with the workload): relative Frobenius error <= 2e-3 and per-element
+|err| <= 1e-2 * max|C_ref| against the oracle's fp64-accumulated result; unpacking and
+single-term results bit-exact.
+"""
+import numpy as np
+import pytest
+
+from gpu_util import DeviceProblem, assert_parity, dev
+from oracle_pins import np_dense_weight, random_case
+from paper_2402_00025_amd import binding as b
+from paper_2402_00025_amd.inputs import make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    b.lib()          # fail loudly if the HIP library is missing
+    yield
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ probes: bit-exact unpack
+@pytest.mark.parametrize("n,k,g", [(1024, 1024, 128), (200, 384, 128), (8, 32, 32), (72, 512, 64)])
+def test_unpack_bit_exact(oracle, n, k, g):
+    import torch
+    _, qw, _, qz = random_case(1, n, k, g, seed=21)
+    q = torch.empty((k, n), dtype=torch.uint8, device="cuda")
+    z = torch.empty((k // g, n), dtype=torch.uint8, device="cuda")
+    b.w4a16_unpack(dev(qw), dev(qz), q, z, n, k, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy(), oracle.unpack_qweight(qw))
+    assert np.array_equal(z.cpu().numpy(), oracle.unpack_qzeros(qz))
+
+
+def test_unpack_known_words(oracle):
+    import torch
+    words = np.array([[0x76543210, 0x89ABCDEF - (1 << 32), 0, -1, 0x0F0F0F0F, -0x0F0F0F10, 0x12345678, -2]],
+                     dtype=np.int64).astype(np.int32)
+    zw = np.array([[0x76543210]], dtype=np.int32)
+    q = torch.empty((8, 8), dtype=torch.uint8, device="cuda")
+    z = torch.empty((1, 8), dtype=torch.uint8, device="cuda")
+    b.w4a16_unpack(dev(words), dev(zw), q, z, 8, 8, 8)
+    torch.cuda.synchronize()
+    qh = q.cpu().numpy()
+    assert qh[:, 0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert qh[:, 1].tolist() == [15, 14, 13, 12, 11, 10, 9, 8]
+    assert np.array_equal(qh, oracle.unpack_qweight(words))
+    assert z.cpu().numpy()[0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+
+
+@pytest.mark.parametrize("n,k,g", [(256, 512, 128), (200, 384, 128), (64, 256, 32), (64, 512, 256)])
+def test_dequant_bit_exact(oracle, n, k, g):
+    """fp16((q - z) * s): one rounding of an exact product, so equal to the oracle's W rounded once."""
+    import torch
+    _, qw, s, qz = random_case(1, n, k, g, seed=22)
+    W = torch.empty((k, n), dtype=torch.float16, device="cuda")
+    b.w4a16_dequant(dev(qw), dev(s), dev(qz), W, n, k, g)
+    torch.cuda.synchronize()
+    ref = oracle.dequant(qw, s, qz, g).astype(np.float16)
+    assert np.array_equal(W.cpu().numpy().view(np.uint16), ref.view(np.uint16))
+
+
+# ------------------------------------------------------------------ configuration 1
+def test_cfg1(oracle):
+    x = make_inputs(1, 1024, 1024, 128, seed=0)
+    Cref, _ = oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, 128)
+    p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+    b.w4a16_gemm(*p.args(), 4)
+    assert_parity(p.result(), Cref, "cfg1 splitk=4")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "cfg1 dp")
+
+
+# ------------------------------------------------------------------ small shapes: tiles, ragged tail, every knob
+SMALL = [
+    # m, n, k, g, split_k, tile_cols, waves, reduce
+    (1, 200, 512, 128, 1, 64, 1, 0),
+    (2, 200, 512, 128, 2, 64, 2, 1),
+    (3, 200, 512, 128, 4, 64, 1, 1),
+    (5, 200, 1024, 128, 2, 64, 4, 3),
+    (16, 200, 1024, 128, 4, 64, 2, 2),
+    (16, 328, 1024, 128, 8, 64, 1, 1),
+    (7, 136, 512, 128, 2, 32, 2, 1),
+    (16, 136, 512, 128, 1, 32, 4, 0),
+    (4, 72, 512, 128, 4, 16, 1, 3),
+    (16, 72, 1024, 128, 2, 16, 4, 2),
+    (16, 264, 2048, 128, 1, 64, 16, 0),
+    (9, 264, 2048, 128, 2, 64, 8, 1),
+    (16, 192, 512, 32, 2, 64, 4, 1),
+    (11, 192, 512, 64, 4, 64, 2, 3),
+    (16, 192, 1024, 256, 2, 64, 2, 1),
+    (13, 192, 1024, 256, 1, 32, 4, 0),
+    (1, 8, 128, 128, 1, 16, 1, 0),
+    (16, 8, 256, 128, 2, 64, 1, 1),
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves,reduce", SMALL)
+def test_small_shapes(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
+    A, qw, s, qz = random_case(m, n, k, g, seed=100 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, reduce)
+    assert_parity(p.result(), Cref, f"splitk m={m} n={n} k={k} S={split_k}")
+    # second call into the same C: overwritten, not accumulated; scratch left clean by the first
+    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, reduce)
+    assert_parity(p.result(), Cref, "second call")
+    # data-parallel kernel on the same tile shape
+    if (k // g) % waves == 0:
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_dp_ex(*p.args(), tile_cols, waves)
+        assert_parity(p.result(), Cref, f"dp m={m} n={n} k={k}")
+
+
+# ------------------------------------------------------------------ exact cases
+@pytest.mark.parametrize("split_k,reduce", [(1, 0), (4, 1), (4, 2), (4, 3)])
+def test_one_hot_rows_bit_exact(split_k, reduce):
+    """A row equal to e_r selects row r of W: one non-zero term, every other partial sum is an
+    exact zero, so every reduction flavour must return fp16(w[r, :]) exactly.  Sweeps all k."""
+    m, n, k, g = 16, 200, 1024, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=31)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), split_k, 64, 2, reduce)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+@pytest.mark.parametrize("split_k", [1, 4])
+def test_zero_cases_exact(split_k):
+    m, n, k, g = 5, 200, 512, 128
+    A, qw, s, qz = random_case(m, n, k, g, seed=33)
+    p = DeviceProblem(np.zeros_like(A), qw, s, qz, g)
+    b.w4a16_gemm(*p.args(), split_k)
+    assert not p.result().view(np.uint16).any()            # A == 0 -> +0 everywhere
+    # q == z everywhere
+    zwords = np.random.Generator(np.random.Philox(2)).integers(0, 16, size=(k // g, n), dtype=np.uint8)
+    zcol = zwords.astype(np.uint32)
+    # a word whose eight fields all equal z[gi][j]: z * 0x11111111
+    qw_eq = np.repeat((zcol * np.uint32(0x11111111)).astype(np.uint32), g // 8, axis=0).view(np.int32)
+    qz_eq = np.zeros((k // g, n // 8), np.uint32)
+    for i in range(8):
+        qz_eq |= zcol[:, i::8] << np.uint32(4 * i)
+    p2 = DeviceProblem(A, qw_eq, s, qz_eq.view(np.int32), g)
+    b.w4a16_gemm(*p2.args(), split_k)
+    assert not p2.result().astype(np.float32).any()
+
+
+def test_constant_fields_closed_form():
+    """q = q0, z = z0 everywhere: C[i, j] = (q0 - z0) * s_j * sum_k A[i, k]."""
+    m, n, k, g = 4, 128, 1024, 128
+    rng = np.random.Generator(np.random.Philox(35))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    s_col = rng.uniform(0.001, 0.01, size=n).astype(np.float16)
+    scales = np.tile(s_col, (k // g, 1))
+    q0, z0 = 13, 6
+    qw = np.full((k // 8, n), q0 * 0x11111111, dtype=np.uint32).view(np.int32)
+    qz = np.full((k // g, n // 8), z0 * 0x11111111, dtype=np.uint32).view(np.int32)
+    expect = (q0 - z0) * s_col.astype(np.float64)[None, :] * A.astype(np.float64).sum(axis=1)[:, None]
+    for split_k in (1, 2, 8):
+        p = DeviceProblem(A, qw, scales, qz, g)
+        b.w4a16_gemm(*p.args(), split_k)
+        got = p.result().astype(np.float64)
+        assert np.abs(got - expect).max() <= 2e-3 * np.abs(expect).max() + 1e-6
+
+
+def test_deterministic_variants():
+    """The data-parallel kernel, split_k = 1 and the workspace reduction give the same bits on
+    every run; the atomic variants may differ in the last bits between runs."""
+    m, n, k, g = 16, 256, 2048, 128
+    A, qw, s, qz = random_case(m, n, k, g, seed=37)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in (lambda: b.w4a16_gemm_dp(*p.args()),
+                 lambda: b.w4a16_gemm(*p.args(), 1),
+                 lambda: b.w4a16_gemm_ex(*p.args(), 4, 64, 2, b.REDUCE_WORKSPACE)):
+        call()
+        first = p.result().copy()
+        for _ in range(3):
+            p.C.fill_(float("nan"))
+            call()
+            assert np.array_equal(p.result().view(np.uint16), first.view(np.uint16))
+
+
+def test_auto_split(oracle):
+    A, qw, s, qz = random_case(8, 512, 2048, 128, seed=39)
+    Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+    p = DeviceProblem(A, qw, s, qz, 128)
+    b.w4a16_gemm(*p.args(), 0)
+    assert_parity(p.result(), Cref, "auto split")
+
+
+def test_on_side_stream(oracle):
+    import torch
+    A, qw, s, qz = random_case(4, 256, 1024, 128, seed=41)
+    Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+    p = DeviceProblem(A, qw, s, qz, 128)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        b.w4a16_gemm(*p.args(), 4, stream=st)
+    st.synchronize()
+    assert_parity(p.result(), Cref, "side stream")
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _full(oracle, m, nk, seed=0):
+    x = make_inputs(m, nk, nk, 128, seed=seed)
+    Cref, _ = oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, 128)
+    return x, Cref, DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+
+
+def test_cfg2_split_sweep(oracle):
+    """m = 16, n = k = 4096, split_k in {1, 2, 4, 8, 16}, every reduction flavour, and DP."""
+    x, Cref, p = _full(oracle, 16, 4096)
+    for split_k in (1, 2, 4, 8, 16):
+        for reduce in (b.REDUCE_ATOMIC_F32, b.REDUCE_ATOMIC_PK_F16, b.REDUCE_WORKSPACE):
+            p.C.fill_(float("nan"))
+            b.w4a16_gemm_ex(*p.args(), split_k, 0, 0, reduce)
+            assert_parity(p.result(), Cref, f"cfg2 S={split_k} reduce={reduce}")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "cfg2 dp")
+
+
+@pytest.mark.parametrize("nk", [4096, 8192])
+def test_cfg3_m_sweep(oracle, nk):
+    """m in {1, 2, 4, 8, 16} x n = k in {4096, 8192}: SplitK (library default) and DP."""
+    x16 = make_inputs(16, nk, nk, 128, seed=0)
+    for m in (1, 2, 4, 8, 16):
+        A = np.ascontiguousarray(x16.A[:m])
+        Cref, _ = oracle.gemm(A, x16.qweight, x16.scales, x16.qzeros, 128)
+        p = DeviceProblem(A, x16.qweight, x16.scales, x16.qzeros, 128)
+        b.w4a16_gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"cfg3 splitk m={m} nk={nk}")
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_dp(*p.args())
+        assert_parity(p.result(), Cref, f"cfg3 dp m={m} nk={nk}")
+
+
+def test_cfg4_split_sweep(oracle):
+    x, Cref, p = _full(oracle, 16, 8192)
+    for split_k in (1, 2, 4, 8, 16, 32):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"cfg4 S={split_k}")
+
+
+def test_cfg5_split_sweep(oracle):
+    x, Cref, p = _full(oracle, 8, 16384)
+    for split_k in (1, 4, 16, 32):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"cfg5 S={split_k}")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "cfg5 dp")
