@@ -26,6 +26,33 @@ import numpy as np
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 ROTATE_BYTES = 512 << 20
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+
+def measured_traffic(m, n, k):
+    """HBM bytes per launch of the headline kernel from the committed rocprofv3 counter
+    summary (profiles/), or None when there is none for this shape."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_splitk_m{m}_n{n}_k{k}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def calibrate_copy(reps=6, mib=256):
+    """A plain device-to-device copy of known size, so a counter run of this program can scale
+    FETCH_SIZE / WRITE_SIZE by what they read for a known amount of traffic."""
+    import torch
+
+    src = torch.empty(mib << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    log(f"[bench] calibration: {reps} device copies of {mib} MiB (reads {mib} MiB, writes {mib} MiB each)")
 
 PAPER_CONTEXT = {
     "note": "paper figures are for a Triton kernel on NVIDIA GPUs: context only, not a target",
@@ -161,6 +188,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 256 MiB device copies (reference traffic for rocprofv3 counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; the kernel has no multi-GPU path (see DESIGN.md). Use --gpus 1.")
@@ -172,6 +201,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     binding.lib()
+    if args.calibrate_copy:
+        calibrate_copy()
     dev_name = torch.cuda.get_device_name(0)
     g = 128
     m, n, k = 16, 4096, 4096
@@ -193,7 +224,8 @@ def main():
         Cref, cpu = cpu_baseline(w)
         log(f"[bench] oracle on {cpu['cores']} host threads: {cpu['ms_per_call']:.1f} ms/call = {cpu['value']:.2f} GB/s")
 
-    head = make_call(w, "splitk", split_k=plan["split_k"])
+    head = make_call(w, "splitk", split_k=plan["split_k"], tile_cols=plan["tile_cols"], waves=plan["waves"],
+                     reduce=plan["reduce"])
     ok, rel, emax = verify(w, head, Cref)
     log(f"[bench] parity of the timed configuration: ok={ok} rel_fro={rel:.2e} max_err={emax:.2e}")
     if not ok:
@@ -254,7 +286,8 @@ def main():
         "config": {"workload": f"m={m}, n=k={n}, group_size={g}, split_k={plan['split_k']}, "
                                f"weights rotated over {len(w.sets)} sets (cold HBM)", "seed": args.seed},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k),
+                     "kernel": "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
         "cpu_baseline": cpu,
         "extra": extra,
     }

@@ -51,6 +51,9 @@ extern "C" {
 #define W4A16_REDUCE_ATOMIC_F32 1   /* fp32 atomic adds into scratch; last block of a tile rounds to fp16 */
 #define W4A16_REDUCE_ATOMIC_PK_F16 2 /* packed-fp16 atomic adds straight into C (C zeroed by a fill kernel) */
 #define W4A16_REDUCE_WORKSPACE 3    /* plain fp32 partial tiles in scratch; last block sums them in fixed order */
+#define W4A16_REDUCE_ATOMIC_FIXED 4 /* 64-bit fixed-point atomic adds that also count arrivals: one round trip,
+                                       order-independent (bit-reproducible) sum; split_k <= 64; partial sums
+                                       are clamped to +-131071 */
 
 /*
  * SplitK kernel (Algorithm 1): the grid is (column tiles) x split_k; every workgroup owns one

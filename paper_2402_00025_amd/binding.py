@@ -16,7 +16,7 @@ LIB_PATH = _HERE / "libw4a16.so"
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_SPLIT, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
-REDUCE_AUTO, REDUCE_ATOMIC_F32, REDUCE_ATOMIC_PK_F16, REDUCE_WORKSPACE = 0, 1, 2, 3
+REDUCE_AUTO, REDUCE_ATOMIC_F32, REDUCE_ATOMIC_PK_F16, REDUCE_WORKSPACE, REDUCE_ATOMIC_FIXED = 0, 1, 2, 3, 4
 
 #: every symbol include/w4a16.h declares
 EXPORTS = (

@@ -15,8 +15,11 @@
 //     packed fp16 add/fma, all exact;
 //   * the scale is applied in fp32 to the 16x16 result of a whole group, so the weight is never
 //     rounded to fp16;
-//   * the activation slice of the group is staged through wave-private LDS, permuted to the
-//     field order the unpack produces.
+//   * the activation operand is fetched straight into MFMA layout (row l%16, eight consecutive
+//     k per lane) and permuted in registers to the field order the unpack produces; LDS is used
+//     only to add up the tiles of the waves of a workgroup;
+//   * loads are issued one MFMA step (32 k) at a time into a register ring two groups deep, so
+//     a wave keeps about two groups of weights in flight while it computes.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -54,18 +57,28 @@ __device__ __forceinline__ ZeroConst zero_const(uint32_t z)
 // Field i of a packed word: bits [4i, 4i+3].
 __device__ __forceinline__ uint32_t field(uint32_t word, int i) { return (word >> (4 * i)) & 0xFu; }
 
+// fp16 1024.0 twice.  Kept in a vector register (the asm hides the constant from the
+// optimiser) so that "(word & mask) | magic" becomes one v_and_or_b32: on gfx9 a VOP3
+// instruction can take only one scalar/literal operand, and the mask already is one.
+__device__ __forceinline__ uint32_t magic_1024x2()
+{
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(v));
+    return v;
+}
+
 // The eight fields of `word` minus the zero point as fp16, in slot order
 // [f0, f4, f1, f5, f2, f6, f3, f7] (the order in which the masks deliver them).
-__device__ __forceinline__ half8_t unpack_shift(uint32_t word, ZeroConst c)
+__device__ __forceinline__ half8_t unpack_shift(uint32_t word, ZeroConst c, uint32_t magic)
 {
     const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
     const half2_t clo = __builtin_bit_cast(half2_t, c.lo);
     const half2_t chi = __builtin_bit_cast(half2_t, c.hi);
     const uint32_t w8 = word >> 8;
-    const uint32_t t0 = (word & 0x000F000Fu) | 0x64006400u;  // 1024 + {f0, f4}
-    const uint32_t t1 = (word & 0x00F000F0u) | 0x64006400u;  // 1024 + 16 {f1, f5}
-    const uint32_t t2 = (w8 & 0x000F000Fu) | 0x64006400u;    // 1024 + {f2, f6}
-    const uint32_t t3 = (w8 & 0x00F000F0u) | 0x64006400u;    // 1024 + 16 {f3, f7}
+    const uint32_t t0 = (word & 0x000F000Fu) | magic;  // 1024 + {f0, f4}
+    const uint32_t t1 = (word & 0x00F000F0u) | magic;  // 1024 + 16 {f1, f5}
+    const uint32_t t2 = (w8 & 0x000F000Fu) | magic;    // 1024 + {f2, f6}
+    const uint32_t t3 = (w8 & 0x00F000F0u) | magic;    // 1024 + 16 {f3, f7}
     const half2_t h0 = __builtin_bit_cast(half2_t, t0) + clo;
     const half2_t h1 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t1), sixteenth, chi);
     const half2_t h2 = __builtin_bit_cast(half2_t, t2) + clo;
@@ -73,6 +86,18 @@ __device__ __forceinline__ half8_t unpack_shift(uint32_t word, ZeroConst c)
     u32x4_t packed = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
                       __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
     return __builtin_bit_cast(half8_t, packed);
+}
+
+// Eight consecutive activations {a0..a7} (four registers, two per register) reordered to the
+// slot order of unpack_shift: {a0,a4}, {a1,a5}, {a2,a6}, {a3,a7}.
+__device__ __forceinline__ half8_t permute_activations(u32x4_t d)
+{
+    u32x4_t e;
+    e.x = __builtin_amdgcn_perm(d.z, d.x, 0x05040100u);
+    e.y = __builtin_amdgcn_perm(d.z, d.x, 0x07060302u);
+    e.z = __builtin_amdgcn_perm(d.w, d.y, 0x05040100u);
+    e.w = __builtin_amdgcn_perm(d.w, d.y, 0x07060302u);
+    return __builtin_bit_cast(half8_t, e);
 }
 
 // k offset (0..7) inside a packed word of the value held in slot s of unpack_shift's result.
@@ -148,38 +173,30 @@ __device__ __forceinline__ float scale_of(const ScaleBits<V>& s, int j)
 }
 
 // ------------------------------------------------------------------------------------------
-// What one lane fetches for one quantisation group of its strip: IPG x V weight words
-// (IPG = group_size / 32 MFMA steps), one qzeros word and V scales.
-template <int V, int IPG>
-struct GroupRegs {
-    Words<V> w[IPG];
+// One MFMA step (32 consecutive k) of a lane: V weight words and its 8 activations.
+template <int V>
+struct StepRegs {
+    Words<V> w;
+    u32x4_t a;
+};
+
+// Per-group parameters of a lane: one qzeros word and V scales.
+template <int V>
+struct ParamRegs {
     uint32_t zword;
     ScaleBits<V> s;
 };
 
-// The lane's share of the group's activation slice: up to IPG 16-byte pieces.
-template <int IPG>
-struct ActRegs {
-    u32x4_t a[IPG];
-};
-
 // Addressing that stays fixed for a lane during the whole kernel: 32-bit byte offsets into
 // the four tensors.  A lane whose columns lie beyond n (a strip may overhang the matrix) reads
-// the columns of lane 0 instead; its results are private to it and are never stored.
-template <int V, int IPG>
+// valid columns of the matrix instead, and a lane whose activation row is >= m reads row m-1;
+// in both cases what it computes lands in accumulator entries that are never stored.
 struct LaneMap {
-    static constexpr int CH = 4 * IPG;        // 16-byte pieces per activation row per compute group
-    static constexpr int RPP = kWave / CH;    // activation rows fetched per pass
-    static constexpr int RS = 64 * IPG + 16;  // LDS row stride in bytes (+16 spreads rows over banks)
-
-    uint32_t off_w;   // ((lane / 16) * n + col0) * 4   into qweight
-    uint32_t off_z;   // (col0 / 8) * 4                 into a qzeros row
-    uint32_t off_s;   // col0 * 2                       into a scales row
-    uint32_t off_a;   // (a_row * k + 8 * a_ch) * 2     into A
+    uint32_t off_w;   // ((lane / 16) * n + col0) * 4       into qweight
+    uint32_t off_z;   // (col0 / 8) * 4                     into a qzeros row
+    uint32_t off_s;   // col0 * 2                           into a scales row
+    uint32_t off_a;   // (row * k + 8 * (lane / 16)) * 2    into A, row = min(lane % 16, m - 1)
     int zshift;       // 4 * (col0 % 8)
-    int a_row;        // staging role: activation row of the first pass
-    int lds_wr;       // byte offset of the lane's staging store (first pass)
-    int lds_rd;       // byte offset of the lane's MFMA operand read (step 0)
 };
 
 // Scalar view of the problem.  A "compute group" is 32 * IPG consecutive k; a quantisation
@@ -191,139 +208,120 @@ struct Tensors {
 };
 
 template <int V, int IPG>
-__device__ __forceinline__ void issue_weight_loads(GroupRegs<V, IPG>& r, const LaneMap<V, IPG>& lm,
-                                                   const Tensors& t, int gi)
+__device__ __forceinline__ void issue_step(StepRegs<V>& r, const LaneMap& lm, const Tensors& t, int gi, int it)
+{
+    const uint32_t step = (uint32_t)gi * IPG + it;  // MFMA step index along k: k = 32 * step
+    r.a = __builtin_amdgcn_raw_buffer_load_b128(t.A, lm.off_a, step * 64u, 0);
+    r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
+}
+
+template <int V>
+__device__ __forceinline__ void issue_params(ParamRegs<V>& r, const LaneMap& lm, const Tensors& t, int gi)
 {
     const uint32_t gp = (uint32_t)gi >> t.param_shift;
     r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, gp * (uint32_t)(t.n / 8) * 4u, 0);
     r.s.load(t.scales, lm.off_s, gp * (uint32_t)t.n * 2u);
-#pragma unroll
-    for (int it = 0; it < IPG; ++it)
-        r.w[it].load(t.qweight, lm.off_w, ((uint32_t)gi * IPG + it) * 16u * (uint32_t)t.n);
 }
 
+// Ring of two compute groups: half h holds the IPG steps and the parameters of one group.
 template <int V, int IPG>
-__device__ __forceinline__ void issue_act_loads(ActRegs<IPG>& r, const LaneMap<V, IPG>& lm, const Tensors& t, int gi)
+struct Ring {
+    StepRegs<V> step[2][IPG];
+    ParamRegs<V> par[2];
+};
+
+template <int V, int IPG, int H>
+__device__ __forceinline__ void issue_group(Ring<V, IPG>& ring, const LaneMap& lm, const Tensors& t, int gi)
 {
-    using LM = LaneMap<V, IPG>;
+    issue_params<V>(ring.par[H], lm, t, gi);
 #pragma unroll
-    for (int p = 0; p < IPG; ++p) {
-        if (lm.a_row + p * LM::RPP < t.m)
-            r.a[p] = __builtin_amdgcn_raw_buffer_load_b128(
-                t.A, lm.off_a, ((uint32_t)gi * (32 * IPG) + (uint32_t)p * LM::RPP * (uint32_t)t.k) * 2u, 0);
-    }
+    for (int it = 0; it < IPG; ++it) issue_step<V, IPG>(ring.step[H][it], lm, t, gi, it);
 }
 
-// Write the lane's share of the group's activation slice to the wave's LDS region, each
-// 8-value piece permuted to the slot order of unpack_shift.
-template <int V, int IPG>
-__device__ __forceinline__ void stage_activations(const ActRegs<IPG>& r, const LaneMap<V, IPG>& lm, char* lds, int m)
-{
-    using LM = LaneMap<V, IPG>;
-#pragma unroll
-    for (int t = 0; t < IPG; ++t) {
-        if (lm.a_row + t * LM::RPP < m) {
-            const u32x4_t d = r.a[t];  // d.x = {a0,a1}, d.y = {a2,a3}, d.z = {a4,a5}, d.w = {a6,a7}
-            u32x4_t e;
-            e.x = (d.x & 0xFFFFu) | (d.z << 16);         // {a0, a4}
-            e.y = (d.x >> 16) | (d.z & 0xFFFF0000u);     // {a1, a5}
-            e.z = (d.y & 0xFFFFu) | (d.w << 16);         // {a2, a6}
-            e.w = (d.y >> 16) | (d.w & 0xFFFF0000u);     // {a3, a7}
-            *(u32x4_t*)(lds + lm.lds_wr + t * LM::RPP * LM::RS) = e;
-        }
-    }
-}
-
-// One quantisation group: IPG MFMA steps into a fresh 16x16 tile per column set, then
-// acc += scale * tile in fp32.
-template <int V, int IPG>
-__device__ __forceinline__ void compute_group(const GroupRegs<V, IPG>& r, const LaneMap<V, IPG>& lm,
-                                              const char* lds, float4_t (&acc)[V])
+// One compute group out of ring half H: IPG MFMA steps into a fresh 16x16 tile per column
+// set, then acc += scale * tile in fp32.  Each step's registers are refilled with the same
+// step of group `refill` (two groups ahead) as soon as they have been consumed.
+template <int V, int IPG, int H, bool REFILL>
+__device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap& lm, const Tensors& t,
+                                              uint32_t magic, int refill, float4_t (&acc)[V])
 {
     ZeroConst zc[V];
+    float sc[V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) zc[j] = zero_const((r.zword >> (lm.zshift + 4 * j)) & 0xFu);
+    for (int j = 0; j < V; ++j) {
+        zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
+        sc[j] = scale_of<V>(ring.par[H].s, j);
+    }
+    if constexpr (REFILL) {
+        // sched_barrier: keep the instruction scheduler from sinking the refill loads to the
+        // end of the loop body (it would serialise load latency and compute)
+        __builtin_amdgcn_sched_barrier(0);
+        issue_params<V>(ring.par[H], lm, t, refill);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     float4_t tile[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) tile[j] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int it = 0; it < IPG; ++it) {
-        const half8_t a8 = *(const half8_t*)(lds + lm.lds_rd + it * 64);
+        const half8_t a8 = permute_activations(ring.step[H][it].a);
+        half8_t b8[V];
 #pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const half8_t b8 = unpack_shift(r.w[it].v[j], zc[j]);
-            tile[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8, tile[j], 0, 0, 0);
+        for (int j = 0; j < V; ++j) b8[j] = unpack_shift(ring.step[H][it].w.v[j], zc[j], magic);
+        if constexpr (REFILL) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue_step<V, IPG>(ring.step[H][it], lm, t, refill, it);
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int j = 0; j < V; ++j) tile[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8[j], tile[j], 0, 0, 0);
     }
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-        const float s = scale_of<V>(r.s, j);
-        acc[j] += s * tile[j];
-    }
-}
-
-// Make LDS writes of this wave visible to the other lanes of the same wave, and keep the
-// compiler from moving LDS accesses across this point.  LDS operations of one wave execute
-// in program order, so no hardware barrier is needed.
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int j = 0; j < V; ++j) acc[j] += sc[j] * tile[j];
 }
 
 // The loop of Algorithm 1 for one wave: compute groups [g_begin, g_begin + g_count) of its
-// strip.  While group i is computed, the weight words and activations of group i+1 are in
-// flight (weights double-buffered in registers; activations single-buffered, because the
-// staging store consumes them before the next fetch is issued).
+// strip, with up to two groups of loads in flight.  The steady-state loop refills without any
+// branch, so the compiler's wait counts stay exact; the last one to three groups drain the ring.
 template <int V, int IPG>
-__device__ __forceinline__ void wave_mainloop(const Tensors& t, const LaneMap<V, IPG>& lm, char* lds, int g_begin,
-                                              int g_count, float4_t (&acc)[V])
+__device__ __forceinline__ void wave_mainloop(const Tensors& t, const LaneMap& lm, int g_begin, int g_count,
+                                              float4_t (&acc)[V])
 {
-    GroupRegs<V, IPG> r0, r1;
-    ActRegs<IPG> ar;
-    issue_weight_loads<V, IPG>(r0, lm, t, g_begin);
-    issue_act_loads<V, IPG>(ar, lm, t, g_begin);
-    for (int i = 0; i < g_count; i += 2) {
-        stage_activations<V, IPG>(ar, lm, lds, t.m);
-        const bool has1 = (i + 1 < g_count);
-        if (has1) {
-            issue_weight_loads<V, IPG>(r1, lm, t, g_begin + i + 1);
-            issue_act_loads<V, IPG>(ar, lm, t, g_begin + i + 1);
-        }
-        wave_lds_sync();
-        compute_group<V, IPG>(r0, lm, lds, acc);
-        wave_lds_sync();
-        if (!has1) break;
-        stage_activations<V, IPG>(ar, lm, lds, t.m);
-        if (i + 2 < g_count) {
-            issue_weight_loads<V, IPG>(r0, lm, t, g_begin + i + 2);
-            issue_act_loads<V, IPG>(ar, lm, t, g_begin + i + 2);
-        }
-        wave_lds_sync();
-        compute_group<V, IPG>(r1, lm, lds, acc);
-        wave_lds_sync();
+    const uint32_t magic = magic_1024x2();
+    Ring<V, IPG> ring;
+    issue_group<V, IPG, 0>(ring, lm, t, g_begin);
+    if (g_count > 1) issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+    int i = 0;
+    for (; i + 3 < g_count; i += 2) {
+        compute_group<V, IPG, 0, true>(ring, lm, t, magic, g_begin + i + 2, acc);
+        compute_group<V, IPG, 1, true>(ring, lm, t, magic, g_begin + i + 3, acc);
+    }
+    const int left = g_count - i;  // 1, 2 or 3 groups; half 0 holds group i, half 1 group i + 1
+    if (left == 3) {
+        compute_group<V, IPG, 0, true>(ring, lm, t, magic, g_begin + i + 2, acc);
+        compute_group<V, IPG, 1, false>(ring, lm, t, magic, 0, acc);
+        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
+    } else if (left == 2) {
+        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
+        compute_group<V, IPG, 1, false>(ring, lm, t, magic, 0, acc);
+    } else if (left == 1) {
+        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
     }
 }
 
-template <int V, int IPG>
-__device__ __forceinline__ LaneMap<V, IPG> make_lane_map(int lane, int n0, int m, int n, int k)
+template <int V>
+__device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n, int k)
 {
-    using LM = LaneMap<V, IPG>;
-    LM lm;
+    LaneMap lm;
     const int col0 = n0 + V * (lane & 15);
-    const int colc = col0 < n ? col0 : V * (lane & 15) % n;  // an overhanging lane reads valid columns
+    const int colc = col0 < n ? col0 : 0;  // an overhanging lane reads the first columns (n >= 8 >= V)
     lm.off_w = ((uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
     lm.off_z = (uint32_t)(colc >> 3) * 4u;
     lm.off_s = (uint32_t)colc * 2u;
     lm.zshift = 4 * (colc & 7);
-    const int a_ch = lane % LM::CH;
-    lm.a_row = lane / LM::CH;
-    lm.off_a = ((uint32_t)lm.a_row * (uint32_t)k + 8u * (uint32_t)a_ch) * 2u;
-    lm.lds_wr = lm.a_row * LM::RS + a_ch * 16;
     const int mrow = lane & 15;
-    const int arow = mrow < m ? mrow : m;  // row m of the region holds zeros
-    lm.lds_rd = arow * LM::RS + (lane >> 4) * 16;
+    const int arow = mrow < m ? mrow : m - 1;
+    lm.off_a = ((uint32_t)arow * (uint32_t)k + 8u * (uint32_t)(lane >> 4)) * 2u;
     return lm;
 }
 

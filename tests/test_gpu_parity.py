@@ -98,6 +98,10 @@ SMALL = [
     (13, 192, 1024, 256, 1, 32, 4, 0),
     (1, 8, 128, 128, 1, 16, 1, 0),
     (16, 8, 256, 128, 2, 64, 1, 1),
+    (16, 200, 1024, 128, 4, 64, 2, 4),
+    (3, 328, 1024, 128, 8, 64, 1, 4),
+    (16, 136, 512, 128, 2, 32, 2, 4),
+    (5, 72, 1024, 128, 2, 16, 4, 4),
 ]
 
 
@@ -119,7 +123,7 @@ def test_small_shapes(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
 
 
 # ------------------------------------------------------------------ exact cases
-@pytest.mark.parametrize("split_k,reduce", [(1, 0), (4, 1), (4, 2), (4, 3)])
+@pytest.mark.parametrize("split_k,reduce", [(1, 0), (4, 1), (4, 2), (4, 3), (4, 4)])
 def test_one_hot_rows_bit_exact(split_k, reduce):
     """A row equal to e_r selects row r of W: one non-zero term, every other partial sum is an
     exact zero, so every reduction flavour must return fp16(w[r, :]) exactly.  Sweeps all k."""
@@ -185,7 +189,8 @@ def test_deterministic_variants():
     p = DeviceProblem(A, qw, s, qz, g)
     for call in (lambda: b.w4a16_gemm_dp(*p.args()),
                  lambda: b.w4a16_gemm(*p.args(), 1),
-                 lambda: b.w4a16_gemm_ex(*p.args(), 4, 64, 2, b.REDUCE_WORKSPACE)):
+                 lambda: b.w4a16_gemm_ex(*p.args(), 4, 64, 2, b.REDUCE_WORKSPACE),
+                 lambda: b.w4a16_gemm_ex(*p.args(), 8, 64, 2, b.REDUCE_ATOMIC_FIXED)):
         call()
         first = p.result().copy()
         for _ in range(3):
@@ -226,7 +231,7 @@ def test_cfg2_split_sweep(oracle):
     """m = 16, n = k = 4096, split_k in {1, 2, 4, 8, 16}, every reduction flavour, and DP."""
     x, Cref, p = _full(oracle, 16, 4096)
     for split_k in (1, 2, 4, 8, 16):
-        for reduce in (b.REDUCE_ATOMIC_F32, b.REDUCE_ATOMIC_PK_F16, b.REDUCE_WORKSPACE):
+        for reduce in (b.REDUCE_ATOMIC_F32, b.REDUCE_ATOMIC_PK_F16, b.REDUCE_WORKSPACE, b.REDUCE_ATOMIC_FIXED):
             p.C.fill_(float("nan"))
             b.w4a16_gemm_ex(*p.args(), split_k, 0, 0, reduce)
             assert_parity(p.result(), Cref, f"cfg2 S={split_k} reduce={reduce}")
