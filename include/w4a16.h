@@ -19,8 +19,9 @@
  * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls enqueue work on
  * that stream and return without synchronising; results are valid once the stream is.
  *
- * Limits: 1 <= m <= 16; n a multiple of 8; g (group_size) one of 32, 64, 128, 256;
- * k a multiple of g; for split-k, k / split_k a multiple of g.
+ * Limits: m >= 1 (the paper's regime is m <= 16; larger m runs as one launch per 16 rows, each
+ * streaming the weights again); n a multiple of 8; g (group_size) one of 32, 64, 128, 256;
+ * k a multiple of g; for split-k, k / split_k a multiple of g; k * n < 2^32.
  *
  * Return value: W4A16_OK or a negative W4A16_ERR_* code.  Argument checks run before any HIP
  * call, so they behave the same on a machine without a GPU.  Nothing is printed, nothing
@@ -43,7 +44,7 @@ extern "C" {
 #define W4A16_ERR_NULL (-1)        /* a required pointer is NULL */
 #define W4A16_ERR_SHAPE (-2)       /* m < 1, n % 8, bad group_size, k % group_size */
 #define W4A16_ERR_SPLIT (-3)       /* split_k < 1, k % split_k, (k / split_k) % group_size */
-#define W4A16_ERR_UNSUPPORTED (-4) /* m > 16, group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
+#define W4A16_ERR_UNSUPPORTED (-4) /* group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
 #define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
 
 /* How split-k partial sums reach C (Section 2.1 of the paper discusses the atomic form). */

@@ -346,7 +346,6 @@ static int check_args(int m, int n, int k, int group_size, int split_k)
         return W4A16_ERR_SHAPE;
     if (split_k < 0) return W4A16_ERR_SPLIT;
     if (split_k > 0 && ((k % split_k) != 0 || ((k / split_k) % group_size) != 0)) return W4A16_ERR_SPLIT;
-    if (m > 16) return W4A16_ERR_UNSUPPORTED;
     if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
     return W4A16_OK;
 }
@@ -508,6 +507,17 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (rc != W4A16_OK) return rc;
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
+    if (m > 16) {
+        // more than one MFMA row tile: one launch per 16 rows (each streams the weights again;
+        // the paper's regime is m <= 16, larger m is served for completeness)
+        for (int r = 0; r < m; r += 16) {
+            const int mm = m - r < 16 ? m - r : 16;
+            rc = run_gemm((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros, (_Float16*)C + (size_t)r * n, mm,
+                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, stream_v);
+            if (rc != W4A16_OK) return rc;
+        }
+        return W4A16_OK;
+    }
     Plan plan;
     rc = make_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce, &plan);
     if (rc != W4A16_OK) return rc;
@@ -661,7 +671,7 @@ const char* w4a16_strerror(int code)
     case W4A16_ERR_SHAPE: return "bad shape: need m >= 1, n % 8 == 0, group_size % 8 == 0, k % group_size == 0";
     case W4A16_ERR_SPLIT: return "bad split_k: need split_k >= 0, k % split_k == 0, (k / split_k) % group_size == 0";
     case W4A16_ERR_UNSUPPORTED:
-        return "unsupported: m > 16, group_size not in {32,64,128,256}, pointer not 16-byte aligned, or bad tuning value";
+        return "unsupported: group_size not in {32,64,128,256}, pointer not 16-byte aligned, or bad tuning value";
     case W4A16_ERR_HIP: return "a HIP runtime call failed";
     default: return "unknown w4a16 error code";
     }

@@ -52,7 +52,7 @@ def test_error_codes_match_header():
     ((1, 4096, 4096, 128, -1), b.ERR_SPLIT),
     ((1, 4096, 4096, 128, 3), b.ERR_SPLIT),      # k % split_k
     ((1, 4096, 4096, 128, 64), b.ERR_SPLIT),     # (k / split_k) % group_size
-    ((17, 4096, 4096, 128, 1), b.ERR_UNSUPPORTED),
+    ((17, 4096, 4096, 128, 1), b.OK),            # rows beyond 16 run as further launches
     ((1, 4096, 4096, 96, 1), b.ERR_SHAPE),       # 4096 % 96
     ((1, 4096, 3840, 96, 1), b.ERR_UNSUPPORTED), # a legal GPTQ shape this build does not implement
 ])
@@ -68,7 +68,7 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_gemm(p, p, p, p, None, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
     assert L.w4a16_gemm(p, p, p, p, p, 1, 1020, 1024, 128, 4, None) == b.ERR_SHAPE
     assert L.w4a16_gemm(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
-    assert L.w4a16_gemm(p, p, p, p, p, 32, 1024, 1024, 128, 4, None) == b.ERR_UNSUPPORTED
+    assert L.w4a16_gemm(p, p, p, p, p, 32, 1024, 1024, 100, 4, None) == b.ERR_SHAPE
     assert L.w4a16_gemm(p, odd, p, p, p, 1, 1024, 1024, 128, 4, None) == b.ERR_UNSUPPORTED
     assert L.w4a16_gemm_dp(p, p, p, None, p, 1, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_gemm_dp(p, p, p, p, p, 1, 1024, 1000, 128, None) == b.ERR_SHAPE

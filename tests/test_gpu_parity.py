@@ -220,6 +220,18 @@ def test_on_side_stream(oracle):
     assert_parity(p.result(), Cref, "side stream")
 
 
+def test_more_than_16_rows(oracle):
+    """m = 40: three MFMA row tiles (16 + 16 + 8), SplitK and DP."""
+    A, qw, s, qz = random_case(40, 264, 1024, 128, seed=43)
+    Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+    p = DeviceProblem(A, qw, s, qz, 128)
+    b.w4a16_gemm(*p.args(), 4)
+    assert_parity(p.result(), Cref, "m=40 splitk")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "m=40 dp")
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
