@@ -100,7 +100,8 @@ class Workload:
 
 
 def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0):
-    """A closure launching call number i (weights rotate with i) through the C ABI."""
+    """A closure launching call number i (weights rotate with i) through the C ABI on torch's
+    current stream (looked up per call, so the same closure works under graph capture)."""
     import ctypes
 
     import torch
@@ -108,28 +109,33 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
     from paper_2402_00025_amd import binding
 
     L = binding.lib()
-    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     A, C = ctypes.c_void_p(w.A.data_ptr()), ctypes.c_void_p(w.C.data_ptr())
     ptrs = [tuple(ctypes.c_void_p(t.data_ptr()) for t in s) for s in w.sets]
     m, n, k, g = w.m, w.n, w.k, w.g
     nsets = len(ptrs)
+    current_stream = torch.cuda.current_stream
     if kind == "splitk":
         def call(i):
             qw, s, qz = ptrs[i % nsets]
-            rc = L.w4a16_gemm_ex(A, qw, s, qz, C, m, n, k, g, split_k, tile_cols, waves, reduce, stream)
+            rc = L.w4a16_gemm_ex(A, qw, s, qz, C, m, n, k, g, split_k, tile_cols, waves, reduce,
+                                 ctypes.c_void_p(current_stream().cuda_stream))
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_ex")
     else:
         def call(i):
             qw, s, qz = ptrs[i % nsets]
-            rc = L.w4a16_gemm_dp_ex(A, qw, s, qz, C, m, n, k, g, tile_cols, waves, stream)
+            rc = L.w4a16_gemm_dp_ex(A, qw, s, qz, C, m, n, k, g, tile_cols, waves,
+                                    ctypes.c_void_p(current_stream().cuda_stream))
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_dp_ex")
+    call.nsets = nsets
     return call
 
 
-def time_calls(call, steps, warmup):
-    """(wall seconds per call, HIP-event seconds per call) over exactly `steps` calls."""
+def time_calls_eager(call, steps, warmup):
+    """(wall seconds per call, HIP-event seconds per call) over exactly `steps` eager calls.
+    With two launches per call from Python the host enqueues about one call per 7-8 us, so
+    for small shapes this measures the host, not the GPU; see time_calls."""
     import torch
 
     for i in range(warmup):
@@ -140,6 +146,55 @@ def time_calls(call, steps, warmup):
     e0.record()
     for i in range(steps):
         call(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
+
+_GRAPH_KEEP = []  # captured graphs must outlive their replays
+
+
+def time_calls(call, steps, warmup, prewarm_s=0.03):
+    """(wall seconds per call, HIP-event seconds per call) over exactly `steps` calls.
+
+    The calls are captured once into HIP graphs (every kernel the library launches is
+    captured; nothing is skipped or cached) and replayed, which takes the Python/ctypes
+    enqueue cost out of the timed region: `chunk` consecutive calls (a whole rotation over the
+    weight sets when possible) per graph, steps // chunk replays plus a second graph for the
+    remainder.  Untimed before that: `warmup` eager calls, one replay of each graph, and
+    `prewarm_s` seconds of replays so the GPU is at its running clocks."""
+    import torch
+
+    for i in range(max(warmup, 3)):
+        call(i)
+    torch.cuda.synchronize()
+    chunk = min(steps, max(call.nsets, 64))
+    reps, rem = divmod(steps, chunk)
+    side = torch.cuda.Stream()
+    graphs = []
+    for count in ((chunk, rem) if rem else (chunk,)):
+        g = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(g, stream=side):
+            for i in range(count):
+                call(i)
+        graphs.append(g)
+    _GRAPH_KEEP.append(graphs)
+    for g in graphs:
+        g.replay()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter() + prewarm_s
+    while time.perf_counter() < t_end:
+        graphs[0].replay()
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(reps):
+        graphs[0].replay()
+    if rem:
+        graphs[1].replay()
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -232,15 +287,8 @@ def main():
         log("[bench] FAILED parity; refusing to report a number")
         sys.exit(1)
 
-    # bring the GPU out of its idle clocks before the contract's warm-up and timed steps
-    t_end = time.perf_counter() + 0.3
-    i = 0
-    while time.perf_counter() < t_end:
-        for _ in range(200):
-            head(i)
-            i += 1
-        torch.cuda.synchronize()
-    wall, ev = time_calls(head, args.steps, args.warmup)
+    wall, ev = time_calls(head, args.steps, args.warmup, prewarm_s=0.3)
+    wall_eager, ev_eager = time_calls_eager(head, min(args.steps, 400), 50)
     value = w.bytes / wall / 1e9
     achieved = w.bytes / ev / 1e9
     log(f"[bench] splitk S={plan['split_k']}: {wall * 1e6:.2f} us/call wall, {ev * 1e6:.2f} us/launch by events, "
@@ -248,7 +296,11 @@ def main():
 
     extra = {"device": dev_name, "plan": plan, "paper_context": PAPER_CONTEXT,
              "parity": {"rel_fro": rel, "max_abs_err": emax}, "weight_sets": len(w.sets),
-             "us_per_call_wall": wall * 1e6, "us_per_launch_events": ev * 1e6}
+             "us_per_call_wall": wall * 1e6, "us_per_launch_events": ev * 1e6,
+             "timing": "calls captured in HIP graphs and replayed (all kernels of every call run)",
+             "eager_us_per_call_400_steps": ev_eager * 1e6,
+             "eager_note": "eager launches from Python cost the host ~7-8 us per call (two launches), so long eager "
+                           "runs of the small shapes are host-bound"}
 
     if not args.no_sweep:
         sweep_steps, sweep_warm = 400, 50
