@@ -27,11 +27,13 @@
  * call, so they behave the same on a machine without a GPU.  Nothing is printed, nothing
  * aborts.
  *
- * Split-k scratch: the split-k entry points reduce partial sums with fp32 atomic adds into a
- * library-owned per-device scratch buffer (16 * n floats plus one counter per column tile),
- * allocated on the first call that needs it and kept zero between calls by the kernel itself.
- * Two split-k calls that overlap in time on the same device (different streams) would share
- * that scratch and must not be issued; calls on one stream are safe.
+ * Split-k scratch: depending on the reduction flavour (W4A16_REDUCE_*) the split-k entry points
+ * keep partial sums, arrival counters or per-tile flags in library-owned per-device scratch
+ * buffers (at most 16 * n 64-bit words, split_k * m * n floats for the workspace flavour, and a
+ * few words per column tile), allocated on the first call that needs them and left consistent
+ * for the next call by the kernel itself.  Two split-k calls that overlap in time on the same
+ * device (different streams) would share that scratch and must not be issued; calls on one
+ * stream are safe.
  */
 #ifndef W4A16_H
 #define W4A16_H
@@ -55,6 +57,10 @@ extern "C" {
 #define W4A16_REDUCE_ATOMIC_FIXED 4 /* 64-bit fixed-point atomic adds that also count arrivals: one round trip,
                                        order-independent (bit-reproducible) sum; split_k <= 64; partial sums
                                        are clamped to +-131071 */
+#define W4A16_REDUCE_ATOMIC_PK_F16_PHASE 5 /* packed-fp16 atomic adds straight into C with no launch before the
+                                       GEMM kernel: the first k slice's workgroup zeroes its tile of C inside
+                                       the kernel and the others wait for that through a per-tile flag;
+                                       split_k a power of two, 2..64; n <= 65536 */
 
 /*
  * SplitK kernel (Algorithm 1): the grid is (column tiles) x split_k; every workgroup owns one
@@ -112,6 +118,14 @@ const char* w4a16_strerror(int code);
 
 /* After a W4A16_ERR_HIP on this host thread: which HIP call failed and HIP's text for it. */
 const char* w4a16_last_hip_error(void);
+
+/*
+ * W4A16_REDUCE_ATOMIC_PK_F16_PHASE only: how many wavefronts on the current device have so far
+ * given up waiting for a tile's zeroing (they then add into whatever C held).  0 unless the
+ * per-tile words were corrupted, e.g. by two overlapping calls or an aborted kernel; releasing
+ * the scratch resets them.  Synchronises the device.  Negative: a W4A16_ERR_* code.
+ */
+long long w4a16_phase_timeouts(void);
 
 /* Release the per-device scratch of the current device (synchronises the device). */
 int w4a16_release_scratch(void);

@@ -17,12 +17,13 @@ LIB_PATH = _HERE / "libw4a16.so"
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_SPLIT, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
 REDUCE_AUTO, REDUCE_ATOMIC_F32, REDUCE_ATOMIC_PK_F16, REDUCE_WORKSPACE, REDUCE_ATOMIC_FIXED = 0, 1, 2, 3, 4
+REDUCE_ATOMIC_PK_F16_PHASE = 5
 
 #: every symbol include/w4a16.h declares
 EXPORTS = (
     "w4a16_gemm", "w4a16_gemm_dp", "w4a16_gemm_ex", "w4a16_gemm_dp_ex", "w4a16_plan", "w4a16_check",
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
-    "w4a16_release_scratch",
+    "w4a16_release_scratch", "w4a16_phase_timeouts",
 )
 
 _lib = None
@@ -69,8 +70,10 @@ def lib() -> ctypes.CDLL:
     L.w4a16_last_hip_error.argtypes = []
     L.w4a16_last_hip_error.restype = ctypes.c_char_p
     L.w4a16_release_scratch.argtypes = []
+    L.w4a16_phase_timeouts.argtypes = []
+    L.w4a16_phase_timeouts.restype = ctypes.c_longlong
     for name in EXPORTS:
-        if name not in ("w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error"):
+        if name not in ("w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error", "w4a16_phase_timeouts"):
             getattr(L, name).restype = ci
     _lib = L
     return L
@@ -148,6 +151,13 @@ def w4a16_dequant(qweight, scales, qzeros, W, n, k, group_size, stream=None) -> 
 
 def w4a16_algorithmic_bytes(m, n, k, group_size) -> int:
     return int(lib().w4a16_algorithmic_bytes(m, n, k, group_size))
+
+
+def w4a16_phase_timeouts() -> int:
+    v = int(lib().w4a16_phase_timeouts())
+    if v < 0:
+        _check(v, "w4a16_phase_timeouts")
+    return v
 
 
 def w4a16_release_scratch() -> None:

@@ -5,9 +5,12 @@
 // decomposition".  Algorithm 1 is the SplitK kernel; Section 3 (first paragraph) describes the
 // data-parallel tiling it is compared with; Section 2.1 the atomic reduction.
 #include "w4a16_device.hpp"
+#include "w4a16_shared.hpp"
 
 #include <cstdio>
+#include <cstdlib>
 #include <mutex>
+#include <type_traits>
 
 #include "../../include/w4a16.h"
 
@@ -21,6 +24,11 @@ struct GemmArgs {
     _Float16* C;
     float* scratch;     // split-k: fp32 sums [16, n] (atomic) or partial tiles [split_k, m, n] (workspace)
     uint32_t* tickets;  // split-k: one arrival counter per column tile
+    uint32_t* flags;    // phase mode: zeroings so far, per tile origin
+    uint32_t* counts;   // phase mode: calls so far, per (tile origin, slice)
+    uint32_t* errors;   // phase mode: count of waits that ran out
+    int spin_limit;     // phase mode: bound on polls of a flag
+    int probe_delay;    // phase mode: 64-cycle sleeps before the early sample of the flag
     int m, n, k;
     int tiles;            // column tiles = ceil(n / (16 V))
     int split_k;
@@ -30,7 +38,7 @@ struct GemmArgs {
     int lds_wave_bytes;   // LDS region of one wave
 };
 
-enum : int { kDirect = 0, kAtomicF32 = 1, kAtomicPkF16 = 2, kWorkspace = 3, kAtomicFixed = 4 };
+enum : int { kDirect = 0, kAtomicF32 = 1, kAtomicPkF16 = 2, kWorkspace = 3, kAtomicFixed = 4, kAtomicPkF16Phase = 5 };
 
 // kAtomicFixed: one 64-bit integer atomic add per output element and workgroup.
 //   bits 56..63  arrivals so far (split_k <= 64)
@@ -91,6 +99,9 @@ __device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcn
 //                    in slice order (bit-reproducible).
 // MODE kAtomicFixed  64-bit fixed-point atomic adds that also count arrivals (see above);
 //                    bit-reproducible, one round trip.
+// MODE kAtomicPkF16Phase  packed-fp16 atomic adds straight into C with no launch before this one:
+//                    the slice-0 workgroup of a tile zeroes the tile as its first action and
+//                    publishes that in the tile's flag; the others add once they have seen it.
 //
 // Synchronisation of the ticketed modes.  Every access that one workgroup makes and another
 // reads is a device-scope atomic operation (add, exchange, write-through store, cache-bypassing
@@ -100,21 +111,73 @@ __device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcn
 // the ticket, and the last workgroup reads only after its ticket came back.  A device-scope
 // release fence would do the same but also write back the whole L2 of the die, which costs
 // more than the GEMM itself.
+//
+// The phase protocol (kAtomicPkF16Phase) uses no atomic operation besides the adds into C
+// (atomics of several workgroups on one word are served one after the other, at about a
+// memory round trip each).  State, per split_k and per tile origin e = n0 / 16:
+//   counts[e][slice]  how many calls this (tile, slice) workgroup has run; only it writes it
+//   flags[e]          how many times the tile has been zeroed; only the slice-0 workgroup writes it
+// Every call that touches a tile runs all split_k of its workgroups, so before a call these
+// words are all equal (= c) and after it all are c + 1.  Wave 0 of the slice-0 workgroup stores
+// zeros (write-through) to the tile before it issues any load.  Then wave 0 of every workgroup
+// loads its own count c.  Vector memory operations of a wave complete in issue order, so when c
+// has arrived the zeros are in memory: the slice-0 workgroup stores c + 1 into flags[e] (and every
+// workgroup stores c + 1 into its own count).  Every wave samples flags[e] during its last
+// compute group and, after the workgroup's barrier, adds only when it has seen c + 1; otherwise
+// it polls (bounded by spin_limit; a wait that runs out is counted in `errors` and the wave goes
+// on).  The slice-0 workgroup never waits for anyone and has the lowest block index of the
+// tile's workgroups, so the wait ends.
 // WMAX (4 or 16) is the largest number of waves the instantiation may be launched with; the
 // small one lets the compiler use more than 128 registers per lane.
-template <int V, int IPG, int MODE, int WMAX>
+constexpr int kPhaseMaxSplit = 64;          // split_k of the phase protocol: a power of two up to this
+constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
+
+// GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
+template <int V, int IPG, int MODE, int WMAX, int GC>
 __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V;
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps offsets scalar
-    const int waves = blockDim.x / kWave;
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // uniform: keeps offsets scalar
+    const int waves = nthreads / kWave;
     const int tile = blockIdx.x % p.tiles;
     const int slice = blockIdx.x / p.tiles;
     const int n0 = tile * BN;
     const int m = p.m, n = p.n, k = p.k;
+
+    // ---- phase protocol, first part (wave 0): the zeros of slice 0, then this workgroup's call
+    // count.  Buffer instructions whose offset lies outside the buffer are dropped by the
+    // hardware, so the lanes and waves that take no part get such an offset instead of a branch:
+    // the count stays an ordinary value that is waited for only where it is used.
+    uint32_t count = 0, early = 0;
+    const uint32_t origin = (uint32_t)n0 / 16u;
+    if constexpr (MODE == kAtomicPkF16Phase) {
+        constexpr uint32_t kOutside = 0xFFFFFF00u;
+        // 16-byte units of the tile: unit u = (row, 8 columns); n % 8 == 0 keeps a unit either
+        // inside or outside the matrix.  m * BN / 8 <= 128 units: two per lane of wave 0.
+        const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
+        const bool zeroer = slice == 0 && wave == 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int u = lane + kWave * i;
+            const int row = u / (BN / 8), col = n0 + 8 * (u % (BN / 8));
+            const bool inside = zeroer && row < m && col < n;
+            const uint32_t off = inside ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            // aux 16 = sc1: written through to memory, where every compute die sees it
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{0u, 0u, 0u, 0u}, rs_c, off, 0, 16);
+        }
+        // the count is the first load after the zero stores, and no load is issued ahead of it
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        const rsrc_t rs_counts = make_rsrc(p.counts, kPhaseOrigins * (uint32_t)p.split_k * 4u);
+        count = __builtin_amdgcn_raw_buffer_load_b32(
+            rs_counts, wave == 0 ? (origin * (uint32_t)p.split_k + (uint32_t)slice) * 4u : kOutside, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     const LaneMap lm = make_lane_map<V>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)(k / (32 * IPG)) >> p.param_shift;
@@ -133,94 +196,212 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
     for (int j = 0; j < V; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     const int g_begin = slice * p.groups_per_block + wave * p.groups_per_wave;
-    wave_mainloop<V, IPG>(tensors, lm, g_begin, p.groups_per_wave, acc);
+    // LDS: [0] the flag value this call waits for, [1] wave 0's early sample of the flag; from byte 16 on one [m][BN] fp32 tile per wave
+    uint32_t* lds_phase = (uint32_t*)lds_raw;
+    char* lds_tiles = lds_raw + 16;
+    FlagProbe probe;
+    probe.addr = p.flags + origin;
+    probe.value = 0;
+    Ring<V, IPG> ring;
+    wave_prime<V, IPG, GC>(ring, tensors, lm, g_begin, p.groups_per_wave, [&]() {
+        if constexpr (MODE == kAtomicPkF16Phase) {
+            if (wave == 0) {
+                // wait for the count (the asm makes it a used value here)
+                asm volatile("" : "+v"(count)::"memory");
+                const uint32_t now = __builtin_amdgcn_readfirstlane(count) + 1u;
+                if (lane == 0) {
+                    lds_phase[0] = now;
+                    p.counts[origin * (uint32_t)p.split_k + (uint32_t)slice] = now;
+                    if (slice == 0)
+                        __hip_atomic_store(p.flags + origin, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                // Early sample of the flag for the whole workgroup.  The slice-0 workgroup of
+                // the tile publishes at about this moment, so the sample is taken a little
+                // later; this wave has nothing to do but wait for its weights anyway.  A sample
+                // that comes too early only means that the late sample below is used instead.
+                for (int i = 0; i < p.probe_delay; ++i) __builtin_amdgcn_s_sleep(1);
+                early = __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    });
+    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC>(ring, tensors, lm, g_begin, p.groups_per_wave, acc, probe);
+
+    if constexpr (MODE == kAtomicPkF16Phase) {
+        if (wave == 0 && lane == 0) lds_phase[1] = early;
+    }
 
     // ---- sum the waves' tiles through LDS.  acc[j][r] is row 4*(lane/16)+r, column V*(lane%16)+j.
-    float* red = (float*)(lds_raw + wave * p.lds_wave_bytes);  // [m][BN]
+    float* red = (float*)(lds_tiles + wave * p.lds_wave_bytes);  // [m][BN]
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = 4 * (lane >> 4) + r;
         if (row < m) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) red[row * BN + V * (lane & 15) + j] = acc[j][r];
+            float* dst = red + row * BN + V * (lane & 15);
+            if constexpr (V == 4) {
+                *(float4_t*)dst = float4_t{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+            } else if constexpr (V == 2) {
+                *(float2*)dst = float2{acc[0][r], acc[1][r]};
+            } else {
+                *dst = acc[0][r];
+            }
         }
     }
-    __syncthreads();
 
-    const int pairs = m * (BN / 2);
+    // A unit is one element (modes whose atomics are per element) or two adjacent columns.
+    // Consecutive threads take consecutive units, so an atomic instruction of a wave touches the
+    // fewest cache lines (the L2 charges atomics per line).  A thread's first two units are
+    // handled in straight-line code whose addresses are worked out before the barrier and whose
+    // LDS reads (two units x up to four waves) are in flight together; the modes that write C
+    // itself use buffer instructions, which drop lanes whose offset lies outside the buffer, so
+    // there is no branch between the barrier and the adds.  Further units (few threads, many
+    // rows) go through the loop behind.
+    constexpr int EPU = (MODE == kAtomicF32 || MODE == kAtomicFixed) ? 1 : 2;
+    constexpr bool kBufferOut = MODE == kDirect || MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase;
+    constexpr uint32_t kOutsideC = 0xFFFFFF00u;
+    const int units = m * BN / EPU;
     const int wave_floats = p.lds_wave_bytes / 4;
-    const float* red0 = (const float*)lds_raw;
+    const float* red0 = (const float*)lds_tiles;
+    const rsrc_t rs_out = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
 
-    if constexpr (MODE == kAtomicF32 || MODE == kAtomicFixed) {
-        // one element per lane, consecutive lanes on consecutive columns: an atomic instruction
-        // of a wave then touches the fewest cache lines, and the L2 charges atomics per line.
-        // Up to kBatch elements per thread are in flight at once so that the returning atomics
-        // of the fixed-point mode cost one memory round trip, not one per element.
-        constexpr int kBatch = 4;
-        const int elems = m * BN;
-        for (int e0 = threadIdx.x; e0 < elems; e0 += kBatch * blockDim.x) {
-            size_t idx[kBatch];
-            bool ok[kBatch];
-            float v[kBatch];
+    struct Unit {
+        bool ok;        // inside the tile and the matrix
+        int lds;        // float index inside a wave's tile
+        int row, col;
+        uint32_t off;   // byte offset into C, or kOutsideC
+    };
+    auto make_unit = [&](int u) {
+        Unit x;
+        const int uc = u < units ? u : 0;
+        const int e = uc * EPU;
+        x.lds = e;
+        x.row = e / BN;
+        x.col = n0 + e % BN;
+        x.ok = u < units && x.col < n;
+        x.off = x.ok ? ((uint32_t)x.row * (uint32_t)n + (uint32_t)x.col) * 2u : kOutsideC;
+        return x;
+    };
+    // `base` = wave index of the first of four tiles to read; tiles past the last wave are read
+    // from the last wave (a valid address) and left out of the sum
+    auto read_unit = [&](const Unit& x, int base, float (&v)[4][EPU]) {
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int e = e0 + u * blockDim.x;
-                const int row = e / BN;
-                const int c = e % BN;
-                ok[u] = e < elems && n0 + c < n;
-                idx[u] = ok[u] ? (size_t)row * n + n0 + c : 0;
-                v[u] = 0.f;
-                if (ok[u])
-                    for (int w = 0; w < waves; ++w) v[u] += red0[w * wave_floats + row * BN + c];
-            }
-            if constexpr (MODE == kAtomicF32) {
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u)
-                    if (ok[u])
-                        __hip_atomic_fetch_add(p.scratch + idx[u], v[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int q = 0; q < 4; ++q) {
+            const int wq = base + q < waves ? base + q : waves - 1;
+            const float* src = red0 + wq * wave_floats + x.lds;
+            if constexpr (EPU == 2) {
+                const float2 t2 = *(const float2*)src;
+                v[q][0] = t2.x;
+                v[q][1] = t2.y;
             } else {
-                uint64_t mine[kBatch], old[kBatch];
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    mine[u] = fixed_contribution(v[u]);
-                    old[u] = 0;
-                    if (ok[u])
-                        old[u] = __hip_atomic_fetch_add((uint64_t*)p.scratch + idx[u], mine[u], __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-                }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    float total = 0.f;
-                    if (ok[u] && fixed_finish((uint64_t*)p.scratch + idx[u], old[u], mine[u], p.split_k, &total))
-                        p.C[idx[u]] = (_Float16)total;
-                }
+                v[q][0] = *src;
             }
         }
-    } else {
-        for (int e = threadIdx.x; e < pairs; e += blockDim.x) {
-            const int row = e / (BN / 2);
-            const int c2 = 2 * (e % (BN / 2));
-            const int col = n0 + c2;
-            if (col >= n) continue;
-            float v0 = 0.f, v1 = 0.f;
-            for (int w = 0; w < waves; ++w) {
-                const float2 t = *(const float2*)(red0 + w * wave_floats + row * BN + c2);
-                v0 += t.x;
-                v1 += t.y;
+    };
+    auto add_unit = [&](int base, const float (&v)[4][EPU], float (&sum)[EPU]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float keep = base + q < waves ? 1.f : 0.f;
+#pragma unroll
+            for (int e = 0; e < EPU; ++e) sum[e] = q == 0 ? sum[e] + v[q][e] : sum[e] + keep * v[q][e];
+        }
+    };
+    auto emit_pair = [&](const Unit& xa, const float (&sa)[EPU], const Unit& xb, const float (&sb)[EPU]) {
+        if constexpr (MODE == kDirect) {
+            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sa[0], sa[1]), rs_out, xa.off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sb[0], sb[1]), rs_out, xb.off, 0, 0);
+        } else if constexpr (MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase) {
+            const half2_t ha = {(_Float16)sa[0], (_Float16)sa[1]};
+            const half2_t hb = {(_Float16)sb[0], (_Float16)sb[1]};
+            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(ha, rs_out, xa.off, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(hb, rs_out, xb.off, 0, 0);
+        } else if constexpr (MODE == kAtomicFixed) {
+            const Unit* xs[2] = {&xa, &xb};
+            const float vs[2] = {sa[0], sb[0]};
+            uint64_t mine[2], old[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                mine[i] = fixed_contribution(vs[i]);
+                old[i] = 0;
+                if (xs[i]->ok)
+                    old[i] = __hip_atomic_fetch_add((uint64_t*)p.scratch + (size_t)xs[i]->row * n + xs[i]->col, mine[i],
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            const size_t idx = (size_t)row * n + col;
-            if constexpr (MODE == kDirect) {
-                *(uint32_t*)(p.C + idx) = pack_half2(v0, v1);
-            } else if constexpr (MODE == kAtomicPkF16) {
-                const half2_t h = {(_Float16)v0, (_Float16)v1};
-                __builtin_amdgcn_global_atomic_fadd_v2f16((__attribute__((address_space(1))) half2_t*)(p.C + idx), h);
-            } else {
-                const uint64_t bits = (uint64_t)__builtin_bit_cast(uint32_t, v0) |
-                                      ((uint64_t)__builtin_bit_cast(uint32_t, v1) << 32);
-                __hip_atomic_store((uint64_t*)(p.scratch + ((size_t)slice * m + row) * n + col), bits,
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float total = 0.f;
+                const size_t idx = (size_t)xs[i]->row * n + xs[i]->col;
+                if (xs[i]->ok && fixed_finish((uint64_t*)p.scratch + idx, old[i], mine[i], p.split_k, &total))
+                    p.C[idx] = (_Float16)total;
+            }
+        } else if constexpr (MODE == kAtomicF32) {
+            if (xa.ok)
+                __hip_atomic_fetch_add(p.scratch + (size_t)xa.row * n + xa.col, sa[0], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            if (xb.ok)
+                __hip_atomic_fetch_add(p.scratch + (size_t)xb.row * n + xb.col, sb[0], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        } else {  // kWorkspace
+            const Unit* xs[2] = {&xa, &xb};
+            const float* ss[2] = {sa, sb};
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if (!xs[i]->ok) continue;
+                const uint64_t bits = (uint64_t)__builtin_bit_cast(uint32_t, ss[i][0]) |
+                                      ((uint64_t)__builtin_bit_cast(uint32_t, ss[i][EPU - 1]) << 32);
+                __hip_atomic_store((uint64_t*)(p.scratch + ((size_t)slice * m + xs[i]->row) * n + xs[i]->col), bits,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+    };
+    (void)kBufferOut;
+
+    const Unit first_a = make_unit(tid), first_b = make_unit(tid + nthreads);
+    __syncthreads();
+    float va[4][EPU], vb[4][EPU];
+    read_unit(first_a, 0, va);
+    read_unit(first_b, 0, vb);
+
+    if constexpr (MODE == kAtomicPkF16Phase) {
+        // wait until this call's zeros of the tile are in memory (normally already seen)
+        const uint32_t expect = lds_phase[0];
+        uint32_t seen = lds_phase[1];
+        if (seen != expect) seen = __builtin_amdgcn_readfirstlane(probe.value);
+        int polls = 0;
+        while (seen != expect && polls < p.spin_limit) {
+            __builtin_amdgcn_s_sleep(4);
+            seen = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            ++polls;
+        }
+        if (seen != expect && lane == 0)
+            __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    {
+        float sa[EPU], sb[EPU];
+#pragma unroll
+        for (int e = 0; e < EPU; ++e) sa[e] = sb[e] = 0.f;
+        add_unit(0, va, sa);
+        add_unit(0, vb, sb);
+        for (int base = 4; base < waves; base += 4) {
+            read_unit(first_a, base, va);
+            read_unit(first_b, base, vb);
+            add_unit(base, va, sa);
+            add_unit(base, vb, sb);
+        }
+        emit_pair(first_a, sa, first_b, sb);
+    }
+    for (int u0 = tid + 2 * nthreads; u0 < units; u0 += 2 * nthreads) {
+        const Unit xa = make_unit(u0), xb = make_unit(u0 + nthreads);
+        float sa[EPU], sb[EPU];
+#pragma unroll
+        for (int e = 0; e < EPU; ++e) sa[e] = sb[e] = 0.f;
+        for (int base = 0; base < waves; base += 4) {
+            read_unit(xa, base, va);
+            read_unit(xb, base, vb);
+            add_unit(base, va, sa);
+            add_unit(base, vb, sb);
+        }
+        emit_pair(xa, sa, xb, sb);
     }
 
     if constexpr (MODE == kAtomicF32 || MODE == kWorkspace) {
@@ -234,6 +415,7 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
         }
         __syncthreads();
         if (last_flag) {
+            const int pairs = m * (BN / 2);
             if constexpr (MODE == kAtomicF32) {
                 const int elems = m * BN;
                 for (int e = threadIdx.x; e < elems; e += blockDim.x) {
@@ -262,6 +444,155 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
             }
             if (threadIdx.x == 0)
                 __hip_atomic_store(p.tickets + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// SplitK kernel with the activation slice shared through LDS (see w4a16_shared.hpp).
+// blockIdx.x = tile * split_k + slice: consecutive workgroups go to consecutive compute dies, so
+// with split_k a multiple of 8 every die reads only its own k slices of A.
+//
+// MODE kDirect       split_k == 1: round once, store.
+// MODE kAtomicPkF16  packed-fp16 atomic adds into a C that a fill kernel zeroed beforehand.
+template <int D, int MODE>
+__global__ void __launch_bounds__(512) gemm_shared_kernel(const SharedArgs p)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int slice = blockIdx.x % p.split_k;
+    const int tile = blockIdx.x / p.split_k;
+    const int strip = wave % p.wn;
+    const int kpart = wave / p.wn;
+    const int m = p.m, n = p.n, k = p.k;
+    const int G = p.groups_per_wave;
+    const int g_wg = slice * p.wk * G;     // first compute group of the workgroup
+    const int g_begin = g_wg + kpart * G;  // first compute group of this wave
+    const int n0 = (tile * p.wn + strip) * 64;
+    const bool strip_live = n0 < n;        // uniform per wave; a dead strip only joins the barrier
+
+    const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
+    const uint32_t qgroups = (uint32_t)(k / 128) >> p.param_shift;
+    Tensors tensors;
+    tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 8) * (uint32_t)n * 4u);
+    tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / 8) * 4u);
+    tensors.m = m;
+    tensors.n = n;
+    tensors.k = k;
+    tensors.param_shift = p.param_shift;
+
+    // ---- activation slice -> LDS.  Chunk c = kc * m + row is the 8 halves A[row][k0 + 8 kc ..],
+    // stored at byte 16 c in the slot order of unpack_shift.  The last batch of loads is
+    // followed by the first D groups of weight loads, so the weight stream is already on its way
+    // while the activations are written to LDS.
+    const int chunks = m * p.wk * G * 16;
+    const uint32_t a_soff = (uint32_t)g_wg * 256u;  // 128 k of 2 bytes per compute group
+    constexpr int kBatch = 8;
+    auto chunk_offset = [&](int c) {
+        const int kc = c / m, row = c - kc * m;
+        return ((uint32_t)row * (uint32_t)k + 8u * (uint32_t)kc) * 2u;
+    };
+    int c0 = 0;
+    for (; c0 + kBatch * nthreads < chunks; c0 += kBatch * nthreads) {
+        u32x4_t tmp[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, chunk_offset(c0 + u * nthreads + tid), a_soff, 0);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            *(half8_t*)(lds_raw + (size_t)(c0 + u * nthreads + tid) * 16) = permute_activations(tmp[u]);
+    }
+    // Last batch: 1..kBatch loads per thread, then the first D groups of weight loads, then the
+    // LDS writes.  Straight-line code per load count (a thread past the end repeats the last
+    // chunk), so the wait before each LDS write counts exactly the loads issued after it and
+    // never waits for the weights.
+    WeightRing<D> ring;
+    auto stage_tail = [&](auto nu_tag) {
+        constexpr int NU = decltype(nu_tag)::value;
+        u32x4_t tmp[NU];
+        int cc[NU];
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int c = c0 + u * nthreads + tid;
+            cc[u] = c < chunks ? c : chunks - 1;
+            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, chunk_offset(cc[u]), a_soff, 0);
+        }
+        ring_prime<D, 0>(ring, lm, tensors, g_begin);  // unconditional (a dead strip reads valid columns): no branch
+#pragma unroll
+        for (int u = 0; u < NU; ++u) *(half8_t*)(lds_raw + (size_t)cc[u] * 16) = permute_activations(tmp[u]);
+    };
+    switch ((chunks - c0 + nthreads - 1) / nthreads) {
+    case 1: stage_tail(std::integral_constant<int, 1>{}); break;
+    case 2: stage_tail(std::integral_constant<int, 2>{}); break;
+    case 3: stage_tail(std::integral_constant<int, 3>{}); break;
+    case 4: stage_tail(std::integral_constant<int, 4>{}); break;
+    case 5: stage_tail(std::integral_constant<int, 5>{}); break;
+    case 6: stage_tail(std::integral_constant<int, 6>{}); break;
+    case 7: stage_tail(std::integral_constant<int, 7>{}); break;
+    default: stage_tail(std::integral_constant<int, 8>{}); break;
+    }
+    __syncthreads();
+
+    float4_t acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    if (strip_live) {
+        // lane's A operand of MFMA step s (within the workgroup's k range): slot (4 s + lane / 16, row)
+        const int mrow = lane & 15;
+        const int arow = mrow < m ? mrow : m - 1;
+        const int a_step_bytes = 64 * m;
+        const char* a_ptr = lds_raw + ((lane >> 4) * m + arow) * 16 + (size_t)kpart * G * 4 * a_step_bytes;
+        u32x4_t a[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(a_ptr + it * a_step_bytes);
+        const uint32_t magic = magic_1024x2();
+        int g = 0;
+        for (; g + D < G; g += D)
+            shared_compute_slots<D, 0, true>(ring, lm, tensors, magic, g_begin + g + D, a_ptr, a_step_bytes, a, acc);
+        shared_compute_slots<D, 0, false>(ring, lm, tensors, magic, 0, a_ptr, a_step_bytes, a, acc);
+    }
+
+    // ---- every wave's tile -> LDS (behind the activation slice), then the k parts are added and
+    // the sums leave with consecutive lanes on consecutive column pairs.
+    float* red_all = (float*)(lds_raw + p.a_bytes);
+    float* red = red_all + (size_t)wave * m * 64;  // [m][64]
+    if (strip_live) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * (lane >> 4) + r;
+            if (row < m) {
+                float4_t v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+                *(float4_t*)(red + row * 64 + 4 * (lane & 15)) = v;
+            }
+        }
+    }
+    __syncthreads();
+    const int pairs_per_row = p.wn * 32;
+    const int pairs = m * pairs_per_row;
+    for (int e = tid; e < pairs; e += nthreads) {
+        const int row = e / pairs_per_row;
+        const int cp = e - row * pairs_per_row;
+        const int st = cp >> 5;
+        const int c2 = 2 * (cp & 31);
+        const int col = (tile * p.wn + st) * 64 + c2;
+        if (col >= n) continue;
+        float v0 = 0.f, v1 = 0.f;
+        for (int kp = 0; kp < p.wk; ++kp) {
+            const float2 t2 = *(const float2*)(red_all + (size_t)(kp * p.wn + st) * m * 64 + row * 64 + c2);
+            v0 += t2.x;
+            v1 += t2.y;
+        }
+        const size_t idx = (size_t)row * n + col;
+        if constexpr (MODE == kDirect) {
+            *(uint32_t*)(p.C + idx) = pack_half2(v0, v1);
+        } else {
+            const half2_t h = {(_Float16)v0, (_Float16)v1};
+            __builtin_amdgcn_global_atomic_fadd_v2f16((__attribute__((address_space(1))) half2_t*)(p.C + idx), h);
         }
     }
 }
@@ -323,7 +654,14 @@ struct DeviceScratch {
     Buffer partials;  // workspace mode: fp32 [split_k, m, n]; no invariant
     Buffer fixed;     // fixed-point mode: uint64 [16, n]; all zero whenever no call is running
     Buffer tickets;   // uint32 per column tile; all zero whenever no call is running
+    Buffer phase;     // phase mode, uint32: per split_k = 2^j (j = 1..6) flags [kPhaseOrigins] and counts
+                      // [kPhaseOrigins][split_k]; then the error count [1]
 };
+// Word offsets inside DeviceScratch::phase for split_k = 2^j.
+static size_t phase_flags_offset(int j) { return (size_t)(j - 1) * kPhaseOrigins; }
+static size_t phase_counts_offset(int j) { return 6 * (size_t)kPhaseOrigins + (size_t)kPhaseOrigins * ((1u << j) - 2u); }
+static size_t phase_errors_offset() { return phase_counts_offset(7); }
+static size_t phase_words() { return phase_errors_offset() + 1; }
 // Text of the last failed HIP call on this host thread (for W4A16_ERR_HIP diagnostics).
 static thread_local char g_hip_detail[256] = "";
 
@@ -336,6 +674,13 @@ static bool hip_ok(hipError_t e, const char* what)
 #define W4A16_HIP(call) hip_ok((call), #call)
 
 constexpr int kMaxDevices = 64;
+// Polls of a tile flag before a wave gives up (each poll is a round trip to memory, about a
+// microsecond): far longer than any call takes, short enough that a broken state cannot hang
+// the device.
+constexpr int kSpinLimit = 1 << 17;
+// 64-cycle sleeps between a workgroup learning its call count and its early sample of the tile
+// flag (about 0.45 us at 2.4 GHz).
+static int g_probe_delay = 16;
 static DeviceScratch g_scratch[kMaxDevices];
 static std::mutex g_mutex;
 
@@ -363,6 +708,12 @@ static int largest_wave_split(int groups, int cap)
 struct Plan {
     int split_k, tile_cols, waves, reduce;
 };
+
+// The phase protocol keeps one set of words per split_k: powers of two up to kPhaseMaxSplit.
+static bool phase_split_ok(int split_k)
+{
+    return split_k >= 2 && split_k <= kPhaseMaxSplit && (split_k & (split_k - 1)) == 0;
+}
 
 // Launch shape, from sweeps on MI355X (256 compute units, 1024 SIMDs).
 //
@@ -407,10 +758,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // few rows: the arrival-counting fixed-point adds finish in one round trip with no
         // zero-fill launch.  Many rows: returning 64-bit atomics cost more than the fill launch
         // that the packed-fp16 adds need.
-        reduce = (m <= 4 && split_k <= 64) ? W4A16_REDUCE_ATOMIC_FIXED : W4A16_REDUCE_ATOMIC_PK_F16;
+        reduce = (m <= 4 && split_k <= 64) ? W4A16_REDUCE_ATOMIC_FIXED
+                 : phase_split_ok(split_k)  ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
+                                            : W4A16_REDUCE_ATOMIC_PK_F16;
     }
-    if (reduce < W4A16_REDUCE_ATOMIC_F32 || reduce > W4A16_REDUCE_ATOMIC_FIXED) return W4A16_ERR_UNSUPPORTED;
+    if (reduce < W4A16_REDUCE_ATOMIC_F32 || reduce > W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_ATOMIC_FIXED && split_k > 64) return W4A16_ERR_UNSUPPORTED;
+    if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE && !phase_split_ok(split_k)) return W4A16_ERR_UNSUPPORTED;
     out->split_k = split_k;
     out->tile_cols = tile_cols;
     out->waves = waves;
@@ -434,7 +788,8 @@ static int grow(Buffer& b, size_t bytes, bool* grew)
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
-                          float** sums, float** partials, uint64_t** fixed, uint32_t** tickets)
+                          bool want_phase, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
+                          uint32_t** phase)
 {
     int dev = 0;
     if (!W4A16_HIP(hipGetDevice(&dev))) return W4A16_ERR_HIP;
@@ -446,19 +801,21 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
     if (rc == W4A16_OK) rc = grow(s.partials, partial_floats * sizeof(float), &grew);
     if (rc == W4A16_OK) rc = grow(s.fixed, fixed_words * sizeof(uint64_t), &grew);
     if (rc == W4A16_OK) rc = grow(s.tickets, ticket_count * sizeof(uint32_t), &grew);
+    if (rc == W4A16_OK && want_phase) rc = grow(s.phase, phase_words() * sizeof(uint32_t), &grew);
     if (rc != W4A16_OK) return rc;
     if (grew && !W4A16_HIP(hipDeviceSynchronize())) return W4A16_ERR_HIP;
     *sums = (float*)s.sums.ptr;
     *partials = (float*)s.partials.ptr;
     *fixed = (uint64_t*)s.fixed.ptr;
     *tickets = (uint32_t*)s.tickets.ptr;
+    *phase = (uint32_t*)s.phase.ptr;
     return W4A16_OK;
 }
 
-template <int V, int IPG, int MODE, int WMAX>
+template <int V, int IPG, int MODE, int WMAX, int GC>
 static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_kernel<V, IPG, MODE, WMAX>;
+    auto kern = gemm_kernel<V, IPG, MODE, WMAX, GC>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -472,8 +829,19 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
 template <int V, int IPG, int MODE>
 static int launch_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
-    if (waves <= 4) return launch_bound<V, IPG, MODE, 4>(a, waves, lds_bytes, stream);
-    return launch_bound<V, IPG, MODE, 16>(a, waves, lds_bytes, stream);
+    if (waves <= 4) {
+        // the tuned shape (128-bit loads, group of 128) knows its group count at compile time
+        if constexpr (V == 4 && IPG == 4) {
+            if (a.groups_per_wave == 1) return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
+            return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
+        }
+        return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
+    }
+    if constexpr (V == 4 && IPG == 4) {
+        // one group per wave needs few registers, so large workgroups lose nothing
+        if (a.groups_per_wave == 1) return launch_bound<V, IPG, MODE, 16, 1>(a, waves, lds_bytes, stream);
+    }
+    return launch_bound<V, IPG, MODE, 16, 0>(a, waves, lds_bytes, stream);
 }
 
 template <int V, int IPG>
@@ -484,7 +852,8 @@ static int launch_mode(const GemmArgs& a, int waves, size_t lds_bytes, int mode,
     case kAtomicF32: return launch_one<V, IPG, kAtomicF32>(a, waves, lds_bytes, stream);
     case kAtomicPkF16: return launch_one<V, IPG, kAtomicPkF16>(a, waves, lds_bytes, stream);
     case kWorkspace: return launch_one<V, IPG, kWorkspace>(a, waves, lds_bytes, stream);
-    default: return launch_one<V, IPG, kAtomicFixed>(a, waves, lds_bytes, stream);
+    case kAtomicFixed: return launch_one<V, IPG, kAtomicFixed>(a, waves, lds_bytes, stream);
+    default: return launch_one<V, IPG, kAtomicPkF16Phase>(a, waves, lds_bytes, stream);
     }
 }
 
@@ -498,11 +867,89 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
     }
 }
 
+// ---- launch of the shared-activation SplitK kernel
+template <int D, int MODE>
+static int launch_shared_one(const SharedArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
+{
+    auto kern = gemm_shared_kernel<D, MODE>;
+    if (lds_bytes > 64 * 1024) {
+        if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes)))
+            return W4A16_ERR_HIP;
+    }
+    const unsigned grid = (unsigned)(a.tiles * a.split_k);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * kWave), lds_bytes, stream, a);
+    return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
+}
+
+template <int D>
+static int launch_shared_mode(const SharedArgs& a, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+{
+    if (mode == kDirect) return launch_shared_one<D, kDirect>(a, waves, lds_bytes, stream);
+    return launch_shared_one<D, kAtomicPkF16>(a, waves, lds_bytes, stream);
+}
+
+// tile_cols = 64 * wn (128 or 256), waves = wn * wk (at most 8).  group_size 128 or 256.
+static int run_shared(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                      int n, int k, int group_size, int split_k, int tile_cols, int waves, int reduce,
+                      hipStream_t stream)
+{
+    if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
+    const int wn = tile_cols / 64;
+    if (waves == 0) waves = wn;
+    if (waves < wn || waves > 8 || waves % wn != 0) return W4A16_ERR_UNSUPPORTED;
+    const int wk = waves / wn;
+    const int groups = k / 128;
+    if (split_k < 1 || groups % (split_k * wk) != 0) return W4A16_ERR_SPLIT;
+    if (reduce == W4A16_REDUCE_AUTO) reduce = W4A16_REDUCE_ATOMIC_PK_F16;
+    if (reduce != W4A16_REDUCE_ATOMIC_PK_F16) return W4A16_ERR_UNSUPPORTED;
+    SharedArgs a;
+    a.A = (const _Float16*)A;
+    a.qweight = (const uint32_t*)qweight;
+    a.scales = (const _Float16*)scales;
+    a.qzeros = (const uint32_t*)qzeros;
+    a.C = (_Float16*)C;
+    a.flags = nullptr;
+    a.m = m;
+    a.n = n;
+    a.k = k;
+    a.tiles = (n + tile_cols - 1) / tile_cols;
+    a.split_k = split_k;
+    a.wn = wn;
+    a.wk = wk;
+    a.groups_per_wave = groups / (split_k * wk);
+    a.param_shift = group_size == 256 ? 1 : 0;
+    a.a_bytes = m * wk * a.groups_per_wave * 128 * 2;
+    a.spin_limit = 0;
+    const size_t lds_bytes = (size_t)a.a_bytes + (size_t)waves * m * 64 * 4;
+    if (lds_bytes > 160 * 1024) return W4A16_ERR_UNSUPPORTED;
+    const int mode = split_k > 1 ? kAtomicPkF16 : kDirect;
+    if (mode == kAtomicPkF16) {
+        const size_t words = (size_t)m * n / 2;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                           (uint32_t*)C, words);
+        if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    }
+    const int G = a.groups_per_wave;
+    if (G % 4 == 0) return launch_shared_mode<4>(a, waves, lds_bytes, mode, stream);
+    if (G % 2 == 0) return launch_shared_mode<2>(a, waves, lds_bytes, mode, stream);
+    return launch_shared_mode<1>(a, waves, lds_bytes, mode, stream);
+}
+
+static void read_tuning_env()
+{
+    static bool done = false;
+    if (done) return;
+    done = true;
+    if (const char* e = getenv("W4A16_PROBE_DELAY")) g_probe_delay = atoi(e);
+}
+
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
                     int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves, int reduce,
                     void* stream_v)
 {
     if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
+    read_tuning_env();
     int rc = check_args(m, n, k, group_size, dp ? 1 : split_k);
     if (rc != W4A16_OK) return rc;
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
@@ -517,6 +964,11 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
             if (rc != W4A16_OK) return rc;
         }
         return W4A16_OK;
+    }
+    if (!dp && (tile_cols == 128 || tile_cols == 256)) {
+        if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+        return run_shared(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, tile_cols, waves, reduce,
+                          (hipStream_t)stream_v);
     }
     Plan plan;
     rc = make_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce, &plan);
@@ -543,9 +995,15 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     a.groups_per_block = (k / (32 * ipg)) / plan.split_k;
     a.groups_per_wave = a.groups_per_block / plan.waves;
     a.param_shift = param_shift;
-    // LDS: one [m, tile_cols] fp32 tile per wave, for the sum over the workgroup's waves
+    // LDS: 16 bytes for the phase word, then one [m, tile_cols] fp32 tile per wave, for the sum
+    // over the workgroup's waves
     a.lds_wave_bytes = (m * plan.tile_cols * 4 + 15) & ~15;
-    const size_t lds_bytes = (size_t)a.lds_wave_bytes * plan.waves;
+    const size_t lds_bytes = 16 + (size_t)a.lds_wave_bytes * plan.waves;
+    a.flags = nullptr;
+    a.counts = nullptr;
+    a.errors = nullptr;
+    a.spin_limit = kSpinLimit;
+    a.probe_delay = g_probe_delay;
     if (lds_bytes > 160 * 1024) return W4A16_ERR_UNSUPPORTED;
 
     int mode = kDirect;
@@ -554,12 +1012,21 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         if (mode != kAtomicPkF16) {
             float *sums = nullptr, *partials = nullptr;
             uint64_t* fixed = nullptr;
+            uint32_t* phase = nullptr;
+            if (mode == kAtomicPkF16Phase && (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
             rc = ensure_scratch(mode == kAtomicF32 ? (size_t)16 * n : 0,
                                 mode == kWorkspace ? (size_t)plan.split_k * m * n : 0,
-                                mode == kAtomicFixed ? (size_t)16 * n : 0, (size_t)a.tiles, &sums, &partials, &fixed,
-                                &a.tickets);
+                                mode == kAtomicFixed ? (size_t)16 * n : 0, (size_t)a.tiles,
+                                mode == kAtomicPkF16Phase, &sums, &partials, &fixed, &a.tickets, &phase);
             if (rc != W4A16_OK) return rc;
             a.scratch = mode == kAtomicF32 ? sums : mode == kWorkspace ? partials : (float*)fixed;
+            if (mode == kAtomicPkF16Phase) {
+                int j = 0;
+                while ((1 << j) < plan.split_k) ++j;
+                a.flags = phase + phase_flags_offset(j);
+                a.counts = phase + phase_counts_offset(j);
+                a.errors = phase + phase_errors_offset();
+            }
         } else {
             const size_t words = (size_t)m * n / 2;
             hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
@@ -679,6 +1146,22 @@ const char* w4a16_strerror(int code)
 
 const char* w4a16_last_hip_error(void) { return w4a16::g_hip_detail; }
 
+long long w4a16_phase_timeouts(void)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return W4A16_ERR_HIP;
+    if (dev < 0 || dev >= w4a16::kMaxDevices) return W4A16_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(w4a16::g_mutex);
+    const w4a16::DeviceScratch& s = w4a16::g_scratch[dev];
+    if (!s.phase.ptr) return 0;
+    uint32_t count = 0;
+    if (hipDeviceSynchronize() != hipSuccess) return W4A16_ERR_HIP;
+    if (hipMemcpy(&count, (const uint32_t*)s.phase.ptr + w4a16::phase_errors_offset(), sizeof(count),
+                  hipMemcpyDeviceToHost) != hipSuccess)
+        return W4A16_ERR_HIP;
+    return (long long)count;
+}
+
 int w4a16_release_scratch(void)
 {
     int dev = 0;
@@ -691,6 +1174,7 @@ int w4a16_release_scratch(void)
     if (s.partials.ptr) (void)hipFree(s.partials.ptr);
     if (s.fixed.ptr) (void)hipFree(s.fixed.ptr);
     if (s.tickets.ptr) (void)hipFree(s.tickets.ptr);
+    if (s.phase.ptr) (void)hipFree(s.phase.ptr);
     s = w4a16::DeviceScratch{};
     return W4A16_OK;
 }

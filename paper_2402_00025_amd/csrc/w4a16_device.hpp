@@ -238,12 +238,21 @@ __device__ __forceinline__ void issue_group(Ring<V, IPG>& ring, const LaneMap& l
     for (int it = 0; it < IPG; ++it) issue_step<V, IPG>(ring.step[H][it], lm, t, gi, it);
 }
 
+// A word in memory that the last compute group of a wave samples while it still has work to
+// do, so that the round trip to memory is hidden (used by the split-k mode whose workgroups
+// wait for the zeroing of their output tile; see the kernel).
+struct FlagProbe {
+    const uint32_t* addr;
+    uint32_t value;
+};
+
 // One compute group out of ring half H: IPG MFMA steps into a fresh 16x16 tile per column
 // set, then acc += scale * tile in fp32.  Each step's registers are refilled with the same
-// step of group `refill` (two groups ahead) as soon as they have been consumed.
-template <int V, int IPG, int H, bool REFILL>
+// step of group `refill` (two groups ahead) as soon as they have been consumed.  With PROBE the
+// flag is sampled once the second step's weights have arrived.
+template <int V, int IPG, int H, bool REFILL, bool PROBE>
 __device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap& lm, const Tensors& t,
-                                              uint32_t magic, int refill, float4_t (&acc)[V])
+                                              uint32_t magic, int refill, float4_t (&acc)[V], FlagProbe& probe)
 {
     ZeroConst zc[V];
     float sc[V];
@@ -273,6 +282,13 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap&
             issue_step<V, IPG>(ring.step[H][it], lm, t, refill, it);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (PROBE) {
+            if (it == (IPG > 1 ? 1 : 0)) {
+                __builtin_amdgcn_sched_barrier(0);
+                probe.value = __hip_atomic_load(probe.addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < V; ++j) tile[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8[j], tile[j], 0, 0, 0);
     }
@@ -281,31 +297,56 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap&
 }
 
 // The loop of Algorithm 1 for one wave: compute groups [g_begin, g_begin + g_count) of its
-// strip, with up to two groups of loads in flight.  The steady-state loop refills without any
-// branch, so the compiler's wait counts stay exact; the last one to three groups drain the ring.
-template <int V, int IPG>
-__device__ __forceinline__ void wave_mainloop(const Tensors& t, const LaneMap& lm, int g_begin, int g_count,
-                                              float4_t (&acc)[V])
+// strip, with up to two groups of loads in flight.  wave_prime issues the first one or two
+// groups; wave_run consumes them.  The steady-state loop refills without any branch, so the
+// compiler's wait counts stay exact; the last one to three groups drain the ring.
+// `primed()` runs once, after the loads have been issued, inside the branch that issued them:
+// a wait it contains then counts exactly the loads of that branch.  GC is what is known about
+// g_count at compile time: 1 = exactly one group, 2 = at least two, 0 = nothing.
+template <int V, int IPG, int GC, class F>
+__device__ __forceinline__ void wave_prime(Ring<V, IPG>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
+                                           int g_count, F&& primed)
+{
+    issue_group<V, IPG, 0>(ring, lm, t, g_begin);
+    if constexpr (GC == 1) {
+        primed();
+    } else if constexpr (GC == 2) {
+        issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+        primed();
+    } else {
+        if (g_count > 1) {
+            issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+            primed();
+        } else {
+            primed();
+        }
+    }
+}
+
+template <int V, int IPG, bool PROBE, int GC>
+__device__ __forceinline__ void wave_run(Ring<V, IPG>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
+                                         int g_count, float4_t (&acc)[V], FlagProbe& probe)
 {
     const uint32_t magic = magic_1024x2();
-    Ring<V, IPG> ring;
-    issue_group<V, IPG, 0>(ring, lm, t, g_begin);
-    if (g_count > 1) issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+    if constexpr (GC == 1) {
+        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
+        return;
+    }
     int i = 0;
     for (; i + 3 < g_count; i += 2) {
-        compute_group<V, IPG, 0, true>(ring, lm, t, magic, g_begin + i + 2, acc);
-        compute_group<V, IPG, 1, true>(ring, lm, t, magic, g_begin + i + 3, acc);
+        compute_group<V, IPG, 0, true, false>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
+        compute_group<V, IPG, 1, true, false>(ring, lm, t, magic, g_begin + i + 3, acc, probe);
     }
     const int left = g_count - i;  // 1, 2 or 3 groups; half 0 holds group i, half 1 group i + 1
     if (left == 3) {
-        compute_group<V, IPG, 0, true>(ring, lm, t, magic, g_begin + i + 2, acc);
-        compute_group<V, IPG, 1, false>(ring, lm, t, magic, 0, acc);
-        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
+        compute_group<V, IPG, 0, true, false>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
+        compute_group<V, IPG, 1, false, false>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
     } else if (left == 2) {
-        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
-        compute_group<V, IPG, 1, false>(ring, lm, t, magic, 0, acc);
+        compute_group<V, IPG, 0, false, false>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 1, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
     } else if (left == 1) {
-        compute_group<V, IPG, 0, false>(ring, lm, t, magic, 0, acc);
+        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
     }
 }
 

@@ -31,7 +31,8 @@ def test_error_codes_match_header():
                       ("W4A16_ERR_SPLIT", b.ERR_SPLIT), ("W4A16_ERR_UNSUPPORTED", b.ERR_UNSUPPORTED),
                       ("W4A16_ERR_HIP", b.ERR_HIP), ("W4A16_REDUCE_ATOMIC_F32", b.REDUCE_ATOMIC_F32),
                       ("W4A16_REDUCE_ATOMIC_PK_F16", b.REDUCE_ATOMIC_PK_F16), ("W4A16_REDUCE_WORKSPACE", b.REDUCE_WORKSPACE),
-                      ("W4A16_REDUCE_ATOMIC_FIXED", b.REDUCE_ATOMIC_FIXED)):
+                      ("W4A16_REDUCE_ATOMIC_FIXED", b.REDUCE_ATOMIC_FIXED),
+                      ("W4A16_REDUCE_ATOMIC_PK_F16_PHASE", b.REDUCE_ATOMIC_PK_F16_PHASE)):
         mt = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", HEADER)
         assert mt and int(mt.group(1)) == val, name
     for code in range(-6, 1):

@@ -102,6 +102,12 @@ SMALL = [
     (3, 328, 1024, 128, 8, 64, 1, 4),
     (16, 136, 512, 128, 2, 32, 2, 4),
     (5, 72, 1024, 128, 2, 16, 4, 4),
+    (16, 200, 1024, 128, 4, 64, 2, 5),
+    (3, 328, 1024, 128, 8, 64, 1, 5),
+    (16, 136, 512, 128, 2, 32, 2, 5),
+    (5, 72, 1024, 128, 2, 16, 4, 5),
+    (16, 264, 2048, 128, 2, 64, 8, 5),
+    (9, 192, 512, 32, 16, 64, 1, 5),
 ]
 
 
@@ -123,7 +129,7 @@ def test_small_shapes(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
 
 
 # ------------------------------------------------------------------ exact cases
-@pytest.mark.parametrize("split_k,reduce", [(1, 0), (4, 1), (4, 2), (4, 3), (4, 4)])
+@pytest.mark.parametrize("split_k,reduce", [(1, 0), (4, 1), (4, 2), (4, 3), (4, 4), (4, 5), (2, 5)])
 def test_one_hot_rows_bit_exact(split_k, reduce):
     """A row equal to e_r selects row r of W: one non-zero term, every other partial sum is an
     exact zero, so every reduction flavour must return fp16(w[r, :]) exactly.  Sweeps all k."""
@@ -232,6 +238,76 @@ def test_more_than_16_rows(oracle):
     assert_parity(p.result(), Cref, "m=40 dp")
 
 
+def test_phase_mode_call_sequences(oracle):
+    """The in-kernel zeroing protocol keeps per-tile state between calls: run calls of different
+    shapes, split factors and tile widths back to back into NaN-filled outputs, twice each,
+    and require parity every time and no wait that ran out."""
+    cases = [(16, 328, 1024, 4, 64, 2), (5, 200, 2048, 8, 64, 2), (16, 328, 1024, 2, 32, 4),
+             (1, 72, 1024, 8, 16, 1), (16, 328, 1024, 8, 64, 1), (16, 136, 1024, 2, 64, 4)]
+    probs = []
+    for (m, n, k, S, tc, wv) in cases:
+        A, qw, s, qz = random_case(m, n, k, 128, seed=500 + m + n + S)
+        Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+        probs.append((DeviceProblem(A, qw, s, qz, 128), Cref, S, tc, wv))
+    for rnd in range(3):
+        for (p, Cref, S, tc, wv) in probs:
+            for _ in range(2):
+                p.C.fill_(float("nan"))
+                b.w4a16_gemm_ex(*p.args(), S, tc, wv, b.REDUCE_ATOMIC_PK_F16_PHASE)
+                assert_parity(p.result(), Cref, f"phase S={S} tile={tc} waves={wv} round={rnd}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+# ------------------------------------------------------------------ shared-activation SplitK kernel
+SHARED_SMALL = [
+    # m, n, k, g, split_k, tile_cols (64 * column strips), waves (strips * k parts)
+    (16, 256, 512, 128, 1, 256, 4),     # one group per wave, direct store
+    (16, 256, 512, 128, 4, 256, 4),
+    (16, 512, 1024, 128, 2, 256, 8),    # two k parts added in LDS
+    (1, 256, 1024, 128, 2, 256, 4),
+    (3, 328, 1024, 128, 4, 256, 4),     # ragged: second tile has one live strip and a half
+    (5, 200, 1024, 128, 2, 128, 4),     # 2 strips x 2 k parts, overhanging strip
+    (16, 72, 2048, 128, 2, 128, 2),     # overhanging strip; eight groups per wave (ring depth 4, steady loop)
+    (7, 136, 4096, 128, 2, 128, 2),     # 16 groups per wave: several steady iterations
+    (16, 264, 1536, 128, 2, 256, 4),    # 6 groups per wave: ring depth 2
+    (9, 192, 1024, 256, 2, 128, 4),     # group_size 256
+    (16, 192, 2048, 128, 1, 256, 8),    # direct store with k parts
+    (4, 512, 8192, 128, 1, 256, 4),     # long activation slice: two staging batches, more than 64 KiB of LDS
+    (16, 512, 4096, 128, 2, 256, 4),    # 2048 k per workgroup at 16 rows: 64 KiB slice
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves", SHARED_SMALL)
+def test_shared_kernel_small_shapes(oracle, m, n, k, g, split_k, tile_cols, waves):
+    A, qw, s, qz = random_case(m, n, k, g, seed=300 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+    assert_parity(p.result(), Cref, f"shared m={m} n={n} k={k} S={split_k} tile={tile_cols} waves={waves}")
+    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+    assert_parity(p.result(), Cref, "second call")
+
+
+@pytest.mark.parametrize("split_k,tile_cols,waves", [(1, 256, 4), (4, 256, 4), (2, 128, 4), (2, 256, 8)])
+def test_shared_kernel_one_hot_rows_bit_exact(split_k, tile_cols, waves):
+    """Same single-term argument as test_one_hot_rows_bit_exact, through the LDS-staged
+    activation operand: pins its slot order, the k parts and the slice boundaries."""
+    m, n, k, g = 16, 328, 1024, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=45)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
@@ -243,7 +319,10 @@ def test_cfg2_split_sweep(oracle):
     """m = 16, n = k = 4096, split_k in {1, 2, 4, 8, 16}, every reduction flavour, and DP."""
     x, Cref, p = _full(oracle, 16, 4096)
     for split_k in (1, 2, 4, 8, 16):
-        for reduce in (b.REDUCE_ATOMIC_F32, b.REDUCE_ATOMIC_PK_F16, b.REDUCE_WORKSPACE, b.REDUCE_ATOMIC_FIXED):
+        for reduce in (b.REDUCE_ATOMIC_F32, b.REDUCE_ATOMIC_PK_F16, b.REDUCE_WORKSPACE, b.REDUCE_ATOMIC_FIXED,
+                       b.REDUCE_ATOMIC_PK_F16_PHASE):
+            if split_k == 1 and reduce == b.REDUCE_ATOMIC_PK_F16_PHASE:
+                continue
             p.C.fill_(float("nan"))
             b.w4a16_gemm_ex(*p.args(), split_k, 0, 0, reduce)
             assert_parity(p.result(), Cref, f"cfg2 S={split_k} reduce={reduce}")
