@@ -38,7 +38,10 @@ struct GemmArgs {
     int lds_wave_bytes;   // LDS region of one wave
 };
 
-enum : int { kDirect = 0, kAtomicF32 = 1, kAtomicPkF16 = 2, kWorkspace = 3, kAtomicFixed = 4, kAtomicPkF16Phase = 5 };
+enum : int {
+    kDirect = 0, kAtomicF32 = 1, kAtomicPkF16 = 2, kWorkspace = 3, kAtomicFixed = 4, kAtomicPkF16Phase = 5,
+    kAtomicPkF16Service = 6  // the phase protocol run by one extra wavefront per workgroup (internal)
+};
 
 // kAtomicFixed: one 64-bit integer atomic add per output element and workgroup.
 //   bits 56..63  arrivals so far (split_k <= 64)
@@ -127,20 +130,28 @@ __device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcn
 // it polls (bounded by spin_limit; a wait that runs out is counted in `errors` and the wave goes
 // on).  The slice-0 workgroup never waits for anyone and has the lowest block index of the
 // tile's workgroups, so the wait ends.
-// WMAX (4 or 16) is the largest number of waves the instantiation may be launched with; the
-// small one lets the compiler use more than 128 registers per lane.
+// MODE kAtomicPkF16Service is the same protocol with the roles moved out of the working waves:
+// the workgroup has one wavefront more, which stores the zeros (slice 0), loads the count,
+// publishes, samples the flag until it has seen this call's value, and only then joins the
+// workgroup's barrier.  The working waves neither issue the protocol's memory operations (whose
+// in-order completion would hold back their weight data) nor look at the flag: passing the
+// barrier means the zeros are in memory.  Used where a wave needs few registers (one compute
+// group per wave), so that the extra wave costs no occupancy.
+// WMAX (4 or 16) is the largest number of working waves the instantiation may be launched with;
+// the small one lets the compiler use more than 128 registers per lane.
 constexpr int kPhaseMaxSplit = 64;          // split_k of the phase protocol: a power of two up to this
 constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
 template <int V, int IPG, int MODE, int WMAX, int GC>
-__global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
+__global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0))) gemm_kernel(const GemmArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V;
+    constexpr bool kService = MODE == kAtomicPkF16Service;
 
     const int tid = threadIdx.x;
-    const int nthreads = blockDim.x;
+    const int nthreads = blockDim.x - (kService ? kWave : 0);  // threads of the working waves
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // uniform: keeps offsets scalar
     const int waves = nthreads / kWave;
@@ -148,6 +159,46 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
     const int slice = blockIdx.x / p.tiles;
     const int n0 = tile * BN;
     const int m = p.m, n = p.n, k = p.k;
+
+    if constexpr (kService) {
+        if (wave == waves) {
+            // ---- the service wave (see the protocol above)
+            constexpr uint32_t kOutside = 0xFFFFFF00u;
+            const uint32_t origin_s = (uint32_t)n0 / 16u;
+            const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int u = lane + kWave * i;
+                const int row = u / (BN / 8), col = n0 + 8 * (u % (BN / 8));
+                const bool inside = slice == 0 && row < m && col < n;
+                const uint32_t off = inside ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{0u, 0u, 0u, 0u}, rs_c, off, 0, 16);
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            uint32_t* my_count = p.counts + origin_s * (uint32_t)p.split_k + (uint32_t)slice;
+            uint32_t count_s = *(volatile uint32_t*)my_count;  // issued after the stores: its arrival means they are done
+            asm volatile("" : "+v"(count_s)::"memory");
+            const uint32_t now = __builtin_amdgcn_readfirstlane(count_s) + 1u;
+            if (lane == 0) {
+                *my_count = now;
+                if (slice == 0)
+                    __hip_atomic_store(p.flags + origin_s, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            uint32_t seen = now - 1u;
+            int polls = 0;
+            do {
+                for (int i = 0; i < p.probe_delay; ++i) __builtin_amdgcn_s_sleep(1);
+                seen = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(p.flags + origin_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                ++polls;
+            } while (seen != now && polls < p.spin_limit);
+            if (seen != now && lane == 0)
+                __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();  // the working waves' one barrier
+            return;
+        }
+    }
 
     // ---- phase protocol, first part (wave 0): the zeros of slice 0, then this workgroup's call
     // count.  Buffer instructions whose offset lies outside the buffer are dropped by the
@@ -256,7 +307,8 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
     // there is no branch between the barrier and the adds.  Further units (few threads, many
     // rows) go through the loop behind.
     constexpr int EPU = (MODE == kAtomicF32 || MODE == kAtomicFixed) ? 1 : 2;
-    constexpr bool kBufferOut = MODE == kDirect || MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase;
+    constexpr bool kBufferOut =
+        MODE == kDirect || MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase || MODE == kAtomicPkF16Service;
     constexpr uint32_t kOutsideC = 0xFFFFFF00u;
     const int units = m * BN / EPU;
     const int wave_floats = p.lds_wave_bytes / 4;
@@ -308,7 +360,7 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
         if constexpr (MODE == kDirect) {
             __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sa[0], sa[1]), rs_out, xa.off, 0, 0);
             __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sb[0], sb[1]), rs_out, xb.off, 0, 0);
-        } else if constexpr (MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase) {
+        } else if constexpr (MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase || MODE == kAtomicPkF16Service) {
             const half2_t ha = {(_Float16)sa[0], (_Float16)sa[1]};
             const half2_t hb = {(_Float16)sb[0], (_Float16)sb[1]};
             __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(ha, rs_out, xa.off, 0, 0);
@@ -355,10 +407,13 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
     (void)kBufferOut;
 
     const Unit first_a = make_unit(tid), first_b = make_unit(tid + nthreads);
+    const bool has_units = tid < units;  // a workgroup of many waves on a narrow tile has idle threads
     __syncthreads();
     float va[4][EPU], vb[4][EPU];
-    read_unit(first_a, 0, va);
-    read_unit(first_b, 0, vb);
+    if (has_units) {
+        read_unit(first_a, 0, va);
+        read_unit(first_b, 0, vb);
+    }
 
     if constexpr (MODE == kAtomicPkF16Phase) {
         // wait until this call's zeros of the tile are in memory (normally already seen)
@@ -376,7 +431,7 @@ __global__ void __launch_bounds__(kWave * WMAX) gemm_kernel(const GemmArgs p)
             __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
-    {
+    if (has_units) {
         float sa[EPU], sb[EPU];
 #pragma unroll
         for (int e = 0; e < EPU; ++e) sa[e] = sb[e] = 0.f;
@@ -678,9 +733,9 @@ constexpr int kMaxDevices = 64;
 // microsecond): far longer than any call takes, short enough that a broken state cannot hang
 // the device.
 constexpr int kSpinLimit = 1 << 17;
-// 64-cycle sleeps between a workgroup learning its call count and its early sample of the tile
-// flag (about 0.45 us at 2.4 GHz).
-static int g_probe_delay = 16;
+// 64-cycle sleeps before a sample of the tile flag (service wave: before every sample; in-wave
+// protocol: between learning the call count and the early sample).
+static int g_probe_delay = 2;
 static DeviceScratch g_scratch[kMaxDevices];
 static std::mutex g_mutex;
 
@@ -822,7 +877,8 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
             return W4A16_ERR_HIP;
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * kWave), lds_bytes, stream, a);
+    const unsigned threads = (unsigned)(waves + (MODE == kAtomicPkF16Service ? 1 : 0)) * kWave;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, stream, a);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -832,7 +888,12 @@ static int launch_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_
     if (waves <= 4) {
         // the tuned shape (128-bit loads, group of 128) knows its group count at compile time
         if constexpr (V == 4 && IPG == 4) {
-            if (a.groups_per_wave == 1) return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
+            if (a.groups_per_wave == 1) {
+                // few registers per wave: the phase protocol gets a wave of its own
+                if constexpr (MODE == kAtomicPkF16Phase)
+                    return launch_bound<V, IPG, kAtomicPkF16Service, 4, 1>(a, waves, lds_bytes, stream);
+                return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
+            }
             return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
         }
         return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
