@@ -79,10 +79,14 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 
 /*
  * Same operations with the tuning knobs exposed (0 = library default for each):
- *   tile_cols  output columns per workgroup: 16, 32 or 64
- *   waves      wavefronts per workgroup, 1..16; they divide the workgroup's k range
+ *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
+ *              waves divide the workgroup's k range), or 256 (SplitK only, group_size 128 or
+ *              256: four waves own a 64-column strip each and share their activations
+ *              through LDS; waves = 4 or 8, i.e. one or two such sets dividing the k range;
+ *              reduce W4A16_REDUCE_ATOMIC_PK_F16 or W4A16_REDUCE_ATOMIC_PK_F16_PHASE)
+ *   waves      wavefronts per workgroup, 1..16
  *   reduce     one of W4A16_REDUCE_* (ignored when split_k == 1)
- * (k / split_k) must be divisible by waves * group_size.
+ * (k / split_k) must be divisible by (number of k parts of a workgroup) * group_size.
  */
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                   int m, int n, int k, int group_size, int split_k,

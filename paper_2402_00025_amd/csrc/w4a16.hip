@@ -5,7 +5,7 @@
 // decomposition".  Algorithm 1 is the SplitK kernel; Section 3 (first paragraph) describes the
 // data-parallel tiling it is compared with; Section 2.1 the atomic reduction.
 #include "w4a16_device.hpp"
-#include "w4a16_shared.hpp"
+#include "w4a16_stream.hpp"
 
 #include <cstdio>
 #include <cstdlib>
@@ -503,30 +503,41 @@ __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ?
     }
 }
 
-// SplitK kernel with the activation slice shared through LDS (see w4a16_shared.hpp).
-// blockIdx.x = tile * split_k + slice: consecutive workgroups go to consecutive compute dies, so
-// with split_k a multiple of 8 every die reads only its own k slices of A.
+// Streaming SplitK kernel: the four column strips of a workgroup share their activations
+// through LDS (see w4a16_stream.hpp).  blockIdx.x = tile * split_k + slice: consecutive
+// workgroups go to consecutive compute dies, so with split_k a multiple of 8 every die reads
+// only its own k slices of A.
 //
-// MODE kDirect       split_k == 1: round once, store.
-// MODE kAtomicPkF16  packed-fp16 atomic adds into a C that a fill kernel zeroed beforehand.
+// MODE kDirect            split_k == 1: round once, store.
+// MODE kAtomicPkF16       packed-fp16 atomic adds into a C that a fill kernel zeroed beforehand.
+// MODE kAtomicPkF16Phase  packed-fp16 atomic adds, C zeroed inside this kernel by the phase
+//                         protocol of gemm_kernel, run by wave 0 of the workgroup.  Its memory
+//                         operations (zero stores of slice 0, load of the call count) are issued
+//                         behind the prologue's loads, so their completion holds back none of
+//                         the data the wave needs first; it publishes after the first round of
+//                         the steady loop, when a load issued after the count has been consumed,
+//                         samples the flag before the last groups and does not join the last
+//                         barrier, behind which all waves add into C, before it has seen it.
 template <int D, int MODE>
-__global__ void __launch_bounds__(512) gemm_shared_kernel(const SharedArgs p)
+__global__ void __launch_bounds__(kWave * 8) gemm_stream_kernel(const StreamArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    constexpr bool kPhase = MODE == kAtomicPkF16Phase;
+    constexpr uint32_t kOutside = 0xFFFFFF00u;
+
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int slice = blockIdx.x % p.split_k;
     const int tile = blockIdx.x / p.split_k;
-    const int strip = wave % p.wn;
-    const int kpart = wave / p.wn;
     const int m = p.m, n = p.n, k = p.k;
     const int G = p.groups_per_wave;
-    const int g_wg = slice * p.wk * G;     // first compute group of the workgroup
-    const int g_begin = g_wg + kpart * G;  // first compute group of this wave
-    const int n0 = (tile * p.wn + strip) * 64;
-    const bool strip_live = n0 < n;        // uniform per wave; a dead strip only joins the barrier
+
+    const int strip = wave & (kStreamStrips - 1);
+    const int kpart = wave / kStreamStrips;
+    const int g_begin = (slice * p.wk + kpart) * G;  // first compute group of this wave
+    const int n0 = (tile * kStreamStrips + strip) * 64;
 
     const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)(k / 128) >> p.param_shift;
@@ -539,115 +550,145 @@ __global__ void __launch_bounds__(512) gemm_shared_kernel(const SharedArgs p)
     tensors.n = n;
     tensors.k = k;
     tensors.param_shift = p.param_shift;
+    const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
 
-    // ---- activation slice -> LDS.  Chunk c = kc * m + row is the 8 halves A[row][k0 + 8 kc ..],
-    // stored at byte 16 c in the slot order of unpack_shift.  The last batch of loads is
-    // followed by the first D groups of weight loads, so the weight stream is already on its way
-    // while the activations are written to LDS.
-    const int chunks = m * p.wk * G * 16;
-    const uint32_t a_soff = (uint32_t)g_wg * 256u;  // 128 k of 2 bytes per compute group
-    constexpr int kBatch = 8;
-    auto chunk_offset = [&](int c) {
-        const int kc = c / m, row = c - kc * m;
-        return ((uint32_t)row * (uint32_t)k + 8u * (uint32_t)kc) * 2u;
-    };
-    int c0 = 0;
-    for (; c0 + kBatch * nthreads < chunks; c0 += kBatch * nthreads) {
-        u32x4_t tmp[kBatch];
+    // this wave's quarter of a chunk: rows 4 strip .. 4 strip + 3, 16 lanes (256 bytes) per row;
+    // rows >= m are not fetched (an offset outside the buffer returns zeros)
+    StreamLane sl;
+    const int prow = 4 * strip + (lane >> 4);
+    sl.a_voff = prow < m ? ((uint32_t)prow * (uint32_t)k + 8u * (uint32_t)(lane & 15)) * 2u : kOutside;
+    sl.a_soff0 = (uint32_t)g_begin * 256u;
+    sl.wslot = chunk_slot_bytes(lane & 15, prow);
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u)
-            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, chunk_offset(c0 + u * nthreads + tid), a_soff, 0);
+    for (int it = 0; it < 4; ++it) sl.roff[it] = chunk_slot_bytes(4 * it + (lane >> 4), lane & 15);
+    sl.ring = lds_raw + kpart * 2 * kChunkBytes;
+
+    // ---- prologue: the first D chunk quarters, then the first D groups of weights (the quarters
+    // come first, so they arrive first); chunk 0 goes to LDS
+    u32x4_t a_in[D];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u)
-            *(half8_t*)(lds_raw + (size_t)(c0 + u * nthreads + tid) * 16) = permute_activations(tmp[u]);
-    }
-    // Last batch: 1..kBatch loads per thread, then the first D groups of weight loads, then the
-    // LDS writes.  Straight-line code per load count (a thread past the end repeats the last
-    // chunk), so the wait before each LDS write counts exactly the loads issued after it and
-    // never waits for the weights.
+    for (int h = 0; h < D; ++h)
+        a_in[h] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff, sl.a_soff0 + (uint32_t)h * 256u, 0);
     WeightRing<D> ring;
-    auto stage_tail = [&](auto nu_tag) {
-        constexpr int NU = decltype(nu_tag)::value;
-        u32x4_t tmp[NU];
-        int cc[NU];
+    ring_prime<D, 0>(ring, lm, tensors, g_begin);
+
+    // ---- phase protocol, first part (wave 0), behind the prologue's loads: zeros of slice 0 (the
+    // lanes of every other wave get offsets outside the buffer), then the workgroup's call count
+    const uint32_t origin = (uint32_t)tile * (kStreamTileCols / 16);
+    uint32_t count = 0;
+    if constexpr (kPhase) {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        // 16-byte units of the tile: m rows x 32 units; n % 8 == 0 keeps a unit inside or outside
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            const int c = c0 + u * nthreads + tid;
-            cc[u] = c < chunks ? c : chunks - 1;
-            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, chunk_offset(cc[u]), a_soff, 0);
+        for (int i = 0; i < 8; ++i) {
+            const int u = lane + kWave * i;
+            const int row = u >> 5, col = tile * kStreamTileCols + 8 * (u & 31);
+            const bool inside = wave == 0 && slice == 0 && row < m && col < n;
+            const uint32_t off = inside ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{0u, 0u, 0u, 0u}, rs_c, off, 0, 16);  // 16 = sc1
         }
-        ring_prime<D, 0>(ring, lm, tensors, g_begin);  // unconditional (a dead strip reads valid columns): no branch
-#pragma unroll
-        for (int u = 0; u < NU; ++u) *(half8_t*)(lds_raw + (size_t)cc[u] * 16) = permute_activations(tmp[u]);
-    };
-    switch ((chunks - c0 + nthreads - 1) / nthreads) {
-    case 1: stage_tail(std::integral_constant<int, 1>{}); break;
-    case 2: stage_tail(std::integral_constant<int, 2>{}); break;
-    case 3: stage_tail(std::integral_constant<int, 3>{}); break;
-    case 4: stage_tail(std::integral_constant<int, 4>{}); break;
-    case 5: stage_tail(std::integral_constant<int, 5>{}); break;
-    case 6: stage_tail(std::integral_constant<int, 6>{}); break;
-    case 7: stage_tail(std::integral_constant<int, 7>{}); break;
-    default: stage_tail(std::integral_constant<int, 8>{}); break;
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        const rsrc_t rs_counts = make_rsrc(p.counts, kPhaseOrigins * (uint32_t)p.split_k * 4u);
+        count = __builtin_amdgcn_raw_buffer_load_b32(
+            rs_counts, wave == 0 ? (origin * (uint32_t)p.split_k + (uint32_t)slice) * 4u : kOutside, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
+
+    *(half8_t*)(sl.ring + sl.wslot) = permute_activations(a_in[0]);
     __syncthreads();
+    u32x4_t a[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(sl.ring + sl.roff[it]);
 
     float4_t acc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const uint32_t magic = magic_1024x2();
 
-    if (strip_live) {
-        // lane's A operand of MFMA step s (within the workgroup's k range): slot (4 s + lane / 16, row)
-        const int mrow = lane & 15;
-        const int arow = mrow < m ? mrow : m - 1;
-        const int a_step_bytes = 64 * m;
-        const char* a_ptr = lds_raw + ((lane >> 4) * m + arow) * 16 + (size_t)kpart * G * 4 * a_step_bytes;
-        u32x4_t a[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(a_ptr + it * a_step_bytes);
-        const uint32_t magic = magic_1024x2();
-        int g = 0;
-        for (; g + D < G; g += D)
-            shared_compute_slots<D, 0, true>(ring, lm, tensors, magic, g_begin + g + D, a_ptr, a_step_bytes, a, acc);
-        shared_compute_slots<D, 0, false>(ring, lm, tensors, magic, 0, a_ptr, a_step_bytes, a, acc);
+    uint32_t now = 0, sample = 0;
+    bool published = !(kPhase && wave == 0);
+    auto publish = [&]() {
+        // the count was issued before weights that have been consumed by now: it has arrived,
+        // and with it the zero stores issued before it have completed
+        now = __builtin_amdgcn_readfirstlane(count) + 1u;
+        if (lane == 0) {
+            p.counts[origin * (uint32_t)p.split_k + (uint32_t)slice] = now;
+            if (slice == 0) __hip_atomic_store(p.flags + origin, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        published = true;
+    };
+    int c = 0;
+    for (; c + D < G; c += D) {
+        stream_groups<D, 0, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        if constexpr (kPhase) {
+            if (!published && c >= D) publish();
+        }
     }
+    if constexpr (kPhase) {
+        if (wave == 0) {
+            if (!published) publish();
+            sample = __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    stream_groups<D, 0, false>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
 
-    // ---- every wave's tile -> LDS (behind the activation slice), then the k parts are added and
-    // the sums leave with consecutive lanes on consecutive column pairs.
-    float* red_all = (float*)(lds_raw + p.a_bytes);
+    // ---- every wave's tile -> LDS (behind the chunks); after the barrier the k parts are added
+    // and the sums leave with consecutive lanes on consecutive column pairs
+    float* red_all = (float*)(lds_raw + p.wk * 2 * kChunkBytes);
     float* red = red_all + (size_t)wave * m * 64;  // [m][64]
-    if (strip_live) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 4 * (lane >> 4) + r;
-            if (row < m) {
-                float4_t v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
-                *(float4_t*)(red + row * 64 + 4 * (lane & 15)) = v;
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * (lane >> 4) + r;
+        if (row < m) *(float4_t*)(red + row * 64 + 4 * (lane & 15)) = float4_t{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+    }
+    if constexpr (kPhase) {
+        if (wave == 0) {
+            // wave 0 holds the barrier until this call's zeros of the tile are in memory
+            bool seen = __builtin_amdgcn_readfirstlane(sample) == now;
+            int polls = 0;
+            while (!seen && polls < p.spin_limit) {
+                for (int i = 0; i < p.probe_delay; ++i) __builtin_amdgcn_s_sleep(1);
+                seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED,
+                                                                        __HIP_MEMORY_SCOPE_AGENT)) == now;
+                ++polls;
             }
+            if (!seen && lane == 0)
+                __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();
-    const int pairs_per_row = p.wn * 32;
-    const int pairs = m * pairs_per_row;
-    for (int e = tid; e < pairs; e += nthreads) {
-        const int row = e / pairs_per_row;
-        const int cp = e - row * pairs_per_row;
-        const int st = cp >> 5;
-        const int c2 = 2 * (cp & 31);
-        const int col = (tile * p.wn + st) * 64 + c2;
-        if (col >= n) continue;
-        float v0 = 0.f, v1 = 0.f;
-        for (int kp = 0; kp < p.wk; ++kp) {
-            const float2 t2 = *(const float2*)(red_all + (size_t)(kp * p.wn + st) * m * 64 + row * 64 + c2);
-            v0 += t2.x;
-            v1 += t2.y;
+    const int units = m * (kStreamTileCols / 2);  // pairs of adjacent columns
+    const int strip_floats = m * 64;
+    const int second_part = (p.wk - 1) * kStreamStrips * strip_floats;
+    const float second_keep = p.wk > 1 ? 1.f : 0.f;
+    for (int u0 = tid; u0 < units; u0 += 4 * nthreads) {
+        float2 v[4];
+        uint32_t off[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = u0 + i * nthreads;
+            const int uc = u < units ? u : u0;
+            const int row = uc >> 7, cp = uc & 127;
+            const int st = cp >> 5, c2 = 2 * (cp & 31);
+            const int col = tile * kStreamTileCols + st * 64 + c2;
+            off[i] = (u < units && col < n) ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            // wk is 1 or 2: the second k part's tile, or (wk == 1) the first one again, left out
+            const float* src = red_all + st * strip_floats + row * 64 + c2;
+            const float2 t0 = *(const float2*)src;
+            const float2 t1 = *(const float2*)(src + second_part);
+            v[i].x = t0.x + second_keep * t1.x;
+            v[i].y = t0.y + second_keep * t1.y;
         }
-        const size_t idx = (size_t)row * n + col;
-        if constexpr (MODE == kDirect) {
-            *(uint32_t*)(p.C + idx) = pack_half2(v0, v1);
-        } else {
-            const half2_t h = {(_Float16)v0, (_Float16)v1};
-            __builtin_amdgcn_global_atomic_fadd_v2f16((__attribute__((address_space(1))) half2_t*)(p.C + idx), h);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (MODE == kDirect) {
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, 0);
+            } else {
+                const half2_t h = {(_Float16)v[i].x, (_Float16)v[i].y};
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(h, rs_c, off[i], 0, 0);
+            }
         }
     }
 }
@@ -736,6 +777,8 @@ constexpr int kSpinLimit = 1 << 17;
 // 64-cycle sleeps before a sample of the tile flag (service wave: before every sample; in-wave
 // protocol: between learning the call count and the early sample).
 static int g_probe_delay = 2;
+// Deepest weight ring (compute groups in flight per wave) the streaming kernel may use.
+static int g_stream_depth = 2;
 static DeviceScratch g_scratch[kMaxDevices];
 static std::mutex g_mutex;
 
@@ -784,6 +827,42 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                      int reduce, Plan* out)
 {
     const int groups = k / group_size;
+    // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
+    // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
+    // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
+    if (!dp && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
+        const bool asked = tile_cols == kStreamTileCols;
+        const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
+        const int sgroups = k / 128;
+        const bool shape_ok = group_size == 128 || group_size == 256;
+        const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
+                               reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
+        int S = split_k;
+        if (S == 0) {
+            // about one workgroup per compute unit, at least two groups per wave
+            S = 1;
+            while (S * 2 <= kPhaseMaxSplit && sgroups % (S * 2) == 0 && sgroups / (S * 2) >= 2 && stiles * S * 2 <= 256)
+                S *= 2;
+        }
+        const bool worth = m >= 8 && (long long)k * n / 2 > (8ll << 20) && stiles * S >= 192;
+        if (asked || (shape_ok && reduce_ok && worth && sgroups % S == 0)) {
+            if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
+            if (waves == 0) waves = kStreamStrips;
+            if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
+            if (S < 1 || sgroups % (S * (waves / kStreamStrips)) != 0) return W4A16_ERR_SPLIT;
+            if (reduce == W4A16_REDUCE_AUTO)
+                reduce = phase_split_ok(S) && (size_t)n <= 16 * (size_t)kPhaseOrigins ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
+                                                                                      : W4A16_REDUCE_ATOMIC_PK_F16;
+            if (S > 1 && reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE &&
+                (!phase_split_ok(S) || (size_t)n > 16 * (size_t)kPhaseOrigins))
+                return W4A16_ERR_UNSUPPORTED;
+            out->split_k = S;
+            out->tile_cols = kStreamTileCols;
+            out->waves = waves;
+            out->reduce = reduce;
+            return W4A16_OK;
+        }
+    }
     if (tile_cols == 0) {
         tile_cols = 64;
         if (dp) {
@@ -928,73 +1007,93 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
     }
 }
 
-// ---- launch of the shared-activation SplitK kernel
+// ---- launch of the streaming SplitK kernel
 template <int D, int MODE>
-static int launch_shared_one(const SharedArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
+static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_shared_kernel<D, MODE>;
+    auto kern = gemm_stream_kernel<D, MODE>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
             return W4A16_ERR_HIP;
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * kWave), lds_bytes, stream, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
 template <int D>
-static int launch_shared_mode(const SharedArgs& a, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+static int launch_stream_mode(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
-    if (mode == kDirect) return launch_shared_one<D, kDirect>(a, waves, lds_bytes, stream);
-    return launch_shared_one<D, kAtomicPkF16>(a, waves, lds_bytes, stream);
+    if (mode == kDirect) return launch_stream_one<D, kDirect>(a, lds_bytes, stream);
+    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16>(a, lds_bytes, stream);
+    return launch_stream_one<D, kAtomicPkF16Phase>(a, lds_bytes, stream);
 }
 
-// tile_cols = 64 * wn (128 or 256), waves = wn * wk (at most 8).  group_size 128 or 256.
-static int run_shared(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
-                      int n, int k, int group_size, int split_k, int tile_cols, int waves, int reduce,
-                      hipStream_t stream)
+static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
+                          bool want_phase, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
+                          uint32_t** phase);
+
+// tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
+static int run_stream(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                      int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream)
 {
     if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
-    const int wn = tile_cols / 64;
-    if (waves == 0) waves = wn;
-    if (waves < wn || waves > 8 || waves % wn != 0) return W4A16_ERR_UNSUPPORTED;
-    const int wk = waves / wn;
+    if (waves == 0) waves = kStreamStrips;
+    if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
+    const int wk = waves / kStreamStrips;
     const int groups = k / 128;
     if (split_k < 1 || groups % (split_k * wk) != 0) return W4A16_ERR_SPLIT;
-    if (reduce == W4A16_REDUCE_AUTO) reduce = W4A16_REDUCE_ATOMIC_PK_F16;
-    if (reduce != W4A16_REDUCE_ATOMIC_PK_F16) return W4A16_ERR_UNSUPPORTED;
-    SharedArgs a;
+    if (reduce == W4A16_REDUCE_AUTO)
+        reduce = phase_split_ok(split_k) && (size_t)n <= 16 * (size_t)kPhaseOrigins ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
+                                                                                  : W4A16_REDUCE_ATOMIC_PK_F16;
+    if (reduce != W4A16_REDUCE_ATOMIC_PK_F16 && reduce != W4A16_REDUCE_ATOMIC_PK_F16_PHASE)
+        return W4A16_ERR_UNSUPPORTED;
+    StreamArgs a;
     a.A = (const _Float16*)A;
     a.qweight = (const uint32_t*)qweight;
     a.scales = (const _Float16*)scales;
     a.qzeros = (const uint32_t*)qzeros;
     a.C = (_Float16*)C;
-    a.flags = nullptr;
+    a.flags = a.counts = a.errors = nullptr;
     a.m = m;
     a.n = n;
     a.k = k;
-    a.tiles = (n + tile_cols - 1) / tile_cols;
+    a.tiles = (n + kStreamTileCols - 1) / kStreamTileCols;
     a.split_k = split_k;
-    a.wn = wn;
     a.wk = wk;
     a.groups_per_wave = groups / (split_k * wk);
     a.param_shift = group_size == 256 ? 1 : 0;
-    a.a_bytes = m * wk * a.groups_per_wave * 128 * 2;
-    a.spin_limit = 0;
-    const size_t lds_bytes = (size_t)a.a_bytes + (size_t)waves * m * 64 * 4;
-    if (lds_bytes > 160 * 1024) return W4A16_ERR_UNSUPPORTED;
-    const int mode = split_k > 1 ? kAtomicPkF16 : kDirect;
-    if (mode == kAtomicPkF16) {
-        const size_t words = (size_t)m * n / 2;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
-                           (uint32_t*)C, words);
-        if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    a.spin_limit = kSpinLimit;
+    a.probe_delay = g_probe_delay;
+    const size_t lds_bytes = (size_t)wk * 2 * kChunkBytes + (size_t)waves * m * 64 * 4;
+    int mode = kDirect;
+    if (split_k > 1) {
+        if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) {
+            if (!phase_split_ok(split_k) || (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
+            float *sums = nullptr, *partials = nullptr;
+            uint64_t* fixed = nullptr;
+            uint32_t *tickets = nullptr, *phase = nullptr;
+            const int rc = ensure_scratch(0, 0, 0, 0, true, &sums, &partials, &fixed, &tickets, &phase);
+            if (rc != W4A16_OK) return rc;
+            int j = 0;
+            while ((1 << j) < split_k) ++j;
+            a.flags = phase + phase_flags_offset(j);
+            a.counts = phase + phase_counts_offset(j);
+            a.errors = phase + phase_errors_offset();
+            mode = kAtomicPkF16Phase;
+        } else {
+            const size_t words = (size_t)m * n / 2;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                               (uint32_t*)C, words);
+            if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+            mode = kAtomicPkF16;
+        }
     }
     const int G = a.groups_per_wave;
-    if (G % 4 == 0) return launch_shared_mode<4>(a, waves, lds_bytes, mode, stream);
-    if (G % 2 == 0) return launch_shared_mode<2>(a, waves, lds_bytes, mode, stream);
-    return launch_shared_mode<1>(a, waves, lds_bytes, mode, stream);
+    if (G % 4 == 0 && g_stream_depth >= 4) return launch_stream_mode<4>(a, lds_bytes, mode, stream);
+    if (G % 2 == 0 && g_stream_depth >= 2) return launch_stream_mode<2>(a, lds_bytes, mode, stream);
+    return launch_stream_mode<1>(a, lds_bytes, mode, stream);
 }
 
 static void read_tuning_env()
@@ -1003,6 +1102,7 @@ static void read_tuning_env()
     if (done) return;
     done = true;
     if (const char* e = getenv("W4A16_PROBE_DELAY")) g_probe_delay = atoi(e);
+    if (const char* e = getenv("W4A16_STREAM_DEPTH")) g_stream_depth = atoi(e);
 }
 
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
@@ -1026,14 +1126,14 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         }
         return W4A16_OK;
     }
-    if (!dp && (tile_cols == 128 || tile_cols == 256)) {
-        if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
-        return run_shared(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, tile_cols, waves, reduce,
-                          (hipStream_t)stream_v);
-    }
     Plan plan;
     rc = make_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce, &plan);
     if (rc != W4A16_OK) return rc;
+    if (plan.tile_cols == kStreamTileCols) {
+        if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+        return run_stream(A, qweight, scales, qzeros, C, m, n, k, group_size, plan.split_k, plan.waves, plan.reduce,
+                          (hipStream_t)stream_v);
+    }
 
     hipStream_t stream = (hipStream_t)stream_v;
     const int ipg = group_size >= 128 ? 4 : group_size / 32;  // MFMA steps (32 k each) per compute group

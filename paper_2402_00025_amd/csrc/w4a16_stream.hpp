@@ -1,0 +1,151 @@
+// Device routines of the streaming SplitK kernel, whose workgroup shares its activations through
+// LDS (gfx950, wave64).
+//
+// Paper: "Accelerating a Triton Fused Kernel for W4A16 Quantized Inference with SplitK work
+// decomposition", Algorithm 1: every program owns an output tile and a 1/split_k share of k,
+// loads and dequantises tiles of both operands, multiplies with an fp32 accumulator and adds
+// its partial tile into C.
+//
+// Workgroup = 4 x wk wavefronts.  The four waves of one k part own adjacent 64-column strips
+// (a 256-column tile) and walk the same k range, one quantisation group (128 k) at a time, so
+// they need the same activations A[0:16, 128 k]: a 4 KiB chunk.  Each of the four waves fetches
+// a quarter of every chunk (four rows, full cache lines), reorders it to the field order of the
+// unpack and writes it to LDS in the layout of the MFMA A operand; after the workgroup's barrier
+// every wave reads its operands from there.  That divides the activation traffic through the
+// vector memory pipe by four; what remains is a per-group barrier.
+//
+// A compute unit returns vector-memory data in issue order, so a load issued now arrives only
+// after the D groups of weight loads that are already in flight.  A chunk quarter is therefore
+// requested D groups ahead (into a register ring of D quarters) and written to LDS at the end of
+// the group before the one that uses it; by then it has long arrived and the wait costs nothing.
+// LDS holds two chunks per k part (the one being read and the next one).
+#pragma once
+#include "w4a16_device.hpp"
+
+namespace w4a16 {
+
+struct StreamArgs {
+    const _Float16* A;
+    const uint32_t* qweight;
+    const _Float16* scales;
+    const uint32_t* qzeros;
+    _Float16* C;
+    uint32_t* flags;      // phase protocol: zeroings so far, per tile origin (n0 / 16)
+    uint32_t* counts;     // phase protocol: calls so far, per (tile origin, slice)
+    uint32_t* errors;     // phase protocol: count of waits that ran out
+    int m, n, k;
+    int tiles;            // 256-column workgroup tiles = ceil(n / 256)
+    int split_k;
+    int wk;               // k parts per workgroup; working waves = 4 * wk
+    int groups_per_wave;  // compute groups (128 consecutive k) per wave; a multiple of D
+    int param_shift;      // log2(compute groups per quantisation group)
+    int spin_limit;       // phase protocol: bound on samples of a flag
+    int probe_delay;      // phase protocol: 64-cycle sleeps before a sample
+};
+
+constexpr int kStreamStrips = 4;
+constexpr int kStreamTileCols = 64 * kStreamStrips;
+constexpr int kChunkBytes = 16 * 128 * 2;  // one activation chunk in LDS: 16 rows x 128 k, fp16
+
+// LDS layout of a chunk: one 16-byte slot per (kc = 8 consecutive k, row): slot kc * 16 + (row ^ kc).
+// The xor makes both access patterns conflict-free: a writing wave has, in every 16 lanes, one
+// row and kc = 0..15; a reading wave has one kc and rows 0..15.
+__device__ __forceinline__ int chunk_slot_bytes(int kc, int row) { return (kc * 16 + (row ^ kc)) * 16; }
+
+template <int D>
+struct WeightRing {
+    Words<4> w[D][4];
+    ParamRegs<4> par[D];
+};
+
+template <int D, int H>
+__device__ __forceinline__ void ring_issue_group(WeightRing<D>& ring, const LaneMap& lm, const Tensors& t, int gi)
+{
+    issue_params<4>(ring.par[H], lm, t, gi);
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+        ring.w[H][it].load(t.qweight, lm.off_w, ((uint32_t)gi * 4u + it) * 16u * (uint32_t)t.n);
+}
+
+template <int D, int H>
+__device__ __forceinline__ void ring_prime(WeightRing<D>& ring, const LaneMap& lm, const Tensors& t, int g_begin)
+{
+    if constexpr (H < D) {
+        ring_issue_group<D, H>(ring, lm, t, g_begin + H);
+        ring_prime<D, H + 1>(ring, lm, t, g_begin);
+    }
+}
+
+// What stays fixed for a lane while it streams: where its quarter of a chunk comes from and goes
+// to, and where its MFMA operands of the four steps of a group lie in a chunk.
+struct StreamLane {
+    uint32_t a_voff;   // byte offset of its 16 bytes of A inside a chunk quarter's row, or outside the buffer
+    uint32_t a_soff0;  // byte offset of chunk 0 of this wave's k range
+    int wslot;         // LDS byte offset of the slot it writes
+    int roff[4];       // LDS byte offsets of the slots it reads, per MFMA step
+    char* ring;        // the k part's two chunks in LDS
+};
+
+// One compute group (128 k) of a wave out of ring slot H; `cc` is its index inside the wave's
+// range.  REFILL: request the weights and the chunk quarter of group cc + D.  NEXT: there is a
+// group cc + 1: publish its chunk quarter, meet the other waves, fetch the next operands.
+template <int D, int H, bool REFILL, bool NEXT>
+__device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in)[D], u32x4_t (&a)[4],
+                                             const StreamLane& sl, const LaneMap& lm, const Tensors& t,
+                                             uint32_t magic, int cc, int g_begin, float4_t (&acc)[4])
+{
+    ZeroConst zc[4];
+    float sc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
+        sc[j] = scale_of<4>(ring.par[H].s, j);
+    }
+    if constexpr (REFILL) {
+        __builtin_amdgcn_sched_barrier(0);
+        issue_params<4>(ring.par[H], lm, t, g_begin + cc + D);
+        a_in[H] = __builtin_amdgcn_raw_buffer_load_b128(t.A, sl.a_voff, sl.a_soff0 + (uint32_t)(cc + D) * 256u, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float4_t tile[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tile[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const half8_t a8 = __builtin_bit_cast(half8_t, a[it]);
+        half8_t b8[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b8[j] = unpack_shift(ring.w[H][it].v[j], zc[j], magic);
+        if constexpr (REFILL) {
+            __builtin_amdgcn_sched_barrier(0);
+            ring.w[H][it].load(t.qweight, lm.off_w, ((uint32_t)(g_begin + cc + D) * 4u + it) * 16u * (uint32_t)t.n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tile[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8[j], tile[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] += sc[j] * tile[j];
+    if constexpr (NEXT) {
+        char* buf = sl.ring + ((cc + 1) & 1) * kChunkBytes;
+        *(half8_t*)(buf + sl.wslot) = permute_activations(a_in[(H + 1) % D]);
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(buf + sl.roff[it]);
+    }
+}
+
+template <int D, int H, bool REFILL>
+__device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_in)[D], u32x4_t (&a)[4],
+                                              const StreamLane& sl, const LaneMap& lm, const Tensors& t,
+                                              uint32_t magic, int c0, int g_begin, float4_t (&acc)[4])
+{
+    if constexpr (H < D) {
+        // the last group of the wave has no successor
+        constexpr bool kNext = REFILL || (H + 1 < D);
+        stream_group<D, H, REFILL, kNext>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc);
+        stream_groups<D, H + 1, REFILL>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc);
+    }
+}
+
+}  // namespace w4a16

@@ -258,40 +258,44 @@ def test_phase_mode_call_sequences(oracle):
     assert b.w4a16_phase_timeouts() == 0
 
 
-# ------------------------------------------------------------------ shared-activation SplitK kernel
-SHARED_SMALL = [
-    # m, n, k, g, split_k, tile_cols (64 * column strips), waves (strips * k parts)
-    (16, 256, 512, 128, 1, 256, 4),     # one group per wave, direct store
-    (16, 256, 512, 128, 4, 256, 4),
-    (16, 512, 1024, 128, 2, 256, 8),    # two k parts added in LDS
-    (1, 256, 1024, 128, 2, 256, 4),
-    (3, 328, 1024, 128, 4, 256, 4),     # ragged: second tile has one live strip and a half
-    (5, 200, 1024, 128, 2, 128, 4),     # 2 strips x 2 k parts, overhanging strip
-    (16, 72, 2048, 128, 2, 128, 2),     # overhanging strip; eight groups per wave (ring depth 4, steady loop)
-    (7, 136, 4096, 128, 2, 128, 2),     # 16 groups per wave: several steady iterations
-    (16, 264, 1536, 128, 2, 256, 4),    # 6 groups per wave: ring depth 2
-    (9, 192, 1024, 256, 2, 128, 4),     # group_size 256
-    (16, 192, 2048, 128, 1, 256, 8),    # direct store with k parts
-    (4, 512, 8192, 128, 1, 256, 4),     # long activation slice: two staging batches, more than 64 KiB of LDS
-    (16, 512, 4096, 128, 2, 256, 4),    # 2048 k per workgroup at 16 rows: 64 KiB slice
+# ------------------------------------------------------------------ streaming SplitK kernel (activations shared through LDS)
+STREAM_SMALL = [
+    # m, n, k, g, split_k, waves (4 per k part), reduce
+    (16, 256, 512, 128, 1, 4, 0),      # four groups per wave, ring depth 4, direct store
+    (16, 256, 512, 128, 4, 4, 0),      # one group per wave
+    (16, 512, 1024, 128, 2, 8, 0),     # two k parts added in LDS, two groups per wave
+    (1, 256, 1024, 128, 2, 4, 0),
+    (3, 328, 1024, 128, 4, 4, 0),      # ragged: second tile has one live strip and an eighth
+    (5, 200, 1024, 128, 2, 8, 2),      # fill kernel + atomics, overhanging strip
+    (16, 72, 2048, 128, 2, 4, 0),      # eight groups per wave: steady loop
+    (7, 136, 4096, 128, 2, 4, 5),      # 16 groups per wave: several steady iterations
+    (16, 264, 1536, 128, 2, 4, 0),     # six groups per wave: ring depth 2
+    (13, 264, 1536, 128, 4, 4, 0),     # three groups per wave: ring depth 1
+    (9, 192, 1024, 256, 2, 8, 0),      # group_size 256
+    (16, 192, 2048, 128, 1, 8, 0),     # direct store with k parts, dead strip
+    (4, 512, 8192, 128, 1, 4, 0),      # 64 groups per wave
+    (16, 512, 4096, 128, 8, 4, 5),
+    (16, 1024, 2048, 128, 16, 4, 5),   # one group per wave, 16 slices
 ]
 
 
-@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves", SHARED_SMALL)
-def test_shared_kernel_small_shapes(oracle, m, n, k, g, split_k, tile_cols, waves):
+@pytest.mark.parametrize("m,n,k,g,split_k,waves,reduce", STREAM_SMALL)
+def test_stream_kernel_small_shapes(oracle, m, n, k, g, split_k, waves, reduce):
     A, qw, s, qz = random_case(m, n, k, g, seed=300 + m + n)
     Cref, _ = oracle.gemm(A, qw, s, qz, g)
     p = DeviceProblem(A, qw, s, qz, g)
-    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
-    assert_parity(p.result(), Cref, f"shared m={m} n={n} k={k} S={split_k} tile={tile_cols} waves={waves}")
-    b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+    b.w4a16_gemm_ex(*p.args(), split_k, 256, waves, reduce)
+    assert_parity(p.result(), Cref, f"stream m={m} n={n} k={k} S={split_k} waves={waves} reduce={reduce}")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_ex(*p.args(), split_k, 256, waves, reduce)
     assert_parity(p.result(), Cref, "second call")
+    assert b.w4a16_phase_timeouts() == 0
 
 
-@pytest.mark.parametrize("split_k,tile_cols,waves", [(1, 256, 4), (4, 256, 4), (2, 128, 4), (2, 256, 8)])
-def test_shared_kernel_one_hot_rows_bit_exact(split_k, tile_cols, waves):
+@pytest.mark.parametrize("split_k,waves", [(1, 4), (4, 4), (2, 8), (8, 4)])
+def test_stream_kernel_one_hot_rows_bit_exact(split_k, waves):
     """Same single-term argument as test_one_hot_rows_bit_exact, through the LDS-staged
-    activation operand: pins its slot order, the k parts and the slice boundaries."""
+    activation operand: pins its slot order, the chunk ring, the k parts and the slice boundaries."""
     m, n, k, g = 16, 328, 1024, 128
     _, qw, s, qz = random_case(m, n, k, g, seed=45)
     W = np_dense_weight(qw, s, qz, g)
@@ -303,7 +307,7 @@ def test_shared_kernel_one_hot_rows_bit_exact(split_k, tile_cols, waves):
         for i, r in enumerate(rows):
             A[i, r] = 1.0
         p.A.copy_(torch.from_numpy(A))
-        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+        b.w4a16_gemm_ex(*p.args(), split_k, 256, waves, 0)
         got = p.result()
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
 
