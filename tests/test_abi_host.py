@@ -88,8 +88,12 @@ def test_plan_is_consistent():
                 pl = b.w4a16_plan(m, nk, nk, 128, dp=dp)
                 groups = nk // 128
                 assert groups % pl["split_k"] == 0
-                assert (groups // pl["split_k"]) % pl["waves"] == 0
-                assert pl["tile_cols"] in (16, 32, 64) and 1 <= pl["waves"] <= 16
+                assert pl["tile_cols"] in (16, 32, 64, 256) and 1 <= pl["waves"] <= 16
+                # k parts of a workgroup: all its waves, or (256-column tiles) sets of four
+                kparts = pl["waves"] // 4 if pl["tile_cols"] == 256 else pl["waves"]
+                assert (groups // pl["split_k"]) % kparts == 0
+                if pl["tile_cols"] == 256:
+                    assert not dp and m >= 8 and nk >= 8192
                 if dp:
                     assert pl["split_k"] == 1
     # a requested split is kept
