@@ -13,6 +13,7 @@ HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     "-munsafe-fp-atomics",                                     # hardware fp32 / packed-fp16 atomic adds
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no v_pk_*_f32
+    "-mllvm", "-amdgpu-kernarg-preload-count=14",                # leading kernel arguments arrive in SGPRs
     "-Wall", "-Wno-unused-function",
 ]
 

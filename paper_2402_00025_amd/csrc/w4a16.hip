@@ -17,18 +17,14 @@
 namespace w4a16 {
 
 struct GemmArgs {
+    // what every wave needs before its first load, packed at the front so that it arrives with
+    // one batch of scalar loads
     const _Float16* A;
     const uint32_t* qweight;
     const _Float16* scales;
     const uint32_t* qzeros;
     _Float16* C;
     float* scratch;     // split-k: fp32 sums [16, n] (atomic) or partial tiles [split_k, m, n] (workspace)
-    uint32_t* tickets;  // split-k: one arrival counter per column tile
-    uint32_t* flags;    // phase mode: zeroings so far, per tile origin
-    uint32_t* counts;   // phase mode: calls so far, per (tile origin, slice)
-    uint32_t* errors;   // phase mode: count of waits that ran out
-    int spin_limit;     // phase mode: bound on polls of a flag
-    int probe_delay;    // phase mode: 64-cycle sleeps before the early sample of the flag
     int m, n, k;
     int tiles;            // column tiles = ceil(n / (16 V))
     int split_k;
@@ -36,6 +32,13 @@ struct GemmArgs {
     int groups_per_wave;  // groups_per_block / waves
     int param_shift;      // log2(compute groups per quantisation group)
     int lds_wave_bytes;   // LDS region of one wave
+    int waves;            // working waves per workgroup (the launch has one more in service mode)
+    int spin_limit;     // phase mode: bound on polls of a flag
+    int probe_delay;    // phase mode: 64-cycle sleeps before the early sample of the flag
+    uint32_t* tickets;  // split-k: one arrival counter per column tile
+    uint32_t* flags;    // phase mode: zeroings so far, per tile origin
+    uint32_t* counts;   // phase mode: calls so far, per (tile origin, slice)
+    uint32_t* errors;   // phase mode: count of waits that ran out
 };
 
 enum : int {
@@ -144,14 +147,14 @@ constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers:
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
 template <int V, int IPG, int MODE, int WMAX, int GC>
-__global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0))) gemm_kernel(const GemmArgs p)
+__device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V;
     constexpr bool kService = MODE == kAtomicPkF16Service;
 
     const int tid = threadIdx.x;
-    const int nthreads = blockDim.x - (kService ? kWave : 0);  // threads of the working waves
+    const int nthreads = p.waves * kWave;  // threads of the working waves (not read from the launch: an argument arrives with the others)
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // uniform: keeps offsets scalar
     const int waves = nthreads / kWave;
@@ -503,6 +506,55 @@ __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ?
     }
 }
 
+// Kernel entry.  The first 14 dwords of the argument list (five pointers, four integers) are
+// what a wave needs before it can issue its first load; the build asks the compiler to have
+// them preloaded into scalar registers at wave launch (kernarg preload), so that no round trip
+// to the kernarg segment (about 0.3 us) precedes the loads.  Everything else comes in `rest`
+// and is fetched by one batch of scalar loads while the first vector loads are in flight.
+//   packed = m | param_shift << 5 | waves << 7 | groups_per_wave << 12
+struct GemmRest {
+    float* scratch;
+    uint32_t* tickets;
+    uint32_t* flags;
+    uint32_t* counts;
+    uint32_t* errors;
+    int split_k;
+    int lds_wave_bytes;
+    int spin_limit;
+    int probe_delay;
+};
+
+template <int V, int IPG, int MODE, int WMAX, int GC>
+__global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0)))
+gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, _Float16* C,
+            int packed, int n, int k, int tiles, const GemmRest rest)
+{
+    GemmArgs p;
+    p.A = A;
+    p.qweight = qweight;
+    p.scales = scales;
+    p.qzeros = qzeros;
+    p.C = C;
+    p.m = packed & 31;
+    p.param_shift = (packed >> 5) & 3;
+    p.waves = (packed >> 7) & 31;
+    p.groups_per_wave = (int)((unsigned)packed >> 12);
+    p.groups_per_block = p.groups_per_wave * p.waves;
+    p.n = n;
+    p.k = k;
+    p.tiles = tiles;
+    p.scratch = rest.scratch;
+    p.tickets = rest.tickets;
+    p.flags = rest.flags;
+    p.counts = rest.counts;
+    p.errors = rest.errors;
+    p.split_k = rest.split_k;
+    p.lds_wave_bytes = rest.lds_wave_bytes;
+    p.spin_limit = rest.spin_limit;
+    p.probe_delay = rest.probe_delay;
+    gemm_body<V, IPG, MODE, WMAX, GC>(p);
+}
+
 // Streaming SplitK kernel: the four column strips of a workgroup share their activations
 // through LDS (see w4a16_stream.hpp).  blockIdx.x = tile * split_k + slice: consecutive
 // workgroups go to consecutive compute dies, so with split_k a multiple of 8 every die reads
@@ -519,14 +571,14 @@ __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ?
 //                         samples the flag before the last groups and does not join the last
 //                         barrier, behind which all waves add into C, before it has seen it.
 template <int D, int MODE>
-__global__ void __launch_bounds__(kWave * 8) gemm_stream_kernel(const StreamArgs p)
+__device__ __forceinline__ void stream_body(const StreamArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr bool kPhase = MODE == kAtomicPkF16Phase;
     constexpr uint32_t kOutside = 0xFFFFFF00u;
 
     const int tid = threadIdx.x;
-    const int nthreads = blockDim.x;
+    const int nthreads = kStreamStrips * p.wk * kWave;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int slice = blockIdx.x % p.split_k;
@@ -563,12 +615,18 @@ __global__ void __launch_bounds__(kWave * 8) gemm_stream_kernel(const StreamArgs
     for (int it = 0; it < 4; ++it) sl.roff[it] = chunk_slot_bytes(4 * it + (lane >> 4), lane & 15);
     sl.ring = lds_raw + kpart * 2 * kChunkBytes;
 
-    // ---- prologue: the first D chunk quarters, then the first D groups of weights (the quarters
-    // come first, so they arrive first); chunk 0 goes to LDS
+    // ---- prologue: the first D chunk quarters, then the first D groups of weights; chunk 0 goes
+    // to LDS.  The compute unit returns the loads of all its waves in one issue order, and
+    // nobody can start before all four quarters of chunk 0 are there: the barrier between the
+    // two kinds of loads keeps every quarter ahead of every weight load of the workgroup
+    // (otherwise the last wave's quarter queues behind the other waves' weights, tens of KiB).
     u32x4_t a_in[D];
 #pragma unroll
     for (int h = 0; h < D; ++h)
         a_in[h] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff, sl.a_soff0 + (uint32_t)h * 256u, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
     WeightRing<D> ring;
     ring_prime<D, 0>(ring, lm, tensors, g_begin);
 
@@ -691,6 +749,43 @@ __global__ void __launch_bounds__(kWave * 8) gemm_stream_kernel(const StreamArgs
             }
         }
     }
+}
+
+// Kernel entry of the streaming kernel; the leading 14 dwords are preloaded as for gemm_kernel.
+//   packed = m | param_shift << 5 | wk << 7 | groups_per_wave << 12
+struct StreamRest {
+    uint32_t* flags;
+    uint32_t* counts;
+    uint32_t* errors;
+    int spin_limit;
+    int probe_delay;
+};
+
+template <int D, int MODE>
+__global__ void __launch_bounds__(kWave * 8)
+gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
+                   _Float16* C, int packed, int n, int k, int split_k, const StreamRest rest)
+{
+    StreamArgs p;
+    p.A = A;
+    p.qweight = qweight;
+    p.scales = scales;
+    p.qzeros = qzeros;
+    p.C = C;
+    p.m = packed & 31;
+    p.param_shift = (packed >> 5) & 3;
+    p.wk = (packed >> 7) & 31;
+    p.groups_per_wave = (int)((unsigned)packed >> 12);
+    p.n = n;
+    p.k = k;
+    p.split_k = split_k;
+    p.tiles = 0;  // only the launch needs it
+    p.flags = rest.flags;
+    p.counts = rest.counts;
+    p.errors = rest.errors;
+    p.spin_limit = rest.spin_limit;
+    p.probe_delay = rest.probe_delay;
+    stream_body<D, MODE>(p);
 }
 
 // C <- 0 for the packed-fp16 atomic mode (a kernel, not a memset, so the call can be captured
@@ -957,7 +1052,20 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
     const unsigned threads = (unsigned)(waves + (MODE == kAtomicPkF16Service ? 1 : 0)) * kWave;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, stream, a);
+    if (a.m > 31 || a.param_shift > 3 || a.waves > 31 || a.groups_per_wave >= (1 << 20)) return W4A16_ERR_UNSUPPORTED;
+    const int packed = a.m | a.param_shift << 5 | a.waves << 7 | (int)((unsigned)a.groups_per_wave << 12);
+    GemmRest rest;
+    rest.scratch = a.scratch;
+    rest.tickets = a.tickets;
+    rest.flags = a.flags;
+    rest.counts = a.counts;
+    rest.errors = a.errors;
+    rest.split_k = a.split_k;
+    rest.lds_wave_bytes = a.lds_wave_bytes;
+    rest.spin_limit = a.spin_limit;
+    rest.probe_delay = a.probe_delay;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, stream, a.A, a.qweight, a.scales, a.qzeros, a.C,
+                       packed, a.n, a.k, a.tiles, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -1018,7 +1126,16 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
             return W4A16_ERR_HIP;
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a);
+    if (a.m > 31 || a.groups_per_wave >= (1 << 20)) return W4A16_ERR_UNSUPPORTED;
+    const int packed = a.m | a.param_shift << 5 | a.wk << 7 | (int)((unsigned)a.groups_per_wave << 12);
+    StreamRest rest;
+    rest.flags = a.flags;
+    rest.counts = a.counts;
+    rest.errors = a.errors;
+    rest.spin_limit = a.spin_limit;
+    rest.probe_delay = a.probe_delay;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a.A,
+                       a.qweight, a.scales, a.qzeros, a.C, packed, a.n, a.k, a.split_k, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -1155,6 +1272,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     a.split_k = plan.split_k;
     a.groups_per_block = (k / (32 * ipg)) / plan.split_k;
     a.groups_per_wave = a.groups_per_block / plan.waves;
+    a.waves = plan.waves;
     a.param_shift = param_shift;
     // LDS: 16 bytes for the phase word, then one [m, tile_cols] fp32 tile per wave, for the sum
     // over the workgroup's waves
