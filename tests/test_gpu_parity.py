@@ -258,6 +258,50 @@ def test_phase_mode_call_sequences(oracle):
     assert b.w4a16_phase_timeouts() == 0
 
 
+def test_hip_graph_replays(oracle):
+    """Calls captured in a HIP graph and replayed: the split-k state the library keeps between
+    calls (per-tile flags and counts, fixed-point words, tickets) must come out right on every
+    replay, also with eager calls of other shapes on the same tiles between the replays."""
+    import torch
+    cases = [
+        # m, n, k, split_k, tile_cols, waves, reduce
+        (16, 512, 1024, 8, 64, 1, b.REDUCE_ATOMIC_PK_F16_PHASE),   # one group per wave: service wavefront
+        (16, 512, 2048, 4, 64, 2, b.REDUCE_ATOMIC_PK_F16_PHASE),   # in-wave protocol
+        (9, 520, 2048, 4, 256, 4, b.REDUCE_ATOMIC_PK_F16_PHASE),   # streaming kernel
+        (3, 512, 1024, 4, 64, 2, b.REDUCE_ATOMIC_FIXED),
+        (16, 512, 1024, 4, 64, 2, b.REDUCE_ATOMIC_PK_F16),         # fill kernel + atomics
+        (16, 512, 1024, 2, 64, 2, b.REDUCE_ATOMIC_F32),
+    ]
+    probs = []
+    for (m, n, k, S, tc, wv, red) in cases:
+        A, qw, s, qz = random_case(m, n, k, 128, seed=700 + m + k + S)
+        Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+        probs.append((DeviceProblem(A, qw, s, qz, 128), Cref, S, tc, wv, red))
+    other = DeviceProblem(*random_case(16, 512, 2048, 128, seed=777), 128)
+    for (p, _, S, tc, wv, red) in probs:   # eager warm-up: scratch allocation happens outside the capture
+        b.w4a16_gemm_ex(*p.args(), S, tc, wv, red)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for (p, _, S, tc, wv, red) in probs:
+            b.w4a16_gemm_ex(*p.args(), S, tc, wv, red, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        for (p, *_rest) in probs:
+            p.C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for (p, Cref, S, tc, wv, red) in probs:
+            assert_parity(p.C.cpu().numpy(), Cref, f"replay {rep}: S={S} tile={tc} waves={wv} reduce={red}")
+        # eager work between replays, on the same tiles with other split factors
+        b.w4a16_gemm_ex(*other.args(), 8, 64, 2, b.REDUCE_ATOMIC_PK_F16_PHASE)
+        b.w4a16_gemm_ex(*other.args(), 4, 256, 4, b.REDUCE_ATOMIC_PK_F16_PHASE)
+        torch.cuda.synchronize()
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ streaming SplitK kernel (activations shared through LDS)
 STREAM_SMALL = [
     # m, n, k, g, split_k, waves (4 per k part), reduce
