@@ -717,27 +717,34 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
         }
     }
     __syncthreads();
-    const int units = m * (kStreamTileCols / 2);  // pairs of adjacent columns
+    // A thread keeps one pair of adjacent columns (cp = tid % 128: strip cp / 32, columns
+    // 2 (cp % 32) ..) and walks down the rows nthreads / 128 at a time, so per row it needs one
+    // LDS read per k part, one conversion and one add whose address advances by a constant;
+    // consecutive lanes sit on consecutive pairs (an atomic instruction touches the fewest cache
+    // lines).  Four rows are in flight together; rows >= m and columns >= n get offsets outside
+    // the buffer, which the hardware drops.
+    const int cp = tid & 127;
+    const int st = cp >> 5, c2 = 2 * (cp & 31);
+    const int col = tile * kStreamTileCols + st * 64 + c2;
+    const int rows_per_pass = nthreads >> 7;
     const int strip_floats = m * 64;
-    const int second_part = (p.wk - 1) * kStreamStrips * strip_floats;
-    const float second_keep = p.wk > 1 ? 1.f : 0.f;
-    for (int u0 = tid; u0 < units; u0 += 4 * nthreads) {
+    const float* src0 = red_all + st * strip_floats + c2;
+    const int second_part = (p.wk - 1) * kStreamStrips * strip_floats;  // wk is 1 or 2
+    const bool col_ok = col < n;
+    for (int row0 = tid >> 7; row0 < m; row0 += 4 * rows_per_pass) {
         float2 v[4];
         uint32_t off[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int u = u0 + i * nthreads;
-            const int uc = u < units ? u : u0;
-            const int row = uc >> 7, cp = uc & 127;
-            const int st = cp >> 5, c2 = 2 * (cp & 31);
-            const int col = tile * kStreamTileCols + st * 64 + c2;
-            off[i] = (u < units && col < n) ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
-            // wk is 1 or 2: the second k part's tile, or (wk == 1) the first one again, left out
-            const float* src = red_all + st * strip_floats + row * 64 + c2;
-            const float2 t0 = *(const float2*)src;
-            const float2 t1 = *(const float2*)(src + second_part);
-            v[i].x = t0.x + second_keep * t1.x;
-            v[i].y = t0.y + second_keep * t1.y;
+            const int row = row0 + i * rows_per_pass;
+            const int rc = row < m ? row : row0;
+            off[i] = (row < m && col_ok) ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            v[i] = *(const float2*)(src0 + rc * 64);
+            if (p.wk > 1) {
+                const float2 t1 = *(const float2*)(src0 + rc * 64 + second_part);
+                v[i].x += t1.x;
+                v[i].y += t1.y;
+            }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
