@@ -28,8 +28,11 @@ struct GemmArgs {
     int m, n, k;
     int tiles;            // column tiles = ceil(n / (16 V))
     int split_k;
-    int groups_per_block; // compute groups (32 * IPG consecutive k) per workgroup
-    int groups_per_wave;  // groups_per_block / waves
+    // The compute groups (32 * IPG consecutive k each) are dealt to the split_k * waves k parts
+    // in order: part i = slice * waves + wave gets groups_base of them, the first groups_rem
+    // parts one more (k need not divide evenly; every part stays a whole number of groups).
+    int groups_base;
+    int groups_rem;
     int param_shift;      // log2(compute groups per quantisation group)
     int lds_wave_bytes;   // LDS region of one wave
     int waves;            // working waves per workgroup (the launch has one more in service mode)
@@ -249,7 +252,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 #pragma unroll
     for (int j = 0; j < V; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int g_begin = slice * p.groups_per_block + wave * p.groups_per_wave;
+    const int part = slice * p.waves + wave;
+    const int g_begin = part * p.groups_base + (part < p.groups_rem ? part : p.groups_rem);
+    const int g_count = p.groups_base + (part < p.groups_rem ? 1 : 0);
     // LDS: [0] the flag value this call waits for, [1] wave 0's early sample of the flag; from byte 16 on one [m][BN] fp32 tile per wave
     uint32_t* lds_phase = (uint32_t*)lds_raw;
     char* lds_tiles = lds_raw + 16;
@@ -257,7 +262,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
     probe.addr = p.flags + origin;
     probe.value = 0;
     Ring<V, IPG> ring;
-    wave_prime<V, IPG, GC>(ring, tensors, lm, g_begin, p.groups_per_wave, [&]() {
+    wave_prime<V, IPG, GC>(ring, tensors, lm, g_begin, g_count, [&]() {
         if constexpr (MODE == kAtomicPkF16Phase) {
             if (wave == 0) {
                 // wait for the count (the asm makes it a used value here)
@@ -278,7 +283,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             }
         }
     });
-    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC>(ring, tensors, lm, g_begin, p.groups_per_wave, acc, probe);
+    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC>(ring, tensors, lm, g_begin, g_count, acc, probe);
 
     if constexpr (MODE == kAtomicPkF16Phase) {
         if (wave == 0 && lane == 0) lds_phase[1] = early;
@@ -511,7 +516,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 // them preloaded into scalar registers at wave launch (kernarg preload), so that no round trip
 // to the kernarg segment (about 0.3 us) precedes the loads.  Everything else comes in `rest`
 // and is fetched by one batch of scalar loads while the first vector loads are in flight.
-//   packed = m | param_shift << 5 | waves << 7 | groups_per_wave << 12
+//   packed = m | param_shift << 5 | waves << 7 | groups_base << 12
+//   tiles_rem = tiles | groups_rem << 20
 struct GemmRest {
     float* scratch;
     uint32_t* tickets;
@@ -527,7 +533,7 @@ struct GemmRest {
 template <int V, int IPG, int MODE, int WMAX, int GC>
 __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0)))
 gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, _Float16* C,
-            int packed, int n, int k, int tiles, const GemmRest rest)
+            int packed, int n, int k, int tiles_rem, const GemmRest rest)
 {
     GemmArgs p;
     p.A = A;
@@ -538,11 +544,11 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
     p.m = packed & 31;
     p.param_shift = (packed >> 5) & 3;
     p.waves = (packed >> 7) & 31;
-    p.groups_per_wave = (int)((unsigned)packed >> 12);
-    p.groups_per_block = p.groups_per_wave * p.waves;
+    p.groups_base = (int)((unsigned)packed >> 12);
+    p.groups_rem = (int)((unsigned)tiles_rem >> 20);
     p.n = n;
     p.k = k;
-    p.tiles = tiles;
+    p.tiles = tiles_rem & ((1 << 20) - 1);
     p.scratch = rest.scratch;
     p.tickets = rest.tickets;
     p.flags = rest.flags;
@@ -584,11 +590,14 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     const int slice = blockIdx.x % p.split_k;
     const int tile = blockIdx.x / p.split_k;
     const int m = p.m, n = p.n, k = p.k;
-    const int G = p.groups_per_wave;
 
     const int strip = wave & (kStreamStrips - 1);
     const int kpart = wave / kStreamStrips;
-    const int g_begin = (slice * p.wk + kpart) * G;  // first compute group of this wave
+    // k part of this wave, its first compute group and its group count (the same for every wave
+    // of the workgroup: the host allows a remainder only with one k part per workgroup)
+    const int part = slice * p.wk + kpart;
+    const int g_begin = part * p.groups_base + (part < p.groups_rem ? part : p.groups_rem);
+    const int G = p.groups_base + (part < p.groups_rem ? 1 : 0);
     const int n0 = (tile * kStreamStrips + strip) * 64;
 
     const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
@@ -677,8 +686,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
         }
         published = true;
     };
+    // steady state: D groups are consumed and the next D requested, as long as those exist
     int c = 0;
-    for (; c + D < G; c += D) {
+    for (; c + 2 * D <= G; c += D) {
         stream_groups<D, 0, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
         if constexpr (kPhase) {
             if (!published && c >= D) publish();
@@ -690,7 +700,14 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
             sample = __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    stream_groups<D, 0, false>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+    // D to 2 D - 1 groups are left (D <= 2: at most one beyond the ring, requested on the way)
+    if (D == 2 && G - c == 3) {
+        stream_group<D, 0, true, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        stream_group<D, D - 1, false, true>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
+        stream_group<D, 0, false, false>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
+    } else {
+        stream_groups<D, 0, false>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+    }
 
     // ---- every wave's tile -> LDS (behind the chunks); after the barrier the k parts are added
     // and the sums leave with consecutive lanes on consecutive column pairs
@@ -759,7 +776,8 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
 }
 
 // Kernel entry of the streaming kernel; the leading 14 dwords are preloaded as for gemm_kernel.
-//   packed = m | param_shift << 5 | wk << 7 | groups_per_wave << 12
+//   packed = m | param_shift << 5 | wk << 7 | groups_base << 12
+//   split_rem = split_k | groups_rem << 16
 struct StreamRest {
     uint32_t* flags;
     uint32_t* counts;
@@ -771,7 +789,7 @@ struct StreamRest {
 template <int D, int MODE>
 __global__ void __launch_bounds__(kWave * 8)
 gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
-                   _Float16* C, int packed, int n, int k, int split_k, const StreamRest rest)
+                   _Float16* C, int packed, int n, int k, int split_rem, const StreamRest rest)
 {
     StreamArgs p;
     p.A = A;
@@ -782,10 +800,11 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.m = packed & 31;
     p.param_shift = (packed >> 5) & 3;
     p.wk = (packed >> 7) & 31;
-    p.groups_per_wave = (int)((unsigned)packed >> 12);
+    p.groups_base = (int)((unsigned)packed >> 12);
+    p.groups_rem = (int)((unsigned)split_rem >> 16);
     p.n = n;
     p.k = k;
-    p.split_k = split_k;
+    p.split_k = split_rem & 0xFFFF;
     p.tiles = 0;  // only the launch needs it
     p.flags = rest.flags;
     p.counts = rest.counts;
@@ -879,29 +898,36 @@ constexpr int kSpinLimit = 1 << 17;
 // 64-cycle sleeps before a sample of the tile flag (service wave: before every sample; in-wave
 // protocol: between learning the call count and the early sample).
 static int g_probe_delay = 2;
-// Deepest weight ring (compute groups in flight per wave) the streaming kernel may use.
+// Deepest weight ring (compute groups in flight per wave) the streaming kernel may use: 1 or 2.
 static int g_stream_depth = 2;
+// Fewest workgroups for which the plan picks the streaming kernel by itself.
+static int g_stream_min_blocks = 192;
 static DeviceScratch g_scratch[kMaxDevices];
 static std::mutex g_mutex;
 
-static int check_args(int m, int n, int k, int group_size, int split_k)
+// `even_split`: a requested split_k must cut k into equal shares of whole quantisation groups
+// (Algorithm 1 as printed); otherwise it only has to be positive, and the shares are whole
+// compute groups whose counts differ by at most one.
+static int check_args(int m, int n, int k, int group_size, int split_k, bool even_split = true)
 {
     if (m < 1 || n < 8 || (n % 8) != 0 || group_size < 8 || (group_size % 8) != 0 || k < group_size ||
         (k % group_size) != 0)
         return W4A16_ERR_SHAPE;
     if (split_k < 0) return W4A16_ERR_SPLIT;
-    if (split_k > 0 && ((k % split_k) != 0 || ((k / split_k) % group_size) != 0)) return W4A16_ERR_SPLIT;
+    if (even_split && split_k > 0 && ((k % split_k) != 0 || ((k / split_k) % group_size) != 0))
+        return W4A16_ERR_SPLIT;
     if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
     return W4A16_OK;
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-// Largest w in {16, 8, 4, 2, 1}, w <= cap, that divides `groups`.
-static int largest_wave_split(int groups, int cap)
+// Largest w in {16, 8, 4, 2, 1}, w <= cap, that leaves every one of `parts_before * w` k parts
+// at least one of the `groups` compute groups.
+static int largest_wave_split(int groups, int parts_before, int cap)
 {
-    for (int w = 16; w >= 1; w >>= 1)
-        if (w <= cap && groups % w == 0) return w;
+    for (int w = 16; w > 1; w >>= 1)
+        if (w <= cap && (long long)parts_before * w <= groups) return w;
     return 1;
 }
 
@@ -928,30 +954,33 @@ static bool phase_split_ok(int split_k)
 static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves,
                      int reduce, Plan* out)
 {
-    const int groups = k / group_size;
+    // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
+    const int cgroups = k / (group_size >= 128 ? 128 : group_size);
+    const long long packed_bytes = (long long)k * n / 2;
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
     // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
     if (!dp && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
         const bool asked = tile_cols == kStreamTileCols;
         const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
-        const int sgroups = k / 128;
         const bool shape_ok = group_size == 128 || group_size == 256;
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
                                reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
         int S = split_k;
         if (S == 0) {
-            // about one workgroup per compute unit, at least two groups per wave
+            // about one workgroup per compute unit, at least two groups per workgroup
             S = 1;
-            while (S * 2 <= kPhaseMaxSplit && sgroups % (S * 2) == 0 && sgroups / (S * 2) >= 2 && stiles * S * 2 <= 256)
-                S *= 2;
+            while (S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
         }
-        const bool worth = m >= 8 && (long long)k * n / 2 > (8ll << 20) && stiles * S >= 192;
-        if (asked || (shape_ok && reduce_ok && worth && sgroups % S == 0)) {
+        const bool worth = m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= g_stream_min_blocks && S <= cgroups;
+        if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
             if (waves == 0) waves = kStreamStrips;
             if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
-            if (S < 1 || sgroups % (S * (waves / kStreamStrips)) != 0) return W4A16_ERR_SPLIT;
+            const int wk = waves / kStreamStrips;
+            // the two k parts of an 8-wave workgroup meet at one barrier per group: equal counts
+            if (S < 1 || S >= (1 << 16) || (long long)S * wk > cgroups || (wk > 1 && cgroups % (S * wk) != 0))
+                return W4A16_ERR_SPLIT;
             if (reduce == W4A16_REDUCE_AUTO)
                 reduce = phase_split_ok(S) && (size_t)n <= 16 * (size_t)kPhaseOrigins ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
                                                                                       : W4A16_REDUCE_ATOMIC_PK_F16;
@@ -978,18 +1007,22 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     if (dp) {
         split_k = 1;
     } else if (split_k == 0) {
-        const long long packed_bytes = (long long)k * n / 2;
-        const int target_waves = packed_bytes <= (8ll << 20) ? 2048 : 1024;
-        int want = 1;  // split_k * waves
-        while (want * 2 <= groups && groups % (want * 2) == 0 && tiles * want * 2 <= target_waves) want *= 2;
-        const int w = want < 4 ? want : 4;
-        split_k = want / w;
+        int parts = 1;  // k parts of a column tile = split_k * waves
+        if (packed_bytes <= (8ll << 20)) {
+            while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
+        } else {
+            // four waves per workgroup, and enough k slices for a workgroup per compute unit
+            parts = cgroups < 4 ? cgroups : 4;
+            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < 256) parts *= 2;
+        }
+        int w = waves != 0 ? waves : parts < 4 ? parts : 4;
+        if (w > parts) w = parts;
+        split_k = parts / w;
         if (waves == 0) waves = w;
     }
-    if (split_k < 1 || groups % split_k != 0) return W4A16_ERR_SPLIT;
-    const int gpb = groups / split_k;
-    if (waves == 0) waves = largest_wave_split(gpb, dp ? wave_cap : 4);
-    if (waves < 1 || waves > 16 || gpb % waves != 0) return W4A16_ERR_UNSUPPORTED;
+    if (split_k < 1 || split_k > cgroups) return W4A16_ERR_SPLIT;
+    if (waves == 0) waves = largest_wave_split(cgroups, split_k, dp ? wave_cap : 4);
+    if (waves < 1 || waves > 16 || (long long)split_k * waves > cgroups) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_AUTO) {
         // few rows: the arrival-counting fixed-point adds finish in one round trip with no
         // zero-fill launch.  Many rows: returning 64-bit atomics cost more than the fill launch
@@ -1059,8 +1092,11 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
     const unsigned threads = (unsigned)(waves + (MODE == kAtomicPkF16Service ? 1 : 0)) * kWave;
-    if (a.m > 31 || a.param_shift > 3 || a.waves > 31 || a.groups_per_wave >= (1 << 20)) return W4A16_ERR_UNSUPPORTED;
-    const int packed = a.m | a.param_shift << 5 | a.waves << 7 | (int)((unsigned)a.groups_per_wave << 12);
+    if (a.m > 31 || a.param_shift > 3 || a.waves > 31 || a.groups_base >= (1 << 20) || a.tiles >= (1 << 20) ||
+        a.groups_rem >= (1 << 11))
+        return W4A16_ERR_UNSUPPORTED;
+    const int packed = a.m | a.param_shift << 5 | a.waves << 7 | (int)((unsigned)a.groups_base << 12);
+    const int tiles_rem = a.tiles | a.groups_rem << 20;
     GemmRest rest;
     rest.scratch = a.scratch;
     rest.tickets = a.tickets;
@@ -1072,7 +1108,7 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
     rest.spin_limit = a.spin_limit;
     rest.probe_delay = a.probe_delay;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, stream, a.A, a.qweight, a.scales, a.qzeros, a.C,
-                       packed, a.n, a.k, a.tiles, rest);
+                       packed, a.n, a.k, tiles_rem, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -1082,19 +1118,19 @@ static int launch_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_
     if (waves <= 4) {
         // the tuned shape (128-bit loads, group of 128) knows its group count at compile time
         if constexpr (V == 4 && IPG == 4) {
-            if (a.groups_per_wave == 1) {
+            if (a.groups_base == 1 && a.groups_rem == 0) {
                 // few registers per wave: the phase protocol gets a wave of its own
                 if constexpr (MODE == kAtomicPkF16Phase)
                     return launch_bound<V, IPG, kAtomicPkF16Service, 4, 1>(a, waves, lds_bytes, stream);
                 return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
             }
-            return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
+            if (a.groups_base >= 2) return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
         }
         return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
     }
     if constexpr (V == 4 && IPG == 4) {
         // one group per wave needs few registers, so large workgroups lose nothing
-        if (a.groups_per_wave == 1) return launch_bound<V, IPG, MODE, 16, 1>(a, waves, lds_bytes, stream);
+        if (a.groups_base == 1 && a.groups_rem == 0) return launch_bound<V, IPG, MODE, 16, 1>(a, waves, lds_bytes, stream);
     }
     return launch_bound<V, IPG, MODE, 16, 0>(a, waves, lds_bytes, stream);
 }
@@ -1133,8 +1169,10 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
             return W4A16_ERR_HIP;
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    if (a.m > 31 || a.groups_per_wave >= (1 << 20)) return W4A16_ERR_UNSUPPORTED;
-    const int packed = a.m | a.param_shift << 5 | a.wk << 7 | (int)((unsigned)a.groups_per_wave << 12);
+    if (a.m > 31 || a.groups_base >= (1 << 20) || a.split_k >= (1 << 16) || a.groups_rem >= (1 << 15))
+        return W4A16_ERR_UNSUPPORTED;
+    const int packed = a.m | a.param_shift << 5 | a.wk << 7 | (int)((unsigned)a.groups_base << 12);
+    const int split_rem = a.split_k | a.groups_rem << 16;
     StreamRest rest;
     rest.flags = a.flags;
     rest.counts = a.counts;
@@ -1142,7 +1180,7 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     rest.spin_limit = a.spin_limit;
     rest.probe_delay = a.probe_delay;
     hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a.A,
-                       a.qweight, a.scales, a.qzeros, a.C, packed, a.n, a.k, a.split_k, rest);
+                       a.qweight, a.scales, a.qzeros, a.C, packed, a.n, a.k, split_rem, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -1167,7 +1205,9 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
     const int wk = waves / kStreamStrips;
     const int groups = k / 128;
-    if (split_k < 1 || groups % (split_k * wk) != 0) return W4A16_ERR_SPLIT;
+    // the two k parts of an 8-wave workgroup meet at one barrier per group: equal counts
+    if (split_k < 1 || (long long)split_k * wk > groups || (wk > 1 && groups % (split_k * wk) != 0))
+        return W4A16_ERR_SPLIT;
     if (reduce == W4A16_REDUCE_AUTO)
         reduce = phase_split_ok(split_k) && (size_t)n <= 16 * (size_t)kPhaseOrigins ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
                                                                                   : W4A16_REDUCE_ATOMIC_PK_F16;
@@ -1186,7 +1226,8 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     a.tiles = (n + kStreamTileCols - 1) / kStreamTileCols;
     a.split_k = split_k;
     a.wk = wk;
-    a.groups_per_wave = groups / (split_k * wk);
+    a.groups_base = groups / (split_k * wk);
+    a.groups_rem = groups % (split_k * wk);
     a.param_shift = group_size == 256 ? 1 : 0;
     a.spin_limit = kSpinLimit;
     a.probe_delay = g_probe_delay;
@@ -1214,9 +1255,8 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
             mode = kAtomicPkF16;
         }
     }
-    const int G = a.groups_per_wave;
-    if (G % 4 == 0 && g_stream_depth >= 4) return launch_stream_mode<4>(a, lds_bytes, mode, stream);
-    if (G % 2 == 0 && g_stream_depth >= 2) return launch_stream_mode<2>(a, lds_bytes, mode, stream);
+    // ring depth: two groups in flight per wave when every k part has at least two
+    if (a.groups_base >= 2 && g_stream_depth >= 2) return launch_stream_mode<2>(a, lds_bytes, mode, stream);
     return launch_stream_mode<1>(a, lds_bytes, mode, stream);
 }
 
@@ -1227,15 +1267,16 @@ static void read_tuning_env()
     done = true;
     if (const char* e = getenv("W4A16_PROBE_DELAY")) g_probe_delay = atoi(e);
     if (const char* e = getenv("W4A16_STREAM_DEPTH")) g_stream_depth = atoi(e);
+    if (const char* e = getenv("W4A16_STREAM_MIN_BLOCKS")) g_stream_min_blocks = atoi(e);
 }
 
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
                     int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves, int reduce,
-                    void* stream_v)
+                    bool even_split, void* stream_v)
 {
     if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
     read_tuning_env();
-    int rc = check_args(m, n, k, group_size, dp ? 1 : split_k);
+    int rc = check_args(m, n, k, group_size, dp ? 1 : split_k, even_split);
     if (rc != W4A16_OK) return rc;
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
@@ -1245,7 +1286,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         for (int r = 0; r < m; r += 16) {
             const int mm = m - r < 16 ? m - r : 16;
             rc = run_gemm((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros, (_Float16*)C + (size_t)r * n, mm,
-                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, stream_v);
+                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v);
             if (rc != W4A16_OK) return rc;
         }
         return W4A16_OK;
@@ -1277,8 +1318,9 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     a.k = k;
     a.tiles = (n + plan.tile_cols - 1) / plan.tile_cols;
     a.split_k = plan.split_k;
-    a.groups_per_block = (k / (32 * ipg)) / plan.split_k;
-    a.groups_per_wave = a.groups_per_block / plan.waves;
+    const int cgroups = k / (32 * ipg), kparts = plan.split_k * plan.waves;
+    a.groups_base = cgroups / kparts;
+    a.groups_rem = cgroups % kparts;
     a.waves = plan.waves;
     a.param_shift = param_shift;
     // LDS: 16 bytes for the phase word, then one [m, tile_cols] fp32 tile per wave, for the sum
@@ -1336,14 +1378,14 @@ int w4a16_gemm(const void* A, const void* qweight, const void* scales, const voi
                int k, int group_size, int split_k, void* stream)
 {
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
-                           W4A16_REDUCE_AUTO, stream);
+                           W4A16_REDUCE_AUTO, true, stream);
 }
 
 int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
                   int k, int group_size, void* stream)
 {
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
-                           stream);
+                           true, stream);
 }
 
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
@@ -1351,7 +1393,7 @@ int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const 
 {
     if (tile_cols < 0 || waves < 0 || reduce < 0) return W4A16_ERR_UNSUPPORTED;
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, tile_cols, waves,
-                           reduce, stream);
+                           reduce, false, stream);
 }
 
 int w4a16_gemm_dp_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
@@ -1359,13 +1401,13 @@ int w4a16_gemm_dp_ex(const void* A, const void* qweight, const void* scales, con
 {
     if (tile_cols < 0 || waves < 0) return W4A16_ERR_UNSUPPORTED;
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, tile_cols, waves,
-                           W4A16_REDUCE_AUTO, stream);
+                           W4A16_REDUCE_AUTO, true, stream);
 }
 
 int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols, int* waves, int* reduce)
 {
     const int req = split_k ? *split_k : 0;
-    int rc = w4a16::check_args(m, n, k, group_size, dp ? 1 : req);
+    int rc = w4a16::check_args(m, n, k, group_size, dp ? 1 : req, false);
     if (rc != W4A16_OK) return rc;
     w4a16::Plan plan;
     rc = w4a16::make_plan(m, n, k, group_size, dp != 0, req, tile_cols ? *tile_cols : 0, waves ? *waves : 0,

@@ -37,7 +37,10 @@ struct StreamArgs {
     int tiles;            // 256-column workgroup tiles = ceil(n / 256)
     int split_k;
     int wk;               // k parts per workgroup; working waves = 4 * wk
-    int groups_per_wave;  // compute groups (128 consecutive k) per wave; a multiple of D
+    // compute groups (128 consecutive k) per k part: part i = slice * wk + kpart gets groups_base,
+    // the first groups_rem parts one more (groups_rem > 0 only with wk == 1); groups_base >= D
+    int groups_base;
+    int groups_rem;
     int param_shift;      // log2(compute groups per quantisation group)
     int spin_limit;       // phase protocol: bound on samples of a flag
     int probe_delay;      // phase protocol: 64-cycle sleeps before a sample

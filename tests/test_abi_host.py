@@ -102,6 +102,29 @@ def test_plan_is_consistent():
         b.w4a16_plan(16, 4096, 4096, 128, split_k=8, waves=8)   # 4 groups per workgroup cannot feed 8 waves
 
 
+def test_uneven_k_shares_host_rules():
+    """w4a16_gemm keeps Algorithm 1's equal shares for a requested split_k; the library's own
+    plan and the _ex entry point deal whole compute groups, counts differing by at most one."""
+    L = b.lib()
+    p = ctypes.c_void_p(4096)
+    assert b.w4a16_check(1, 1024, 1408, 128, 0) == b.OK                                     # 11 groups, library's choice
+    assert b.w4a16_check(1, 1024, 1408, 128, 2) == b.ERR_SPLIT
+    assert L.w4a16_gemm(p, p, p, p, p, 1, 1024, 1408, 128, 2, None) == b.ERR_SPLIT          # 11 groups cannot be halved
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1408, 128, 16, 64, 1, 0, None) == b.ERR_SPLIT   # 16 slices, 11 groups
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1408, 128, 4, 64, 4, 0, None) == b.ERR_UNSUPPORTED  # 16 parts
+    assert L.w4a16_gemm_ex(p, p, p, p, p, 16, 1024, 1408, 128, 2, 256, 8, 0, None) == b.ERR_SPLIT  # 8-wave streaming needs equal parts
+    # llama-style projections, k = 11008 and 13824 included: the plan always has work for every part
+    for m in (1, 16):
+        for (n, k) in ((4096, 11008), (11008, 4096), (12288, 4096), (13824, 5120), (5120, 13824), (28672, 8192),
+                       (8192, 28672), (22016, 4096), (10240, 8192)):
+            for dp in (False, True):
+                pl = b.w4a16_plan(m, n, k, 128, dp=dp)
+                kparts = pl["waves"] // 4 if pl["tile_cols"] == 256 else pl["waves"]
+                assert 1 <= pl["split_k"] * kparts <= k // 128
+                tiles = -(-n // pl["tile_cols"])
+                assert tiles * pl["split_k"] >= 160, (m, n, k, dp, pl)
+
+
 def test_algorithmic_bytes():
     """The library, the input module and the figures derived from the paper's profile agree."""
     for (m, nk, expect) in ((1, 1024, 548864), (1, 4096, 8732672), (16, 4096, 8978432), (1, 8192, 34897920),

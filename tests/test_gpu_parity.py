@@ -356,6 +356,82 @@ def test_stream_kernel_one_hot_rows_bit_exact(split_k, waves):
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
 
 
+# ------------------------------------------------------------------ k that does not divide evenly
+# The compute groups are dealt to the split_k * (k parts per workgroup) parts in order, the
+# first (groups % parts) parts getting one more: shapes whose group count has few factors
+# (llama's k = 11008 has 86 groups of 128) still get a balanced launch.
+UNEVEN = [
+    # m, n, k, g, split_k, tile_cols, waves, reduce
+    (16, 200, 1408, 128, 2, 64, 4, 1),     # 11 groups over 8 parts: 2,2,2,1,1,1,1,1
+    (16, 200, 1408, 128, 1, 64, 4, 0),     # 3,3,3,2: direct store
+    (5, 328, 1408, 128, 4, 64, 2, 5),      # phase protocol, parts of one and two groups
+    (16, 264, 1664, 128, 2, 64, 4, 4),     # 13 groups over 8 parts, fixed-point adds
+    (7, 136, 1408, 128, 3, 32, 1, 3),      # split_k = 3: 4,4,3, workspace
+    (16, 192, 2752, 32, 4, 64, 4, 2),      # 86 compute groups of 32 over 16 parts: 6 x 6, 10 x 5
+    (9, 192, 1408, 64, 3, 64, 2, 2),       # 22 compute groups over 6 parts
+    (16, 192, 1280, 256, 4, 64, 1, 1),     # 10 compute groups of 128 over 4: a part boundary inside a quantisation group
+    (3, 72, 2432, 128, 1, 16, 16, 0),      # 19 groups over 16 waves
+    (16, 200, 1408, 128, 8, 64, 1, 5),     # 8 slices of one or two groups
+    (16, 256, 1408, 128, 2, 256, 4, 0),    # streaming kernel: 6 and 5 groups (odd tail of the ring)
+    (16, 328, 1408, 128, 4, 256, 4, 0),    # 3,3,3,2
+    (11, 328, 1408, 128, 8, 256, 4, 5),    # 2,2,2,1,...: ring depth 1
+    (16, 264, 1408, 128, 3, 256, 4, 2),    # split_k = 3: 4,4,3, fill kernel
+    (16, 512, 1408, 128, 1, 256, 4, 0),    # 11 groups in one part
+    (8, 264, 1280, 256, 4, 256, 4, 0),     # group_size 256, 3,3,2,2
+    (16, 264, 1664, 128, 4, 256, 4, 5),    # 4,3,3,3
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves,reduce", UNEVEN)
+def test_uneven_k_shares(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
+    A, qw, s, qz = random_case(m, n, k, g, seed=500 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, reduce)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} g={g} S={split_k} tile={tile_cols} waves={waves} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+    if tile_cols != 256:
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_dp_ex(*p.args(), tile_cols, waves)
+        assert_parity(p.result(), Cref, f"dp m={m} n={n} k={k} waves={waves}")
+
+
+@pytest.mark.parametrize("split_k,tile_cols,waves", [(2, 64, 4), (3, 64, 2), (1, 32, 8), (2, 256, 4), (4, 256, 4),
+                                                     (8, 256, 4), (3, 256, 4)])
+def test_uneven_k_shares_one_hot_bit_exact(split_k, tile_cols, waves):
+    """One non-zero term per output row, swept over every k: a group that two parts both take,
+    or that none takes, changes a result that must be fp16(w[r, :]) exactly."""
+    m, n, k, g = 16, 264, 1408, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=47)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+def test_auto_plan_awkward_k(oracle):
+    """k = 86 groups (the shape of llama's 11008) with the library's own launch, both kernels."""
+    for m, n in ((16, 512), (1, 264)):
+        A, qw, s, qz = random_case(m, n, 11008, 128, seed=61 + m)
+        Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+        p = DeviceProblem(A, qw, s, qz, 128)
+        b.w4a16_gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"auto m={m} n={n}")
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_dp(*p.args())
+        assert_parity(p.result(), Cref, f"dp m={m} n={n}")
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
