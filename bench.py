@@ -12,7 +12,7 @@ Prints ONE JSON line on stdout (progress and tables go to stderr):
   value        effective HBM GB/s = algorithmic bytes per call / wall time per call
   roofline     the same bytes over the HIP-event time per launch on the launch stream, vs 8 TB/s
   cpu_baseline the CPU oracle timed on this machine's host cores on the same workload
-  extra        SplitK-vs-DP per shape, split_k sweep, warm (cache-resident) figures
+  extra        SplitK-vs-DP per shape, split_k sweep, warm (cache-resident) figures, non-square decoder shapes
 """
 from __future__ import annotations
 
@@ -352,6 +352,25 @@ def main():
             log(f"[bench] m={mm} n=k={nk}: best split_k={best['split_k']} {best['us']:.2f} us "
                 f"({best['GBps']:.0f} GB/s, {100 * best['frac_of_peak']:.1f}% of peak), dp {e_dp * 1e6:.2f} us")
             del wb
+
+        # non-square shapes: the linear layers of llama-7B/13B/70B style decoders (fused qkv,
+        # gate/up and down projections; k = 11008 and 13824 are 86 and 108 groups of 128)
+        rows = []
+        for (n_, k_) in ((12288, 4096), (11008, 4096), (4096, 11008), (13824, 5120), (5120, 13824),
+                         (28672, 8192), (8192, 28672)):
+            wb = Workload(16, n_, k_, g, nsets(n_, k_), seed=args.seed)
+            for mm in (1, 16):
+                wm = wb.with_m(mm)
+                pl = binding.w4a16_plan(mm, n_, k_, g)
+                _, e = time_calls(make_call(wm, "splitk", split_k=0), 200, 30)
+                _, e_dp = time_calls(make_call(wm, "dp"), 200, 30)
+                rows.append({"m": mm, "n": n_, "k": k_, "plan": pl, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
+                             "speedup_over_dp": e_dp / e, "splitk_GBps": wm.bytes / e / 1e9,
+                             "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
+                log(f"[bench] m={mm:2d} n={n_} k={k_}: splitk {e * 1e6:7.2f} us (S={pl['split_k']}, tile {pl['tile_cols']}), "
+                    f"dp {e_dp * 1e6:7.2f} us, x{e_dp / e:.2f}, {wm.bytes / e / 1e9:.0f} GB/s")
+            del wb
+        extra["decoder_projection_shapes"] = rows
 
     out = {
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",

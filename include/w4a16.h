@@ -21,7 +21,12 @@
  *
  * Limits: m >= 1 (the paper's regime is m <= 16; larger m runs as one launch per 16 rows, each
  * streaming the weights again); n a multiple of 8; g (group_size) one of 32, 64, 128, 256;
- * k a multiple of g; for split-k, k / split_k a multiple of g; k * n < 2^32.
+ * k a multiple of g; k * n < 2^32.  A split_k requested from w4a16_gemm must cut k into equal
+ * shares of whole groups (k / split_k a multiple of g), as Algorithm 1 has it.  The library's own
+ * choice (split_k == 0) and w4a16_gemm_ex are not bound by that: they deal out k in compute
+ * groups (min(g, 128) consecutive k) to the k parts in order, the first ones getting one group
+ * more when the count does not divide, so that any k (llama's 11008 = 86 groups) gets a
+ * balanced launch.
  *
  * Return value: W4A16_OK or a negative W4A16_ERR_* code.  Argument checks run before any HIP
  * call, so they behave the same on a machine without a GPU.  Nothing is printed, nothing
@@ -45,7 +50,8 @@ extern "C" {
 #define W4A16_OK 0
 #define W4A16_ERR_NULL (-1)        /* a required pointer is NULL */
 #define W4A16_ERR_SHAPE (-2)       /* m < 1, n % 8, bad group_size, k % group_size */
-#define W4A16_ERR_SPLIT (-3)       /* split_k < 1, k % split_k, (k / split_k) % group_size */
+#define W4A16_ERR_SPLIT (-3)       /* split_k < 0; w4a16_gemm: k % split_k, (k / split_k) % group_size; _ex: more
+                                      k parts than compute groups, uneven parts where they must be equal */
 #define W4A16_ERR_UNSUPPORTED (-4) /* group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
 #define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
 
@@ -86,7 +92,10 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
  *              reduce W4A16_REDUCE_ATOMIC_PK_F16 or W4A16_REDUCE_ATOMIC_PK_F16_PHASE)
  *   waves      wavefronts per workgroup, 1..16
  *   reduce     one of W4A16_REDUCE_* (ignored when split_k == 1)
- * (k / split_k) must be divisible by (number of k parts of a workgroup) * group_size.
+ * split_k here is any value >= 1 (0 = library default) with split_k * (k parts of a workgroup:
+ * waves, or waves / 4 for 256-column tiles) <= k / min(group_size, 128); the parts' shares may
+ * differ by one compute group, except with 256-column tiles and 8 waves, whose two k parts meet
+ * at a barrier per group and must be equal (W4A16_ERR_SPLIT otherwise).
  */
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                   int m, int n, int k, int group_size, int split_k,
@@ -101,7 +110,8 @@ int w4a16_gemm_dp_ex(const void* A, const void* qweight, const void* scales, con
  */
 int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols, int* waves, int* reduce);
 
-/* Argument check alone (host only, no HIP call): what w4a16_gemm would return before launching. */
+/* Argument check alone (host only, no HIP call): what w4a16_gemm would return before launching
+ * (equal shares required of a requested split_k). */
 int w4a16_check(int m, int n, int k, int group_size, int split_k);
 
 /*

@@ -576,7 +576,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
 //                         the steady loop, when a load issued after the count has been consumed,
 //                         samples the flag before the last groups and does not join the last
 //                         barrier, behind which all waves add into C, before it has seen it.
-template <int D, int MODE>
+template <int D, int MODE, bool ODD>
 __device__ __forceinline__ void stream_body(const StreamArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -700,11 +700,16 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
             sample = __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // D to 2 D - 1 groups are left (D <= 2: at most one beyond the ring, requested on the way)
-    if (D == 2 && G - c == 3) {
-        stream_group<D, 0, true, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-        stream_group<D, D - 1, false, true>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
-        stream_group<D, 0, false, false>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
+    // D to 2 D - 1 groups are left.  ODD (D == 2 only): a k part may have an odd count, then
+    // three are left: one beyond the ring, requested on the way.
+    bool three_left = false;
+    if constexpr (ODD) three_left = G - c == 3;
+    if (three_left) {
+        if constexpr (ODD) {
+            stream_group<D, 0, true, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+            stream_group<D, 1, false, true>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
+            stream_group<D, 0, false, false>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
+        }
     } else {
         stream_groups<D, 0, false>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
     }
@@ -786,7 +791,7 @@ struct StreamRest {
     int probe_delay;
 };
 
-template <int D, int MODE>
+template <int D, int MODE, bool ODD>
 __global__ void __launch_bounds__(kWave * 8)
 gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
                    _Float16* C, int packed, int n, int k, int split_rem, const StreamRest rest)
@@ -811,7 +816,8 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.errors = rest.errors;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
-    stream_body<D, MODE>(p);
+    static_assert(!ODD || D == 2, "odd group counts need no code of their own at ring depth 1");
+    stream_body<D, MODE, ODD>(p);
 }
 
 // C <- 0 for the packed-fp16 atomic mode (a kernel, not a memset, so the call can be captured
@@ -900,8 +906,8 @@ constexpr int kSpinLimit = 1 << 17;
 static int g_probe_delay = 2;
 // Deepest weight ring (compute groups in flight per wave) the streaming kernel may use: 1 or 2.
 static int g_stream_depth = 2;
-// Fewest workgroups for which the plan picks the streaming kernel by itself.
-static int g_stream_min_blocks = 192;
+// Fewest workgroups that the plan accepts for a launch whose waves each take a long run of groups.
+static int g_stream_min_blocks = 160;
 static DeviceScratch g_scratch[kMaxDevices];
 static std::mutex g_mutex;
 
@@ -944,11 +950,11 @@ static bool phase_split_ok(int split_k)
 // Launch shape, from sweeps on MI355X (256 compute units, 1024 SIMDs).
 //
 // SplitK: 64-column tiles (128-bit weight loads).  The kernel is bound by how fast a burst of
-// loads can be put in flight, so the plan aims at one to two resident waves per SIMD: about
-// 2048 waves when the whole weight matrix is small enough to be requested at once (<= 8 MiB
-// packed), about 1024 longer-running waves otherwise.  Up to four waves of a workgroup divide
-// its k range (their tiles are added in LDS, which keeps the atomic traffic down); the rest of
-// the k parallelism is split_k.
+// loads can be put in flight, so the plan aims at about 2048 short-lived waves when the whole
+// weight matrix is small enough to be requested at once (<= 8 MiB packed), and otherwise at
+// 160 or more workgroups of long-running waves.  Up to four waves of a workgroup divide its k
+// range (their tiles are added in LDS, which keeps the atomic traffic down); the rest of the k
+// parallelism is split_k.
 // Data-parallel: the only source of workgroups is the column tiling, so tiles shrink (64, 32,
 // 16 columns) until there are about 256 of them, and the waves of a workgroup divide k.
 static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves,
@@ -968,9 +974,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
         int S = split_k;
         if (S == 0) {
-            // about one workgroup per compute unit, at least two groups per workgroup
+            // about one workgroup per compute unit (160 to 319 of them), at least two groups each
             S = 1;
             while (S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
+            if (stiles * S < g_stream_min_blocks && S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2) S *= 2;
         }
         const bool worth = m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= g_stream_min_blocks && S <= cgroups;
         if (asked || (shape_ok && reduce_ok && worth)) {
@@ -1007,13 +1014,19 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     if (dp) {
         split_k = 1;
     } else if (split_k == 0) {
+        // Measured on MI355X: a wave either takes exactly one group (little state per wave, many
+        // resident waves, every load of the launch in flight at once) or a long run of them
+        // (few workgroups, about one per compute unit); runs of two to four groups lose to both.
         int parts = 1;  // k parts of a column tile = split_k * waves
         if (packed_bytes <= (8ll << 20)) {
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
+        } else if (m <= 2 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20)) {
+            // one group per wave; the few rows keep the atomic traffic of the many slices small
+            parts = cgroups;
         } else {
-            // four waves per workgroup, and enough k slices for a workgroup per compute unit
+            // four waves per workgroup and the fewest k slices that give 160 workgroups
             parts = cgroups < 4 ? cgroups : 4;
-            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < 256) parts *= 2;
+            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < g_stream_min_blocks) parts *= 2;
         }
         int w = waves != 0 ? waves : parts < 4 ? parts : 4;
         if (w > parts) w = parts;
@@ -1159,10 +1172,10 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
 }
 
 // ---- launch of the streaming SplitK kernel
-template <int D, int MODE>
+template <int D, int MODE, bool ODD>
 static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_stream_kernel<D, MODE>;
+    auto kern = gemm_stream_kernel<D, MODE, ODD>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -1184,12 +1197,12 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
-template <int D>
+template <int D, bool ODD>
 static int launch_stream_mode(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
-    if (mode == kDirect) return launch_stream_one<D, kDirect>(a, lds_bytes, stream);
-    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16>(a, lds_bytes, stream);
-    return launch_stream_one<D, kAtomicPkF16Phase>(a, lds_bytes, stream);
+    if (mode == kDirect) return launch_stream_one<D, kDirect, ODD>(a, lds_bytes, stream);
+    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, ODD>(a, lds_bytes, stream);
+    return launch_stream_one<D, kAtomicPkF16Phase, ODD>(a, lds_bytes, stream);
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
@@ -1256,8 +1269,11 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
         }
     }
     // ring depth: two groups in flight per wave when every k part has at least two
-    if (a.groups_base >= 2 && g_stream_depth >= 2) return launch_stream_mode<2>(a, lds_bytes, mode, stream);
-    return launch_stream_mode<1>(a, lds_bytes, mode, stream);
+    if (a.groups_base >= 2 && g_stream_depth >= 2) {
+        if (a.groups_rem == 0 && a.groups_base % 2 == 0) return launch_stream_mode<2, false>(a, lds_bytes, mode, stream);
+        return launch_stream_mode<2, true>(a, lds_bytes, mode, stream);
+    }
+    return launch_stream_mode<1, false>(a, lds_bytes, mode, stream);
 }
 
 static void read_tuning_env()
@@ -1464,7 +1480,9 @@ const char* w4a16_strerror(int code)
     case W4A16_OK: return "ok";
     case W4A16_ERR_NULL: return "a required pointer is NULL";
     case W4A16_ERR_SHAPE: return "bad shape: need m >= 1, n % 8 == 0, group_size % 8 == 0, k % group_size == 0";
-    case W4A16_ERR_SPLIT: return "bad split_k: need split_k >= 0, k % split_k == 0, (k / split_k) % group_size == 0";
+    case W4A16_ERR_SPLIT:
+        return "bad split_k: need split_k >= 0; w4a16_gemm: k % split_k == 0 and (k / split_k) % group_size == 0; "
+               "w4a16_gemm_ex: no more k parts than compute groups";
     case W4A16_ERR_UNSUPPORTED:
         return "unsupported: group_size not in {32,64,128,256}, pointer not 16-byte aligned, or bad tuning value";
     case W4A16_ERR_HIP: return "a HIP runtime call failed";
