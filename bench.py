@@ -371,6 +371,18 @@ def main():
                     f"dp {e_dp * 1e6:7.2f} us, x{e_dp / e:.2f}, {wm.bytes / e / 1e9:.0f} GB/s")
             del wb
         extra["decoder_projection_shapes"] = rows
+        # more than 16 rows: row tiles of one launch (up to 64 rows share one pass over the weights)
+        rows = []
+        wb = Workload(64, 8192, 8192, g, nsets(8192, 8192), seed=args.seed)
+        for mm in (16, 32, 48, 64):
+            wm = wb.with_m(mm)
+            _, e = time_calls(make_call(wm, "splitk", split_k=0), 200, 30)
+            rows.append({"m": mm, "n": 8192, "k": 8192, "splitk_us": e * 1e6, "splitk_GBps": wm.bytes / e / 1e9,
+                         "TFLOPs": 2.0 * mm * 8192 * 8192 / e / 1e12})
+            log(f"[bench] m={mm:2d} n=k=8192: splitk {e * 1e6:7.2f} us, {wm.bytes / e / 1e9:.0f} GB/s, "
+                f"{2.0 * mm * 8192 * 8192 / e / 1e12:.0f} TFLOP/s")
+        del wb
+        extra["row_tiles_nk8192"] = rows
 
     out = {
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",

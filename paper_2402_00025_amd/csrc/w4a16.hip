@@ -576,7 +576,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
 //                         the steady loop, when a load issued after the count has been consumed,
 //                         samples the flag before the last groups and does not join the last
 //                         barrier, behind which all waves add into C, before it has seen it.
-template <int D, int MODE, bool ODD>
+template <int D, int MODE, bool ODD, int MT>
 __device__ __forceinline__ void stream_body(const StreamArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -613,26 +613,33 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     tensors.param_shift = p.param_shift;
     const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
 
-    // this wave's quarter of a chunk: rows 4 strip .. 4 strip + 3, 16 lanes (256 bytes) per row;
-    // rows >= m are not fetched (an offset outside the buffer returns zeros)
-    StreamLane sl;
+    // this wave's quarter of a chunk: rows 4 strip .. 4 strip + 3 of every row tile, 16 lanes
+    // (256 bytes) per row; rows >= m are not fetched (an offset outside the buffer returns zeros)
+    StreamLane<MT> sl;
     const int prow = 4 * strip + (lane >> 4);
-    sl.a_voff = prow < m ? ((uint32_t)prow * (uint32_t)k + 8u * (uint32_t)(lane & 15)) * 2u : kOutside;
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt) {
+        const int arow = 16 * rt + prow;
+        sl.a_voff[rt] = arow < m ? ((uint32_t)arow * (uint32_t)k + 8u * (uint32_t)(lane & 15)) * 2u : kOutside;
+    }
     sl.a_soff0 = (uint32_t)g_begin * 256u;
     sl.wslot = chunk_slot_bytes(lane & 15, prow);
 #pragma unroll
     for (int it = 0; it < 4; ++it) sl.roff[it] = chunk_slot_bytes(4 * it + (lane >> 4), lane & 15);
-    sl.ring = lds_raw + kpart * 2 * kChunkBytes;
+    sl.ring = lds_raw + kpart * 2 * (MT * kChunkBytes);
 
     // ---- prologue: the first D chunk quarters, then the first D groups of weights; chunk 0 goes
     // to LDS.  The compute unit returns the loads of all its waves in one issue order, and
     // nobody can start before all four quarters of chunk 0 are there: the barrier between the
     // two kinds of loads keeps every quarter ahead of every weight load of the workgroup
     // (otherwise the last wave's quarter queues behind the other waves' weights, tens of KiB).
-    u32x4_t a_in[D];
+    u32x4_t a_in[D][MT];
 #pragma unroll
     for (int h = 0; h < D; ++h)
-        a_in[h] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff, sl.a_soff0 + (uint32_t)h * 256u, 0);
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt)
+            a_in[h][rt] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff[rt],
+                                                                sl.a_soff0 + (uint32_t)h * 256u, 0);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
@@ -648,7 +655,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
         asm volatile("" ::: "memory");
         // 16-byte units of the tile: m rows x 32 units; n % 8 == 0 keeps a unit inside or outside
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 8 * MT; ++i) {
             const int u = lane + kWave * i;
             const int row = u >> 5, col = tile * kStreamTileCols + 8 * (u & 31);
             const bool inside = wave == 0 && slice == 0 && row < m && col < n;
@@ -663,15 +670,21 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    *(half8_t*)(sl.ring + sl.wslot) = permute_activations(a_in[0]);
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt)
+        *(half8_t*)(sl.ring + rt * kChunkBytes + sl.wslot) = permute_activations(a_in[0][rt]);
     __syncthreads();
-    u32x4_t a[4];
+    u32x4_t a[MT][4];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(sl.ring + sl.roff[it]);
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) a[rt][it] = *(const u32x4_t*)(sl.ring + rt * kChunkBytes + sl.roff[it]);
 
-    float4_t acc[4];
+    float4_t acc[MT][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[rt][j] = float4_t{0.f, 0.f, 0.f, 0.f};
     const uint32_t magic = magic_1024x2();
 
     uint32_t now = 0, sample = 0;
@@ -689,7 +702,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     // steady state: D groups are consumed and the next D requested, as long as those exist
     int c = 0;
     for (; c + 2 * D <= G; c += D) {
-        stream_groups<D, 0, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        stream_groups<D, 0, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
         if constexpr (kPhase) {
             if (!published && c >= D) publish();
         }
@@ -706,23 +719,27 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     if constexpr (ODD) three_left = G - c == 3;
     if (three_left) {
         if constexpr (ODD) {
-            stream_group<D, 0, true, true>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-            stream_group<D, 1, false, true>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
-            stream_group<D, 0, false, false>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
+            stream_group<D, 0, true, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+            stream_group<D, 1, false, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
+            stream_group<D, 0, false, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
         }
     } else {
-        stream_groups<D, 0, false>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        stream_groups<D, 0, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
     }
 
     // ---- every wave's tile -> LDS (behind the chunks); after the barrier the k parts are added
     // and the sums leave with consecutive lanes on consecutive column pairs
-    float* red_all = (float*)(lds_raw + p.wk * 2 * kChunkBytes);
+    float* red_all = (float*)(lds_raw + p.wk * 2 * (MT * kChunkBytes));
     float* red = red_all + (size_t)wave * m * 64;  // [m][64]
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = 4 * (lane >> 4) + r;
-        if (row < m) *(float4_t*)(red + row * 64 + 4 * (lane & 15)) = float4_t{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
-    }
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 16 * rt + 4 * (lane >> 4) + r;
+            if (row < m)
+                *(float4_t*)(red + row * 64 + 4 * (lane & 15)) =
+                    float4_t{acc[rt][0][r], acc[rt][1][r], acc[rt][2][r], acc[rt][3][r]};
+        }
     if constexpr (kPhase) {
         if (wave == 0) {
             // wave 0 holds the barrier until this call's zeros of the tile are in memory
@@ -781,8 +798,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
 }
 
 // Kernel entry of the streaming kernel; the leading 14 dwords are preloaded as for gemm_kernel.
-//   packed = m | param_shift << 5 | wk << 7 | groups_base << 12
+//   packed = m | param_shift << 7 | wk << 9 | groups_base << 12
 //   split_rem = split_k | groups_rem << 16
+// Up to 16 rows: 4 or 8 waves, at most 256 registers each.  More rows (MT row tiles): 4 waves,
+// which may then use the whole register file of their SIMDs for the MT x 4 accumulator tiles.
 struct StreamRest {
     uint32_t* flags;
     uint32_t* counts;
@@ -791,8 +810,8 @@ struct StreamRest {
     int probe_delay;
 };
 
-template <int D, int MODE, bool ODD>
-__global__ void __launch_bounds__(kWave * 8)
+template <int D, int MODE, bool ODD, int MT>
+__global__ void __launch_bounds__(kWave * (MT > 1 ? 4 : 8))
 gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
                    _Float16* C, int packed, int n, int k, int split_rem, const StreamRest rest)
 {
@@ -802,9 +821,9 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.scales = scales;
     p.qzeros = qzeros;
     p.C = C;
-    p.m = packed & 31;
-    p.param_shift = (packed >> 5) & 3;
-    p.wk = (packed >> 7) & 31;
+    p.m = packed & 127;
+    p.param_shift = (packed >> 7) & 3;
+    p.wk = (packed >> 9) & 7;
     p.groups_base = (int)((unsigned)packed >> 12);
     p.groups_rem = (int)((unsigned)split_rem >> 16);
     p.n = n;
@@ -817,7 +836,7 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
     static_assert(!ODD || D == 2, "odd group counts need no code of their own at ring depth 1");
-    stream_body<D, MODE, ODD>(p);
+    stream_body<D, MODE, ODD, MT>(p);
 }
 
 // C <- 0 for the packed-fp16 atomic mode (a kernel, not a memset, so the call can be captured
@@ -967,7 +986,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
     if (!dp && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
-        const bool asked = tile_cols == kStreamTileCols;
+        // more than 16 rows come here only when the streaming kernel can take them
+        const bool asked = tile_cols == kStreamTileCols || m > 16;
         const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
         const bool shape_ok = group_size == 128 || group_size == 256;
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
@@ -984,6 +1004,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
             if (waves == 0) waves = kStreamStrips;
             if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
+            if (m > 16 * kStreamMaxRowTiles || (m > 16 && waves != kStreamStrips)) return W4A16_ERR_UNSUPPORTED;
             const int wk = waves / kStreamStrips;
             // the two k parts of an 8-wave workgroup meet at one barrier per group: equal counts
             if (S < 1 || S >= (1 << 16) || (long long)S * wk > cgroups || (wk > 1 && cgroups % (S * wk) != 0))
@@ -1172,19 +1193,20 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
 }
 
 // ---- launch of the streaming SplitK kernel
-template <int D, int MODE, bool ODD>
+template <int D, int MODE, bool ODD, int MT>
 static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_stream_kernel<D, MODE, ODD>;
+    auto kern = gemm_stream_kernel<D, MODE, ODD, MT>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
             return W4A16_ERR_HIP;
     }
     const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    if (a.m > 31 || a.groups_base >= (1 << 20) || a.split_k >= (1 << 16) || a.groups_rem >= (1 << 15))
+    if (a.m > 16 * MT || (MT > 1 && a.wk != 1) || a.wk > 2 || a.groups_base >= (1 << 20) || a.split_k >= (1 << 16) ||
+        a.groups_rem >= (1 << 15))
         return W4A16_ERR_UNSUPPORTED;
-    const int packed = a.m | a.param_shift << 5 | a.wk << 7 | (int)((unsigned)a.groups_base << 12);
+    const int packed = a.m | a.param_shift << 7 | a.wk << 9 | (int)((unsigned)a.groups_base << 12);
     const int split_rem = a.split_k | a.groups_rem << 16;
     StreamRest rest;
     rest.flags = a.flags;
@@ -1197,12 +1219,24 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
-template <int D, bool ODD>
+template <int D, bool ODD, int MT>
 static int launch_stream_mode(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
-    if (mode == kDirect) return launch_stream_one<D, kDirect, ODD>(a, lds_bytes, stream);
-    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, ODD>(a, lds_bytes, stream);
-    return launch_stream_one<D, kAtomicPkF16Phase, ODD>(a, lds_bytes, stream);
+    if (mode == kDirect) return launch_stream_one<D, kDirect, ODD, MT>(a, lds_bytes, stream);
+    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, ODD, MT>(a, lds_bytes, stream);
+    return launch_stream_one<D, kAtomicPkF16Phase, ODD, MT>(a, lds_bytes, stream);
+}
+
+template <int MT>
+static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
+{
+    // ring depth: two groups in flight per wave when every k part has at least two
+    if (a.groups_base >= 2 && g_stream_depth >= 2) {
+        if (a.groups_rem == 0 && a.groups_base % 2 == 0)
+            return launch_stream_mode<2, false, MT>(a, lds_bytes, mode, stream);
+        return launch_stream_mode<2, true, MT>(a, lds_bytes, mode, stream);
+    }
+    return launch_stream_mode<1, false, MT>(a, lds_bytes, mode, stream);
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
@@ -1210,6 +1244,7 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
                           uint32_t** phase);
 
 // tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
+// m <= 64; more than 16 rows need waves = 4.
 static int run_stream(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
                       int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream)
 {
@@ -1217,6 +1252,8 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     if (waves == 0) waves = kStreamStrips;
     if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
     const int wk = waves / kStreamStrips;
+    const int mt = (m + 15) / 16;  // row tiles
+    if (mt > kStreamMaxRowTiles || (mt > 1 && wk != 1)) return W4A16_ERR_UNSUPPORTED;
     const int groups = k / 128;
     // the two k parts of an 8-wave workgroup meet at one barrier per group: equal counts
     if (split_k < 1 || (long long)split_k * wk > groups || (wk > 1 && groups % (split_k * wk) != 0))
@@ -1244,7 +1281,7 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     a.param_shift = group_size == 256 ? 1 : 0;
     a.spin_limit = kSpinLimit;
     a.probe_delay = g_probe_delay;
-    const size_t lds_bytes = (size_t)wk * 2 * kChunkBytes + (size_t)waves * m * 64 * 4;
+    const size_t lds_bytes = (size_t)wk * 2 * mt * kChunkBytes + (size_t)waves * m * 64 * 4;
     int mode = kDirect;
     if (split_k > 1) {
         if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) {
@@ -1268,12 +1305,21 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
             mode = kAtomicPkF16;
         }
     }
-    // ring depth: two groups in flight per wave when every k part has at least two
-    if (a.groups_base >= 2 && g_stream_depth >= 2) {
-        if (a.groups_rem == 0 && a.groups_base % 2 == 0) return launch_stream_mode<2, false>(a, lds_bytes, mode, stream);
-        return launch_stream_mode<2, true>(a, lds_bytes, mode, stream);
+    switch (mt) {
+    case 1: return launch_stream_tiles<1>(a, lds_bytes, mode, stream);
+    case 2: return launch_stream_tiles<2>(a, lds_bytes, mode, stream);
+    case 3: return launch_stream_tiles<3>(a, lds_bytes, mode, stream);
+    default: return launch_stream_tiles<4>(a, lds_bytes, mode, stream);
     }
-    return launch_stream_mode<1, false>(a, lds_bytes, mode, stream);
+}
+
+// Can a call with these knobs use the streaming kernel with more than one row tile?
+static bool stream_rows_ok(int group_size, bool dp, int tile_cols, int waves, int reduce)
+{
+    return !dp && (group_size == 128 || group_size == 256) && (tile_cols == 0 || tile_cols == kStreamTileCols) &&
+           (waves == 0 || waves == kStreamStrips) &&
+           (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
+            reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE);
 }
 
 static void read_tuning_env()
@@ -1296,11 +1342,14 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (rc != W4A16_OK) return rc;
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
-    if (m > 16) {
-        // more than one MFMA row tile: one launch per 16 rows (each streams the weights again;
-        // the paper's regime is m <= 16, larger m is served for completeness)
-        for (int r = 0; r < m; r += 16) {
-            const int mm = m - r < 16 ? m - r : 16;
+    // More than 16 rows (beyond the paper's regime): the streaming kernel takes up to 64 rows as
+    // row tiles of one launch, so the weights stream once per 64 rows; whatever it does not
+    // cover (data-parallel kernel, group sizes below 128, the other tile widths and reductions)
+    // runs as one launch per 16 rows.
+    const int rows_per_launch = stream_rows_ok(group_size, dp, tile_cols, waves, reduce) ? 16 * kStreamMaxRowTiles : 16;
+    if (m > rows_per_launch) {
+        for (int r = 0; r < m; r += rows_per_launch) {
+            const int mm = m - r < rows_per_launch ? m - r : rows_per_launch;
             rc = run_gemm((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros, (_Float16*)C + (size_t)r * n, mm,
                           n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v);
             if (rc != W4A16_OK) return rc;
@@ -1426,8 +1475,13 @@ int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* t
     int rc = w4a16::check_args(m, n, k, group_size, dp ? 1 : req, false);
     if (rc != W4A16_OK) return rc;
     w4a16::Plan plan;
-    rc = w4a16::make_plan(m, n, k, group_size, dp != 0, req, tile_cols ? *tile_cols : 0, waves ? *waves : 0,
-                          reduce ? *reduce : 0, &plan);
+    // more rows than one launch takes: the plan of each launch
+    const int rows = w4a16::stream_rows_ok(group_size, dp != 0, tile_cols ? *tile_cols : 0, waves ? *waves : 0,
+                                           reduce ? *reduce : 0)
+                         ? 16 * w4a16::kStreamMaxRowTiles
+                         : 16;
+    rc = w4a16::make_plan(m < rows ? m : rows, n, k, group_size, dp != 0, req, tile_cols ? *tile_cols : 0,
+                          waves ? *waves : 0, reduce ? *reduce : 0, &plan);
     if (rc != W4A16_OK) return rc;
     if (split_k) *split_k = plan.split_k;
     if (tile_cols) *tile_cols = plan.tile_cols;

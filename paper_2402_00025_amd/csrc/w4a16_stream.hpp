@@ -19,6 +19,10 @@
 // requested D groups ahead (into a register ring of D quarters) and written to LDS at the end of
 // the group before the one that uses it; by then it has long arrived and the wait costs nothing.
 // LDS holds two chunks per k part (the one being read and the next one).
+//
+// More than 16 activation rows (up to 64) are row tiles of the same workgroup: a chunk grows to
+// one 4 KiB block per row tile, and the weights a wave has unpacked for an MFMA step are used
+// once per row tile, so the weight stream and the unpacking are paid once for all rows.
 #pragma once
 #include "w4a16_device.hpp"
 
@@ -36,7 +40,7 @@ struct StreamArgs {
     int m, n, k;
     int tiles;            // 256-column workgroup tiles = ceil(n / 256)
     int split_k;
-    int wk;               // k parts per workgroup; working waves = 4 * wk
+    int wk;               // k parts per workgroup; working waves = 4 * wk (2 only with m <= 16)
     // compute groups (128 consecutive k) per k part: part i = slice * wk + kpart gets groups_base,
     // the first groups_rem parts one more (groups_rem > 0 only with wk == 1); groups_base >= D
     int groups_base;
@@ -48,7 +52,8 @@ struct StreamArgs {
 
 constexpr int kStreamStrips = 4;
 constexpr int kStreamTileCols = 64 * kStreamStrips;
-constexpr int kChunkBytes = 16 * 128 * 2;  // one activation chunk in LDS: 16 rows x 128 k, fp16
+constexpr int kChunkBytes = 16 * 128 * 2;  // one row tile of an activation chunk in LDS: 16 rows x 128 k, fp16
+constexpr int kStreamMaxRowTiles = 4;      // row tiles of 16 activation rows per workgroup
 
 // LDS layout of a chunk: one 16-byte slot per (kc = 8 consecutive k, row): slot kc * 16 + (row ^ kc).
 // The xor makes both access patterns conflict-free: a writing wave has, in every 16 lanes, one
@@ -80,22 +85,26 @@ __device__ __forceinline__ void ring_prime(WeightRing<D>& ring, const LaneMap& l
 }
 
 // What stays fixed for a lane while it streams: where its quarter of a chunk comes from and goes
-// to, and where its MFMA operands of the four steps of a group lie in a chunk.
+// to, and where its MFMA operands of the four steps of a group lie in a chunk.  MT = row tiles
+// of 16 activation rows (m <= 16 MT): a chunk then is MT blocks of 4 KiB, one per row tile, and
+// every wave fetches its quarter (four rows) of each.
+template <int MT>
 struct StreamLane {
-    uint32_t a_voff;   // byte offset of its 16 bytes of A inside a chunk quarter's row, or outside the buffer
-    uint32_t a_soff0;  // byte offset of chunk 0 of this wave's k range
-    int wslot;         // LDS byte offset of the slot it writes
-    int roff[4];       // LDS byte offsets of the slots it reads, per MFMA step
-    char* ring;        // the k part's two chunks in LDS
+    uint32_t a_voff[MT];  // per row tile: byte offset of its 16 bytes of A inside a chunk quarter's row, or outside the buffer
+    uint32_t a_soff0;     // byte offset of chunk 0 of this wave's k range
+    int wslot;            // LDS byte offset (inside a row tile's block) of the slot it writes
+    int roff[4];          // LDS byte offsets (inside a row tile's block) of the slots it reads, per MFMA step
+    char* ring;           // the k part's two chunks in LDS
 };
 
 // One compute group (128 k) of a wave out of ring slot H; `cc` is its index inside the wave's
-// range.  REFILL: request the weights and the chunk quarter of group cc + D.  NEXT: there is a
-// group cc + 1: publish its chunk quarter, meet the other waves, fetch the next operands.
-template <int D, int H, bool REFILL, bool NEXT>
-__device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in)[D], u32x4_t (&a)[4],
-                                             const StreamLane& sl, const LaneMap& lm, const Tensors& t,
-                                             uint32_t magic, int cc, int g_begin, float4_t (&acc)[4])
+// range.  REFILL: request the weights and the chunk quarters of group cc + D.  NEXT: there is a
+// group cc + 1: publish its chunk quarters, meet the other waves, fetch the next operands.
+// The unpacked weights of a step serve all MT row tiles.
+template <int D, int H, bool REFILL, bool NEXT, int MT>
+__device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
+                                             const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
+                                             uint32_t magic, int cc, int g_begin, float4_t (&acc)[MT][4])
 {
     ZeroConst zc[4];
     float sc[4];
@@ -107,15 +116,19 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
     if constexpr (REFILL) {
         __builtin_amdgcn_sched_barrier(0);
         issue_params<4>(ring.par[H], lm, t, g_begin + cc + D);
-        a_in[H] = __builtin_amdgcn_raw_buffer_load_b128(t.A, sl.a_voff, sl.a_soff0 + (uint32_t)(cc + D) * 256u, 0);
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt)
+            a_in[H][rt] = __builtin_amdgcn_raw_buffer_load_b128(t.A, sl.a_voff[rt],
+                                                                sl.a_soff0 + (uint32_t)(cc + D) * 256u, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
-    float4_t tile[4];
+    float4_t tile[MT][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) tile[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tile[rt][j] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const half8_t a8 = __builtin_bit_cast(half8_t, a[it]);
         half8_t b8[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) b8[j] = unpack_shift(ring.w[H][it].v[j], zc[j], magic);
@@ -125,29 +138,40 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) tile[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8[j], tile[j], 0, 0, 0);
+        for (int rt = 0; rt < MT; ++rt) {
+            const half8_t a8 = __builtin_bit_cast(half8_t, a[rt][it]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                tile[rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, b8[j], tile[rt][j], 0, 0, 0);
+        }
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] += sc[j] * tile[j];
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[rt][j] += sc[j] * tile[rt][j];
     if constexpr (NEXT) {
-        char* buf = sl.ring + ((cc + 1) & 1) * kChunkBytes;
-        *(half8_t*)(buf + sl.wslot) = permute_activations(a_in[(H + 1) % D]);
+        char* buf = sl.ring + ((cc + 1) & 1) * (MT * kChunkBytes);
+#pragma unroll
+        for (int rt = 0; rt < MT; ++rt)
+            *(half8_t*)(buf + rt * kChunkBytes + sl.wslot) = permute_activations(a_in[(H + 1) % D][rt]);
         __syncthreads();
 #pragma unroll
-        for (int it = 0; it < 4; ++it) a[it] = *(const u32x4_t*)(buf + sl.roff[it]);
+        for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+            for (int it = 0; it < 4; ++it) a[rt][it] = *(const u32x4_t*)(buf + rt * kChunkBytes + sl.roff[it]);
     }
 }
 
-template <int D, int H, bool REFILL>
-__device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_in)[D], u32x4_t (&a)[4],
-                                              const StreamLane& sl, const LaneMap& lm, const Tensors& t,
-                                              uint32_t magic, int c0, int g_begin, float4_t (&acc)[4])
+template <int D, int H, bool REFILL, int MT>
+__device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
+                                              const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
+                                              uint32_t magic, int c0, int g_begin, float4_t (&acc)[MT][4])
 {
     if constexpr (H < D) {
         // the last group of the wave has no successor
         constexpr bool kNext = REFILL || (H + 1 < D);
-        stream_group<D, H, REFILL, kNext>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc);
-        stream_groups<D, H + 1, REFILL>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc);
+        stream_group<D, H, REFILL, kNext, MT>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc);
+        stream_groups<D, H + 1, REFILL, MT>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc);
     }
 }
 

@@ -238,6 +238,56 @@ def test_more_than_16_rows(oracle):
     assert_parity(p.result(), Cref, "m=40 dp")
 
 
+ROW_TILES = [
+    # m, n, k, g, split_k, tile_cols, waves, reduce: more than 16 rows are row tiles of one launch
+    # of the streaming kernel (up to 64 rows), further rows further launches
+    (17, 264, 1024, 128, 2, 0, 0, 0),      # two row tiles, the second with one row
+    (32, 256, 1024, 128, 4, 256, 4, 5),    # two full tiles, phase protocol
+    (33, 328, 1408, 128, 2, 256, 4, 2),    # three tiles, 6 and 5 groups per part, fill kernel
+    (48, 200, 2048, 128, 1, 0, 0, 0),      # three tiles, direct store
+    (50, 264, 1664, 128, 4, 0, 0, 0),      # four tiles, 4,3,3,3 groups
+    (64, 512, 2048, 128, 8, 256, 4, 5),    # four full tiles, 2 groups per part
+    (64, 136, 1024, 128, 8, 0, 0, 0),      # one group per part: ring depth 1
+    (64, 264, 1280, 256, 2, 0, 0, 0),      # group_size 256
+    (65, 264, 1024, 128, 2, 0, 0, 0),      # 64 rows in one launch, one more in a second
+    (150, 200, 1024, 128, 0, 0, 0, 0),     # 64 + 64 + 22, the library's split
+    (40, 264, 1024, 64, 2, 0, 0, 0),       # group_size 64: one launch per 16 rows
+    (40, 264, 1024, 128, 2, 64, 2, 1),     # 64-column tiles asked for: one launch per 16 rows
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves,reduce", ROW_TILES)
+def test_row_tiles(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
+    A, qw, s, qz = random_case(m, n, k, g, seed=700 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, reduce)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} g={g} S={split_k} tile={tile_cols} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("split_k", [1, 4])
+def test_row_tiles_one_hot_bit_exact(split_k):
+    """64 one-hot rows per call: every row tile must pick its own rows of A and write its own
+    rows of C; swept over all k."""
+    m, n, k, g = 64, 264, 1024, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=49)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 5 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), split_k, 0, 0, 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 def test_phase_mode_call_sequences(oracle):
     """The in-kernel zeroing protocol keeps per-tile state between calls: run calls of different
     shapes, split factors and tile widths back to back into NaN-filled outputs, twice each,
