@@ -121,6 +121,12 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
                                  ctypes.c_void_p(current_stream().cuda_stream))
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_ex")
+    elif kind == "streamk":
+        def call(i):
+            qw, s, qz = ptrs[i % nsets]
+            rc = L.w4a16_gemm_streamk(A, qw, s, qz, C, m, n, k, g, 0, ctypes.c_void_p(current_stream().cuda_stream))
+            if rc:
+                raise binding.W4A16Error(rc, "w4a16_gemm_streamk")
     else:
         def call(i):
             qw, s, qz = ptrs[i % nsets]
@@ -364,11 +370,12 @@ def main():
                 pl = binding.w4a16_plan(mm, n_, k_, g)
                 _, e = time_calls(make_call(wm, "splitk", split_k=0), 200, 30)
                 _, e_dp = time_calls(make_call(wm, "dp"), 200, 30)
+                _, e_sk = time_calls(make_call(wm, "streamk"), 200, 30)
                 rows.append({"m": mm, "n": n_, "k": k_, "plan": pl, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
-                             "speedup_over_dp": e_dp / e, "splitk_GBps": wm.bytes / e / 1e9,
+                             "streamk_us": e_sk * 1e6, "speedup_over_dp": e_dp / e, "splitk_GBps": wm.bytes / e / 1e9,
                              "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
                 log(f"[bench] m={mm:2d} n={n_} k={k_}: splitk {e * 1e6:7.2f} us (S={pl['split_k']}, tile {pl['tile_cols']}), "
-                    f"dp {e_dp * 1e6:7.2f} us, x{e_dp / e:.2f}, {wm.bytes / e / 1e9:.0f} GB/s")
+                    f"dp {e_dp * 1e6:7.2f} us, x{e_dp / e:.2f}, streamk {e_sk * 1e6:7.2f} us, {wm.bytes / e / 1e9:.0f} GB/s")
             del wb
         extra["decoder_projection_shapes"] = rows
         # more than 16 rows: row tiles of one launch (up to 64 rows share one pass over the weights)

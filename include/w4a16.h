@@ -87,6 +87,17 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
                   int m, int n, int k, int group_size, void* stream);
 
 /*
+ * StreamK decomposition (the paper's Conclusion names it as the successor of SplitK to explore):
+ * `workgroups` persistent workgroups (0 = library default, one per compute unit) share the
+ * iterations (256-column tile x 128 consecutive k) evenly, whatever the shape; each adds the
+ * pieces of the tiles it touched to C with packed-fp16 atomic adds (C zeroed by a fill kernel
+ * on the same stream) and stores the tiles it computed alone.  group_size 128 or 256
+ * (W4A16_ERR_UNSUPPORTED otherwise); no scratch; more than 16 rows run one launch per 16.
+ */
+int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                       int m, int n, int k, int group_size, int workgroups, void* stream);
+
+/*
  * Same operations with the tuning knobs exposed (0 = library default for each):
  *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
  *              waves divide the workgroup's k range), or 256 (SplitK only, group_size 128 or

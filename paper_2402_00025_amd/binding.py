@@ -21,7 +21,8 @@ REDUCE_ATOMIC_PK_F16_PHASE = 5
 
 #: every symbol include/w4a16.h declares
 EXPORTS = (
-    "w4a16_gemm", "w4a16_gemm_dp", "w4a16_gemm_ex", "w4a16_gemm_dp_ex", "w4a16_plan", "w4a16_check",
+    "w4a16_gemm", "w4a16_gemm_dp", "w4a16_gemm_streamk", "w4a16_gemm_ex", "w4a16_gemm_dp_ex", "w4a16_plan",
+    "w4a16_check",
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts",
 )
@@ -57,6 +58,7 @@ def lib() -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     L.w4a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w4a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
+    L.w4a16_gemm_streamk.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w4a16_gemm_ex.argtypes = [vp] * 5 + [ci] * 8 + [vp]
     L.w4a16_gemm_dp_ex.argtypes = [vp] * 5 + [ci] * 6 + [vp]
     L.w4a16_plan.argtypes = [ci] * 5 + [ip] * 4
@@ -114,6 +116,11 @@ def w4a16_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, stre
 def w4a16_gemm_dp(A, qweight, scales, qzeros, C, m, n, k, group_size, stream=None) -> None:
     _check(lib().w4a16_gemm_dp(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size,
                                _stream(stream)), "w4a16_gemm_dp")
+
+
+def w4a16_gemm_streamk(A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups=0, stream=None) -> None:
+    _check(lib().w4a16_gemm_streamk(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size,
+                                    workgroups, _stream(stream)), "w4a16_gemm_streamk")
 
 
 def w4a16_gemm_ex(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, tile_cols=0, waves=0, reduce=0,

@@ -839,6 +839,158 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     stream_body<D, MODE, ODD, MT>(p);
 }
 
+// StreamK decomposition (the paper's Conclusion names it as the successor of SplitK to explore):
+// a fixed number of persistent workgroups, about one or two per compute unit, divide the
+// iteration space evenly.  An iteration is one compute group (128 k) of one 256-column tile;
+// iterations are numbered tile-major, and workgroup w takes [w T / W, (w + 1) T / W) of the
+// T = tiles x groups iterations: a run that may end one tile and begin the next.  Every piece
+// of a tile (a "segment") is computed like a k slice of the streaming SplitK kernel and added
+// to C with packed-fp16 atomics (C zeroed by the fill kernel); a segment that is a whole tile
+// is stored.  Segments have any length >= 1, so the drain of the two-group ring handles one,
+// two or three groups left.
+__device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_raw, int tile, int g_begin, int G,
+                                                int groups)
+{
+    constexpr int D = 2;
+    constexpr uint32_t kOutside = 0xFFFFFF00u;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int strip = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int m = p.m, n = p.n, k = p.k;
+    const int n0 = (tile * kStreamStrips + strip) * 64;
+
+    const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
+    const uint32_t qgroups = (uint32_t)groups >> p.param_shift;
+    Tensors tensors;
+    tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 8) * (uint32_t)n * 4u);
+    tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / 8) * 4u);
+    tensors.m = m;
+    tensors.n = n;
+    tensors.k = k;
+    tensors.param_shift = p.param_shift;
+    const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
+
+    StreamLane<1> sl;
+    const int prow = 4 * strip + (lane >> 4);
+    sl.a_voff[0] = prow < m ? ((uint32_t)prow * (uint32_t)k + 8u * (uint32_t)(lane & 15)) * 2u : kOutside;
+    sl.a_soff0 = (uint32_t)g_begin * 256u;
+    sl.wslot = chunk_slot_bytes(lane & 15, prow);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) sl.roff[it] = chunk_slot_bytes(4 * it + (lane >> 4), lane & 15);
+    sl.ring = lds_raw;
+
+    // prologue as in stream_body.  The ring is primed with two groups even when the segment has
+    // one: the second then belongs to the next segment of the tile or lies behind the end of k
+    // (the buffer returns zeros); it is loaded and not used.
+    u32x4_t a_in[D][1];
+#pragma unroll
+    for (int h = 0; h < D; ++h)
+        a_in[h][0] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff[0], sl.a_soff0 + (uint32_t)h * 256u, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    WeightRing<D> ring;
+    ring_prime<D, 0>(ring, lm, tensors, g_begin);
+    *(half8_t*)(sl.ring + sl.wslot) = permute_activations(a_in[0][0]);
+    __syncthreads();
+    u32x4_t a[1][4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) a[0][it] = *(const u32x4_t*)(sl.ring + sl.roff[it]);
+    float4_t acc[1][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[0][j] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const uint32_t magic = magic_1024x2();
+
+    int c = 0;
+    for (; c + 2 * D <= G; c += D) stream_groups<D, 0, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+    const int left = G - c;  // 1 (only when G == 1), 2 or 3
+    if (left == 3) {
+        stream_group<D, 0, true, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        stream_group<D, 1, false, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
+        stream_group<D, 0, false, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
+    } else if (left == 2) {
+        stream_groups<D, 0, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+    } else {
+        stream_group<D, 0, false, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+    }
+
+    // the tile -> LDS; column pairs leave as in stream_body
+    float* red_all = (float*)(lds_raw + 2 * kChunkBytes);
+    float* red = red_all + (size_t)strip * m * 64;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * (lane >> 4) + r;
+        if (row < m)
+            *(float4_t*)(red + row * 64 + 4 * (lane & 15)) = float4_t{acc[0][0][r], acc[0][1][r], acc[0][2][r], acc[0][3][r]};
+    }
+    __syncthreads();
+    const bool whole_tile = G == groups;
+    const int cp = tid & 127;
+    const int st = cp >> 5, c2 = 2 * (cp & 31);
+    const int col = tile * kStreamTileCols + st * 64 + c2;
+    constexpr int rows_per_pass = kStreamStrips * kWave >> 7;
+    const float* src0 = red_all + st * (m * 64) + c2;
+    const bool col_ok = col < n;
+    for (int row0 = tid >> 7; row0 < m; row0 += 4 * rows_per_pass) {
+        float2 v[4];
+        uint32_t off[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = row0 + i * rows_per_pass;
+            const int rc = row < m ? row : row0;
+            off[i] = (row < m && col_ok) ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            v[i] = *(const float2*)(src0 + rc * 64);
+        }
+        if (whole_tile) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const half2_t h = {(_Float16)v[i].x, (_Float16)v[i].y};
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(h, rs_c, off[i], 0, 0);
+            }
+        }
+    }
+}
+
+// Kernel entry of the StreamK variant: 4 waves (one 256-column tile wide); `workgroups` is the
+// launch's grid size (an argument, so that no launch-geometry read is needed).
+//   packed = m | param_shift << 7
+__global__ void __launch_bounds__(kWave* kStreamStrips)
+gemm_streamk_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
+                    _Float16* C, int packed, int n, int k, int workgroups)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    StreamArgs p;
+    p.A = A;
+    p.qweight = qweight;
+    p.scales = scales;
+    p.qzeros = qzeros;
+    p.C = C;
+    p.m = packed & 127;
+    p.param_shift = (packed >> 7) & 3;
+    p.n = n;
+    p.k = k;
+    const int groups = k / 128;
+    const long long total = (long long)((n + kStreamTileCols - 1) / kStreamTileCols) * groups;
+    const long long w = blockIdx.x;
+    long long it = w * total / workgroups;
+    const long long end = (w + 1) * total / workgroups;
+    while (it < end) {
+        const int tile = (int)(it / groups);
+        const int g_begin = (int)(it - (long long)tile * groups);
+        const long long rest = end - it;
+        const int G = rest < groups - g_begin ? (int)rest : groups - g_begin;
+        streamk_segment(p, lds_raw, tile, g_begin, G, groups);
+        it += G;
+        __syncthreads();  // the next segment reuses the chunks and the tile in LDS
+    }
+}
+
 // C <- 0 for the packed-fp16 atomic mode (a kernel, not a memset, so the call can be captured
 // in a HIP graph).
 __global__ void fill_zero_kernel(uint32_t* p, size_t words)
@@ -925,6 +1077,8 @@ constexpr int kSpinLimit = 1 << 17;
 static int g_probe_delay = 2;
 // Deepest weight ring (compute groups in flight per wave) the streaming kernel may use: 1 or 2.
 static int g_stream_depth = 2;
+// Persistent workgroups of the StreamK variant when the caller leaves the choice to the library.
+static int g_streamk_blocks = 256;
 // Fewest workgroups that the plan accepts for a launch whose waves each take a long run of groups.
 static int g_stream_min_blocks = 160;
 static DeviceScratch g_scratch[kMaxDevices];
@@ -1322,6 +1476,35 @@ static bool stream_rows_ok(int group_size, bool dp, int tile_cols, int waves, in
             reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE);
 }
 
+// StreamK variant: `workgroups` persistent workgroups (0 = one per compute unit, the best count
+// in sweeps; capped by the number of iterations).  group_size 128 or 256; m <= 16 per launch.
+static int run_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                       int n, int k, int group_size, int workgroups, hipStream_t stream)
+{
+    if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
+    if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+    const int groups = k / 128;
+    const int tiles = (n + kStreamTileCols - 1) / kStreamTileCols;
+    const long long total = (long long)tiles * groups;
+    if (workgroups < 0) return W4A16_ERR_UNSUPPORTED;
+    if (workgroups == 0) workgroups = g_streamk_blocks;
+    if (workgroups > total) workgroups = (int)total;
+    // no tile is shared between workgroups: nothing to add up, nothing to zero
+    const bool whole_tiles = total % workgroups == 0 && (total / workgroups) % groups == 0;
+    if (!whole_tiles) {
+        const size_t words = (size_t)m * n / 2;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                           (uint32_t*)C, words);
+        if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    }
+    const int packed = m | (group_size == 256 ? 1 : 0) << 7;
+    const size_t lds_bytes = 2 * kChunkBytes + (size_t)kStreamStrips * m * 64 * 4;
+    hipLaunchKernelGGL(gemm_streamk_kernel, dim3((unsigned)workgroups), dim3(kStreamStrips * kWave), lds_bytes, stream,
+                       (const _Float16*)A, (const uint32_t*)qweight, (const _Float16*)scales,
+                       (const uint32_t*)qzeros, (_Float16*)C, packed, n, k, workgroups);
+    return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
+}
+
 static void read_tuning_env()
 {
     static bool done = false;
@@ -1330,6 +1513,7 @@ static void read_tuning_env()
     if (const char* e = getenv("W4A16_PROBE_DELAY")) g_probe_delay = atoi(e);
     if (const char* e = getenv("W4A16_STREAM_DEPTH")) g_stream_depth = atoi(e);
     if (const char* e = getenv("W4A16_STREAM_MIN_BLOCKS")) g_stream_min_blocks = atoi(e);
+    if (const char* e = getenv("W4A16_STREAMK_BLOCKS")) g_streamk_blocks = atoi(e) > 0 ? atoi(e) : g_streamk_blocks;
 }
 
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
@@ -1451,6 +1635,25 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 {
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
                            true, stream);
+}
+
+int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                       int n, int k, int group_size, int workgroups, void* stream)
+{
+    if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
+    w4a16::read_tuning_env();
+    int rc = w4a16::check_args(m, n, k, group_size, 1);
+    if (rc != W4A16_OK) return rc;
+    if (!w4a16::aligned16(A) || !w4a16::aligned16(qweight) || !w4a16::aligned16(scales) || !w4a16::aligned16(qzeros) ||
+        !w4a16::aligned16(C))
+        return W4A16_ERR_UNSUPPORTED;
+    for (int r = 0; r < m; r += 16) {
+        const int mm = m - r < 16 ? m - r : 16;
+        rc = w4a16::run_streamk((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros,
+                                (_Float16*)C + (size_t)r * n, mm, n, k, group_size, workgroups, (hipStream_t)stream);
+        if (rc != W4A16_OK) return rc;
+    }
+    return W4A16_OK;
 }
 
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,

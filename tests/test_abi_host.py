@@ -76,6 +76,10 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 48, 0, 0, None) == b.ERR_UNSUPPORTED   # tile_cols
     assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 64, 3, 0, None) == b.ERR_UNSUPPORTED   # waves
     assert L.w4a16_gemm_ex(p, p, p, p, p, 1, 1024, 1024, 128, 4, 64, 2, 9, None) == b.ERR_UNSUPPORTED   # reduce
+    assert L.w4a16_gemm_streamk(p, None, p, p, p, 1, 1024, 1024, 128, 0, None) == b.ERR_NULL
+    assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1000, 128, 0, None) == b.ERR_SHAPE
+    assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1024, 64, 0, None) == b.ERR_UNSUPPORTED   # group_size
+    assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1024, 128, -2, None) == b.ERR_UNSUPPORTED  # workgroups
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL

@@ -482,6 +482,65 @@ def test_auto_plan_awkward_k(oracle):
         assert_parity(p.result(), Cref, f"dp m={m} n={n}")
 
 
+# ------------------------------------------------------------------ StreamK variant
+STREAMK = [
+    # m, n, k, g, workgroups
+    (16, 512, 1024, 128, 1),      # one workgroup walks both tiles: whole tiles, stored
+    (16, 512, 1024, 128, 2),      # one tile each: no fill kernel
+    (16, 512, 1024, 128, 3),      # 16 iterations over 3: segments of 5, 3 + 2, 6
+    (16, 512, 1024, 128, 16),     # one group per workgroup
+    (16, 512, 1024, 128, 5),      # 3, 3, 2 + 1, 3, 4
+    (7, 328, 1408, 128, 4),       # 22 iterations, ragged second tile
+    (1, 264, 2048, 128, 7),
+    (16, 1032, 1536, 128, 13),    # 5 tiles x 12 groups over 13
+    (9, 520, 1280, 256, 6),       # group_size 256
+    (16, 256, 4096, 128, 0),      # library default: more workgroups than iterations
+    (16, 2048, 2048, 128, 0),
+    (40, 520, 1024, 128, 5),      # three launches of 16, 16, 8 rows
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,workgroups", STREAMK)
+def test_streamk(oracle, m, n, k, g, workgroups):
+    A, qw, s, qz = random_case(m, n, k, g, seed=800 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_streamk(*p.args(), workgroups)
+        assert_parity(p.result(), Cref, f"streamk m={m} n={n} k={k} g={g} W={workgroups} call {call}")
+
+
+@pytest.mark.parametrize("workgroups", [1, 3, 5, 7, 16, 24])
+def test_streamk_one_hot_bit_exact(workgroups):
+    """One non-zero term per row, swept over all k: every iteration belongs to exactly one
+    segment of exactly one workgroup."""
+    m, n, k, g = 16, 520, 1024, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=51)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_streamk(*p.args(), workgroups)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+def test_streamk_full_size(oracle):
+    """The headline shape and a non-square one at full size, library default."""
+    for (m, n, k) in ((16, 4096, 4096), (16, 5120, 13824)):
+        x = make_inputs(m, n, k, 128, seed=3)
+        Cref, _ = oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, 128)
+        p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+        b.w4a16_gemm_streamk(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"streamk m={m} n={n} k={k}")
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
