@@ -1195,13 +1195,16 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         int parts = 1;  // k parts of a column tile = split_k * waves
         if (packed_bytes <= (8ll << 20)) {
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
-        } else if (m <= 2 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20)) {
-            // one group per wave; the few rows keep the atomic traffic of the many slices small
-            parts = cgroups;
         } else {
             // four waves per workgroup and the fewest k slices that give 160 workgroups
             parts = cgroups < 4 ? cgroups : 4;
             while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < g_stream_min_blocks) parts *= 2;
+            // A single row makes the atomic traffic of many slices negligible: where the count
+            // above sits badly on 256 compute units, one group per wave does better.
+            const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
+            if (m == 1 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
+                (blocks < 200 || blocks > 320))
+                parts = cgroups;
         }
         int w = waves != 0 ? waves : parts < 4 ? parts : 4;
         if (w > parts) w = parts;
