@@ -28,7 +28,9 @@
  * partial sum and ascending partition index across partial sums.
  *
  * Parity status: all functions below are pinned by tests/test_oracle_*.py against closed
- * forms, exact-rational brute force, numpy's float16 and matmul, and pack/unpack bijection.
+ * forms, exact-rational brute force, numpy's float16 and matmul, and pack/unpack bijection;
+ * the functions for other field widths (end of the file) by hand-written words, numpy byte
+ * views, exact rationals, closed forms, numpy's matmul and, at 4 bits, the 4-bit functions.
  * Unpinned: agreement with the bit layout of the authors' own kernel and with real GPTQ
  * checkpoints (the paper prints neither).
  */
@@ -258,6 +260,115 @@ int w4a16_oracle_gemm(const uint16_t* A, const int32_t* qweight, const uint16_t*
         free(part64);
         free(part32);
         free(wrow);
+    }
+    return used;
+}
+
+/* ---------------------------------------------------------------- other field widths
+ *
+ * Section 2 of the paper remarks that the method carries over to other n-bit quantisation
+ * schemes.  The same layout with fields of `bits` bits (2, 4 or 8), f = 32 / bits per word:
+ *     q[kk][j]  = field (kk % f) of qweight[kk / f][j],   qweight int32 [k / f, n]
+ *     z[gi][j]  = field (j % f)  of qzeros[gi][j / f],    qzeros  int32 [k / g, n / f]
+ * field i = bits [bits * i, bits * i + bits - 1];  W = (q - z) * s as before.
+ * Written on their own (they share nothing with the 4-bit functions above), so that
+ * bits = 4 can be checked against those. */
+
+static inline int bits_ok(int bits) { return bits == 2 || bits == 4 || bits == 8; }
+
+static inline int field_of_width(const int32_t* words, size_t word_index, int field, int bits)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    return (int)(((uint32_t)words[word_index] >> (bits * field)) & mask);
+}
+
+int w4a16_oracle_unpack_qweight_bits(const int32_t* qweight, uint8_t* q, int n, int k, int bits)
+{
+    if (!bits_ok(bits)) return -1;
+    const int f = 32 / bits;
+    for (int kk = 0; kk < k; ++kk)
+        for (int j = 0; j < n; ++j)
+            q[(size_t)kk * n + j] = (uint8_t)field_of_width(qweight, (size_t)(kk / f) * n + j, kk % f, bits);
+    return 0;
+}
+
+int w4a16_oracle_unpack_qzeros_bits(const int32_t* qzeros, uint8_t* z, int n, int groups, int bits)
+{
+    if (!bits_ok(bits)) return -1;
+    const int f = 32 / bits;
+    for (int gi = 0; gi < groups; ++gi)
+        for (int j = 0; j < n; ++j)
+            z[(size_t)gi * n + j] = (uint8_t)field_of_width(qzeros, (size_t)gi * (n / f) + j / f, j % f, bits);
+    return 0;
+}
+
+int w4a16_oracle_pack_qweight_bits(const uint8_t* q, int32_t* qweight, int n, int k, int bits)
+{
+    if (!bits_ok(bits)) return -1;
+    const int f = 32 / bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    for (int r = 0; r < k / f; ++r)
+        for (int j = 0; j < n; ++j) {
+            uint32_t word = 0;
+            for (int i = 0; i < f; ++i) word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * i);
+            qweight[(size_t)r * n + j] = (int32_t)word;
+        }
+    return 0;
+}
+
+int w4a16_oracle_pack_qzeros_bits(const uint8_t* z, int32_t* qzeros, int n, int groups, int bits)
+{
+    if (!bits_ok(bits)) return -1;
+    const int f = 32 / bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    for (int gi = 0; gi < groups; ++gi)
+        for (int c = 0; c < n / f; ++c) {
+            uint32_t word = 0;
+            for (int i = 0; i < f; ++i) word |= ((uint32_t)z[(size_t)gi * n + f * c + i] & mask) << (bits * i);
+            qzeros[(size_t)gi * (n / f) + c] = (int32_t)word;
+        }
+    return 0;
+}
+
+/* Cref (fp64 [m, n], required) and C16 (fp16 [m, n], may be NULL) <- A . W, the definition:
+ * every product exact in fp64 ((q - z) * s is exact in fp32: at most 9 + 11 significant bits),
+ * summed over k in ascending order in an fp64 accumulator.  Returns the OpenMP threads used or
+ * a negative number on bad arguments. */
+int w4a16_oracle_gemm_bits(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
+                           const int32_t* qzeros, double* Cref, uint16_t* C16,
+                           int m, int n, int k, int group_size, int bits, int threads)
+{
+    if (!A || !qweight || !scales || !qzeros || !Cref) return -1;
+    if (!bits_ok(bits)) return -5;
+    const int f = 32 / bits;
+    if (m < 1 || n < f || n % f || group_size < f || group_size % f || k < group_size || k % group_size) return -2;
+
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < n; ++j) {
+        for (int i = 0; i < m; ++i) {
+            double sum = 0.0;
+            for (int kk = 0; kk < k; ++kk) {
+                const int gi = kk / group_size;
+                const int qv = field_of_width(qweight, (size_t)(kk / f) * n + j, kk % f, bits);
+                const int zv = field_of_width(qzeros, (size_t)gi * (n / f) + j / f, j % f, bits);
+                const float sv = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);
+                const float wv = (float)(qv - zv) * sv; /* exact */
+                const float av = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
+                sum += (double)av * (double)wv;
+            }
+            Cref[(size_t)i * n + j] = sum;
+            if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(sum);
+        }
     }
     return used;
 }

@@ -60,6 +60,16 @@ class Oracle:
         lib.w4a16_oracle_dequant.restype = None
         lib.w4a16_oracle_gemm.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 8
         lib.w4a16_oracle_gemm.restype = ctypes.c_int
+        for name in ("unpack_qweight_bits", "unpack_qzeros_bits"):
+            fn = getattr(lib, "w4a16_oracle_" + name)
+            fn.argtypes = [_i32p, _u8p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        for name in ("pack_qweight_bits", "pack_qzeros_bits"):
+            fn = getattr(lib, "w4a16_oracle_" + name)
+            fn.argtypes = [_u8p, _i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        lib.w4a16_oracle_gemm_bits.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 6
+        lib.w4a16_oracle_gemm_bits.restype = ctypes.c_int
         self.lib = lib
 
     # ---- fp16 conversions (round to nearest even; the paper does not name a mode)
@@ -154,6 +164,74 @@ class Oracle:
         return Cref, C16
 
 
+    # ---- other field widths (paper Section 2: the method carries over to other n-bit schemes)
+    def unpack_qweight_bits(self, qweight: np.ndarray, bits: int) -> np.ndarray:
+        """int32 [k/f, n] -> uint8 [k, n], f = 32 / bits fields per word along k."""
+        qweight = _c(qweight, np.int32)
+        r, n = qweight.shape
+        f = 32 // bits
+        q = np.empty((r * f, n), np.uint8)
+        if self.lib.w4a16_oracle_unpack_qweight_bits(_ptr(qweight, ctypes.c_int32), _ptr(q, ctypes.c_uint8), n, r * f, bits):
+            raise OracleError("bits must be 2, 4 or 8")
+        return q
+
+    def unpack_qzeros_bits(self, qzeros: np.ndarray, bits: int) -> np.ndarray:
+        """int32 [groups, n/f] -> uint8 [groups, n]."""
+        qzeros = _c(qzeros, np.int32)
+        g, c = qzeros.shape
+        f = 32 // bits
+        z = np.empty((g, c * f), np.uint8)
+        if self.lib.w4a16_oracle_unpack_qzeros_bits(_ptr(qzeros, ctypes.c_int32), _ptr(z, ctypes.c_uint8), c * f, g, bits):
+            raise OracleError("bits must be 2, 4 or 8")
+        return z
+
+    def pack_qweight_bits(self, q: np.ndarray, bits: int) -> np.ndarray:
+        q = _c(q, np.uint8)
+        k, n = q.shape
+        f = 32 // bits
+        assert k % f == 0
+        out = np.empty((k // f, n), np.int32)
+        if self.lib.w4a16_oracle_pack_qweight_bits(_ptr(q, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, k, bits):
+            raise OracleError("bits must be 2, 4 or 8")
+        return out
+
+    def pack_qzeros_bits(self, z: np.ndarray, bits: int) -> np.ndarray:
+        z = _c(z, np.uint8)
+        g, n = z.shape
+        f = 32 // bits
+        assert n % f == 0
+        out = np.empty((g, n // f), np.int32)
+        if self.lib.w4a16_oracle_pack_qzeros_bits(_ptr(z, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, g, bits):
+            raise OracleError("bits must be 2, 4 or 8")
+        return out
+
+    def gemm_bits(self, A, qweight, scales, qzeros, group_size: int, bits: int, threads: int = 0):
+        """Cref (float64 [m, n]) and its fp16 rounding for fields of `bits` bits: the definition,
+        fp64 accumulation in ascending k."""
+        A = _c(A, np.float16)
+        qweight = _c(qweight, np.int32)
+        scales = _c(scales, np.float16)
+        qzeros = _c(qzeros, np.int32)
+        f = 32 // bits
+        m, k = A.shape
+        r, n = qweight.shape
+        if r * f != k:
+            raise OracleError("qweight rows must be k / (32 / bits)")
+        if group_size <= 0 or k % group_size or scales.shape != (k // group_size, n) \
+                or qzeros.shape != (k // group_size, n // f):
+            raise OracleError("scales / qzeros shapes do not match k, n, group_size, bits")
+        Cref = np.empty((m, n), np.float64)
+        C16 = np.empty((m, n), np.float16)
+        rc = self.lib.w4a16_oracle_gemm_bits(
+            _ptr(A.view(np.uint16), ctypes.c_uint16), _ptr(qweight, ctypes.c_int32),
+            _ptr(scales.view(np.uint16), ctypes.c_uint16), _ptr(qzeros, ctypes.c_int32),
+            _ptr(Cref, ctypes.c_double), _ptr(C16.view(np.uint16), ctypes.c_uint16),
+            m, n, k, group_size, bits, threads)
+        if rc < 0:
+            raise OracleError(f"w4a16_oracle_gemm_bits rejected its arguments (code {rc})")
+        return Cref, C16
+
+
 _default = None
 
 
@@ -199,6 +277,10 @@ def pack_qzeros(z):
 
 def dequant(qweight, scales, qzeros, group_size):
     return default().dequant(qweight, scales, qzeros, group_size)
+
+
+def gemm_bits(A, qweight, scales, qzeros, group_size, bits, **kw):
+    return default().gemm_bits(A, qweight, scales, qzeros, group_size, bits, **kw)
 
 
 def gemm(A, qweight, scales, qzeros, group_size, **kw):

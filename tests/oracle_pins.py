@@ -299,6 +299,150 @@ def pin_distribution(o):
     assert abs(Cref.mean()) < 0.05 * sigma
 
 
+# --------------------------------------------------------------------------- other field widths
+def np_unpack_rows_bits(words: np.ndarray, bits: int) -> np.ndarray:
+    """numpy restatement for fields along the rows (qweight): bytes first (a little-endian view),
+    then the fields inside each byte by integer division, no shifts by bits * i."""
+    r, n = words.shape
+    by = np.ascontiguousarray(words).view(np.uint8).reshape(r, n, 4).astype(np.int64)
+    per = 8 // bits
+    fields = np.stack([(by // (1 << (bits * t))) % (1 << bits) for t in range(per)], axis=-1)   # [r, n, 4, per]
+    fields = fields.reshape(r, n, 4 * per)
+    return np.ascontiguousarray(fields.transpose(0, 2, 1)).reshape(r * 4 * per, n).astype(np.uint8)
+
+
+def np_unpack_cols_bits(words: np.ndarray, bits: int) -> np.ndarray:
+    """The same for fields along the columns (qzeros)."""
+    g, c = words.shape
+    by = np.ascontiguousarray(words).view(np.uint8).reshape(g, c, 4).astype(np.int64)
+    per = 8 // bits
+    fields = np.stack([(by // (1 << (bits * t))) % (1 << bits) for t in range(per)], axis=-1)
+    return fields.reshape(g, c * 4 * per).astype(np.uint8)
+
+
+def random_case_bits(m, n, k, g, bits, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    f = 32 // bits
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    qw = rng.integers(0, 1 << 32, size=(k // f, n), dtype=np.uint32).view(np.int32)
+    s = rng.uniform(0.001, 0.01, size=(k // g, n)).astype(np.float16)
+    qz = rng.integers(0, 1 << 32, size=(k // g, n // f), dtype=np.uint32).view(np.int32)
+    return A, qw, s, qz
+
+
+def np_dense_weight_bits(qweight, scales, qzeros, group_size, bits) -> np.ndarray:
+    q = np_unpack_rows_bits(qweight, bits).astype(np.int64)
+    z = np.repeat(np_unpack_cols_bits(qzeros, bits).astype(np.int64), group_size, axis=0)
+    s = np.repeat(scales.astype(np.float64), group_size, axis=0)
+    return (q - z) * s
+
+
+def pin_bits_known_words(o):
+    """Hand-written words: bytes for 8 bits, hex digits for 4, binary digits for 2."""
+    w = np.array([[0x04030201, 0x80FF7F00 - (1 << 32), -1, 0]], dtype=np.int64).astype(np.int32)
+    q8 = o.unpack_qweight_bits(w, 8)
+    assert q8[:, 0].tolist() == [1, 2, 3, 4] and q8[:, 1].tolist() == [0, 127, 255, 128]
+    assert q8[:, 2].tolist() == [255] * 4 and q8[:, 3].tolist() == [0] * 4
+    z8 = o.unpack_qzeros_bits(w, 8)
+    assert z8[0].tolist() == [1, 2, 3, 4, 0, 127, 255, 128, 255, 255, 255, 255, 0, 0, 0, 0]
+    w4 = np.array([[0x76543210]], dtype=np.int32)
+    assert o.unpack_qweight_bits(w4, 4)[:, 0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert o.unpack_qzeros_bits(w4, 4)[0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    w2 = np.array([[0b11_10_01_00_00_01_10_11_11_11_00_00_01_01_10_10 - (1 << 32)]], dtype=np.int64).astype(np.int32)
+    expect = [2, 2, 1, 1, 0, 0, 3, 3, 3, 2, 1, 0, 0, 1, 2, 3]          # lowest field first
+    assert o.unpack_qweight_bits(w2, 2)[:, 0].tolist() == expect
+    assert o.unpack_qzeros_bits(w2, 2)[0].tolist() == expect
+
+
+def pin_bits_unpack_library_and_bijection(o):
+    rng = np.random.Generator(np.random.Philox(13))
+    for bits in (2, 4, 8):
+        f = 32 // bits
+        words = rng.integers(0, 1 << 32, size=(6, 40), dtype=np.uint32).view(np.int32)
+        assert (words < 0).any()
+        q = o.unpack_qweight_bits(words, bits)
+        assert q.shape == (6 * f, 40) and int(q.max()) == (1 << bits) - 1
+        assert np.array_equal(q, np_unpack_rows_bits(words, bits))
+        assert np.array_equal(o.pack_qweight_bits(q, bits), words)
+        zw = rng.integers(0, 1 << 32, size=(3, 5), dtype=np.uint32).view(np.int32)
+        z = o.unpack_qzeros_bits(zw, bits)
+        assert z.shape == (3, 5 * f)
+        assert np.array_equal(z, np_unpack_cols_bits(zw, bits))
+        assert np.array_equal(o.pack_qzeros_bits(z, bits), zw)
+        fields = rng.integers(0, 1 << bits, size=(2 * f, 24), dtype=np.uint8)
+        assert np.array_equal(o.unpack_qweight_bits(o.pack_qweight_bits(fields, bits), bits), fields)
+    # 8-bit fields are the bytes of the word
+    words = rng.integers(0, 1 << 32, size=(4, 8), dtype=np.uint32).view(np.int32)
+    by = words.view(np.uint8).reshape(4, 8, 4)
+    assert np.array_equal(o.unpack_qweight_bits(words, 8), by.transpose(0, 2, 1).reshape(16, 8))
+
+
+def pin_bits4_is_the_4bit_path(o):
+    """bits = 4 of the general functions against the 4-bit functions (pinned on their own)."""
+    A, qw, s, qz = random_case(5, 72, 512, 128, seed=17)
+    assert np.array_equal(o.unpack_qweight_bits(qw, 4), o.unpack_qweight(qw))
+    assert np.array_equal(o.unpack_qzeros_bits(qz, 4), o.unpack_qzeros(qz))
+    Cb, Cb16 = o.gemm_bits(A, qw, s, qz, 128, 4)
+    C4, C416 = o.gemm(A, qw, s, qz, 128)
+    assert np.array_equal(Cb.view(np.uint64), C4.view(np.uint64))
+    assert np.array_equal(Cb16.view(np.uint16), C416.view(np.uint16))
+
+
+def pin_bits_matmul_library(o):
+    """numpy float64 matmul over the numpy-unpacked dense weight, classical error bound."""
+    for (m, n, k, g, bits, seed) in ((5, 96, 512, 128, 8, 1), (16, 64, 256, 64, 8, 2), (3, 64, 512, 128, 2, 3),
+                                     (1, 200, 384, 128, 8, 4)):
+        A, qw, s, qz = random_case_bits(m, n, k, g, bits, seed)
+        W = np_dense_weight_bits(qw, s, qz, g, bits)
+        ref = A.astype(np.float64) @ W
+        absdot = np.abs(A.astype(np.float64)) @ np.abs(W)
+        C64, C16 = o.gemm_bits(A, qw, s, qz, g, bits)
+        assert np.all(np.abs(C64 - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+        assert np.array_equal(C16.view(np.uint16), C64.astype(np.float16).view(np.uint16))
+
+
+def pin_bits_tiny_vs_fractions(o):
+    """Exact rationals on a tiny 8-bit case; two groups, so the group index matters."""
+    m, n, k, g, bits = 2, 8, 16, 8, 8
+    A, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=23)
+    q = np_unpack_rows_bits(qw, bits)
+    z = np_unpack_cols_bits(qz, bits)
+    Cref, _ = o.gemm_bits(A, qw, s, qz, g, bits)
+    for i in range(m):
+        for j in range(n):
+            ex = sum(Fraction(float(A[i, kk])) * (int(q[kk, j]) - int(z[kk // g, j])) * Fraction(float(s[kk // g, j]))
+                     for kk in range(k))
+            assert abs(Fraction(float(Cref[i, j])) - ex) <= abs(ex) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+
+
+def pin_bits_closed_forms_and_one_hot(o):
+    m, n, k, g = 3, 64, 256, 128
+    rng = np.random.Generator(np.random.Philox(29))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    s_col = rng.uniform(0.001, 0.01, size=n).astype(np.float16)
+    scales = np.tile(s_col, (k // g, 1))
+    rowsum = A.astype(np.float64).sum(axis=1)
+    for bits, q0, z0 in ((8, 200, 77), (8, 3, 255), (2, 3, 1)):
+        f = 32 // bits
+        rep = sum(1 << (bits * i) for i in range(f))
+        qw = np.full((k // f, n), (q0 * rep) & 0xFFFFFFFF, dtype=np.uint32).view(np.int32)
+        qz = np.full((k // g, n // f), (z0 * rep) & 0xFFFFFFFF, dtype=np.uint32).view(np.int32)
+        Cref, _ = o.gemm_bits(A, qw, scales, qz, g, bits)
+        expect = (q0 - z0) * s_col.astype(np.float64)[None, :] * rowsum[:, None]
+        bound = 1e-12 * np.abs(A.astype(np.float64)).sum(axis=1)[:, None] * 255 * 0.01 + 1e-300
+        assert np.all(np.abs(Cref - expect) <= bound)
+    # one-hot rows pick rows of W exactly (8 bits)
+    _, qw, s, qz = random_case_bits(8, 72, 256, 128, 8, seed=31)
+    W = np_dense_weight_bits(qw, s, qz, 128, 8)
+    rows = [0, 3, 4, 127, 128, 131, 200, 255]
+    A1 = np.zeros((8, 256), np.float16)
+    for i, r in enumerate(rows):
+        A1[i, r] = 1.0
+    Cref, C16 = o.gemm_bits(A1, qw, s, qz, 128, 8)
+    assert np.array_equal(Cref, W[rows, :])
+    assert np.array_equal(C16.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16))
+
+
 ALL_PINS = [
     pin_half_to_float_exhaustive,
     pin_double_to_half_rounding,
@@ -313,4 +457,10 @@ ALL_PINS = [
     pin_linearity_and_permutation,
     pin_splitk_invariance,
     pin_distribution,
+    pin_bits_known_words,
+    pin_bits_unpack_library_and_bijection,
+    pin_bits4_is_the_4bit_path,
+    pin_bits_matmul_library,
+    pin_bits_tiny_vs_fractions,
+    pin_bits_closed_forms_and_one_hot,
 ]

@@ -43,6 +43,21 @@ MUTATIONS = [
      "z[(size_t)gi * n + j] = (uint8_t)((word >> (4 * (7 - j % 8))) & 0xFu);", 0),
     ("pack_qweight_field_order", "word |= (uint32_t)(q[(size_t)(8 * r + i) * n + j] & 0xFu) << (4 * i);",
      "word |= (uint32_t)(q[(size_t)(8 * r + i) * n + j] & 0xFu) << (4 * (7 - i));", 0),
+    ("bits_field_shift_fixed_at_4", "return (int)(((uint32_t)words[word_index] >> (bits * field)) & mask);",
+     "return (int)(((uint32_t)words[word_index] >> (4 * field)) & mask);", 0),
+    ("bits_mask_one_bit_short", "const uint32_t mask = (1u << bits) - 1u;\n    return (int)",
+     "const uint32_t mask = (1u << (bits - 1)) - 1u;\n    return (int)", 0),
+    ("bits_qweight_word_row", "field_of_width(qweight, (size_t)(kk / f) * n + j, kk % f, bits);\n                const int zv",
+     "field_of_width(qweight, (size_t)(kk / 8) * n + j, kk % f, bits);\n                const int zv", 0),
+    ("bits_qzeros_word_column", "const int zv = field_of_width(qzeros, (size_t)gi * (n / f) + j / f, j % f, bits);",
+     "const int zv = field_of_width(qzeros, (size_t)gi * (n / f) + j / f, f - 1 - j % f, bits);", 0),
+    ("bits_zero_point_dropped", "const float wv = (float)(qv - zv) * sv;", "const float wv = (float)(qv) * sv;", 0),
+    ("bits_group_index", "const int gi = kk / group_size;\n                const int qv",
+     "const int gi = 0;\n                const int qv", 0),
+    ("bits_unpack_qzeros_row_stride", "z[(size_t)gi * n + j] = (uint8_t)field_of_width(qzeros, (size_t)gi * (n / f) + j / f, j % f, bits);",
+     "z[(size_t)gi * n + j] = (uint8_t)field_of_width(qzeros, (size_t)gi * (n / 8) + j / f, j % f, bits);", 0),
+    ("bits_pack_field_order", "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * i);",
+     "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * (f - 1 - i));", 0),
     ("dequant_drops_zero_point", "W[(size_t)kk * n + j] = (float)(q - z) * s;", "W[(size_t)kk * n + j] = (float)(q) * s;", 0),
 ]
 
