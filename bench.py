@@ -68,20 +68,20 @@ def log(*a):
 class Workload:
     """Device-resident inputs for one shape, with `sets` distinct weight sets to rotate through."""
 
-    def __init__(self, m, n, k, g, sets, seed=0):
+    def __init__(self, m, n, k, g, sets, seed=0, bits=4):
         import torch
 
         from paper_2402_00025_amd.inputs import algorithmic_bytes, make_inputs, make_weight_sets
 
-        self.m, self.n, self.k, self.g = m, n, k, g
-        self.bytes = algorithmic_bytes(m, n, k, g)
-        x = make_inputs(m, n, k, g, seed=seed)
+        self.m, self.n, self.k, self.g, self.bits = m, n, k, g, bits
+        self.bytes = algorithmic_bytes(m, n, k, g, bits)
+        x = make_inputs(m, n, k, g, seed=seed, bits=bits)
         self.host = x
         self.A = torch.from_numpy(x.A).cuda()
         self.C = torch.zeros((m, n), dtype=torch.float16, device="cuda")
         self.sets = [tuple(torch.from_numpy(t).cuda() for t in (x.qweight, x.scales, x.qzeros))]
         if sets > 1:
-            for (qw, s, qz) in make_weight_sets(sets - 1, n, k, g, seed=seed):
+            for (qw, s, qz) in make_weight_sets(sets - 1, n, k, g, seed=seed, bits=bits):
                 self.sets.append((torch.from_numpy(qw).cuda(), torch.from_numpy(s).cuda(), torch.from_numpy(qz).cuda()))
         torch.cuda.synchronize()
 
@@ -95,7 +95,7 @@ class Workload:
         w.m = m
         w.A = self.A[:m].contiguous()
         w.C = self.C[:m].contiguous()
-        w.bytes = algorithmic_bytes(m, self.n, self.k, self.g)
+        w.bytes = algorithmic_bytes(m, self.n, self.k, self.g, self.bits)
         return w
 
 
@@ -121,6 +121,14 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
                                  ctypes.c_void_p(current_stream().cuda_stream))
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_ex")
+    elif kind in ("splitk8", "dp8"):
+        def call(i):
+            qw, s, qz = ptrs[i % nsets]
+            st = ctypes.c_void_p(current_stream().cuda_stream)
+            rc = (L.w8a16_gemm(A, qw, s, qz, C, m, n, k, g, split_k, st) if kind == "splitk8"
+                  else L.w8a16_gemm_dp(A, qw, s, qz, C, m, n, k, g, st))
+            if rc:
+                raise binding.W4A16Error(rc, "w8a16_gemm")
     elif kind == "streamk":
         def call(i):
             qw, s, qz = ptrs[i % nsets]
@@ -390,6 +398,20 @@ def main():
                 f"{2.0 * mm * 8192 * 8192 / e / 1e12:.0f} TFLOP/s")
         del wb
         extra["row_tiles_nk8192"] = rows
+        # 8-bit fields through the same kernels (twice the weight bytes per call)
+        rows = []
+        for nk in (4096, 8192):
+            wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk))), seed=args.seed, bits=8)
+            for mm in (1, 16):
+                wm = wb.with_m(mm)
+                _, e = time_calls(make_call(wm, "splitk8", split_k=0), 200, 30)
+                _, e_dp = time_calls(make_call(wm, "dp8"), 200, 30)
+                rows.append({"m": mm, "n": nk, "k": nk, "bits": 8, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
+                             "splitk_GBps": wm.bytes / e / 1e9, "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
+                log(f"[bench] 8-bit m={mm:2d} n=k={nk}: splitk {e * 1e6:7.2f} us, dp {e_dp * 1e6:7.2f} us, "
+                    f"{wm.bytes / e / 1e9:.0f} GB/s")
+            del wb
+        extra["eight_bit_fields"] = rows
 
     out = {
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",

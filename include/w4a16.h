@@ -98,6 +98,21 @@ int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, c
                        int m, int n, int k, int group_size, int workgroups, void* stream);
 
 /*
+ * 8-bit fields (Section 2 of the paper remarks that the method carries over to other n-bit
+ * quantisation schemes).  Same operation and rules as w4a16_gemm / w4a16_gemm_dp with four
+ * fields per word:
+ *     qweight  int32  [k / 4, n]         field i (bits 8i..8i+7) of word (r, j) is q[4r + i][j], 0..255
+ *     qzeros   int32  [k / g, n / 4]     field i of word (gi, c) is z[gi][4c + i]
+ * SplitK and data-parallel kernels with 64-column tiles; more than 16 rows run one launch per
+ * 16.  w8a16_algorithmic_bytes: qweight + scales + qzeros + A + C for this layout.
+ */
+int w8a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+               int m, int n, int k, int group_size, int split_k, void* stream);
+int w8a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                  int m, int n, int k, int group_size, void* stream);
+long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size);
+
+/*
  * Same operations with the tuning knobs exposed (0 = library default for each):
  *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
  *              waves divide the workgroup's k range), or 256 (SplitK only, group_size 128 or

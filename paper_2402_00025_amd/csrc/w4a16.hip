@@ -149,7 +149,9 @@ constexpr int kPhaseMaxSplit = 64;          // split_k of the phase protocol: a 
 constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
-template <int V, int IPG, int MODE, int WMAX, int GC>
+// BITS: width of the packed fields, 4 (the paper's) or 8 (Section 2: the method carries over to
+// other n-bit schemes; qweight is then int32 [k / 4, n] and qzeros int32 [k / g, n / 4]).
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -236,13 +238,14 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    const LaneMap lm = make_lane_map<V>(lane, n0, m, n, k);
+    const LaneMap lm = make_lane_map<V, BITS>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)(k / (32 * IPG)) >> p.param_shift;
+    constexpr int kFields = 32 / BITS;  // fields per packed word
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 8) * (uint32_t)n * 4u);
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / kFields) * (uint32_t)n * 4u);
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / 8) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / kFields) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;
@@ -261,8 +264,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
     FlagProbe probe;
     probe.addr = p.flags + origin;
     probe.value = 0;
-    Ring<V, IPG> ring;
-    wave_prime<V, IPG, GC>(ring, tensors, lm, g_begin, g_count, [&]() {
+    Ring<V, IPG, BITS> ring;
+    wave_prime<V, IPG, GC, BITS>(ring, tensors, lm, g_begin, g_count, [&]() {
         if constexpr (MODE == kAtomicPkF16Phase) {
             if (wave == 0) {
                 // wait for the count (the asm makes it a used value here)
@@ -283,7 +286,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             }
         }
     });
-    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC>(ring, tensors, lm, g_begin, g_count, acc, probe);
+    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
 
     if constexpr (MODE == kAtomicPkF16Phase) {
         if (wave == 0 && lane == 0) lds_phase[1] = early;
@@ -530,7 +533,7 @@ struct GemmRest {
     int probe_delay;
 };
 
-template <int V, int IPG, int MODE, int WMAX, int GC>
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
 __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0)))
 gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, _Float16* C,
             int packed, int n, int k, int tiles_rem, const GemmRest rest)
@@ -558,7 +561,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
     p.lds_wave_bytes = rest.lds_wave_bytes;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
-    gemm_body<V, IPG, MODE, WMAX, GC>(p);
+    gemm_body<V, IPG, MODE, WMAX, GC, BITS>(p);
 }
 
 // Streaming SplitK kernel: the four column strips of a workgroup share their activations
@@ -1131,15 +1134,21 @@ static bool phase_split_ok(int split_k)
 // Data-parallel: the only source of workgroups is the column tiling, so tiles shrink (64, 32,
 // 16 columns) until there are about 256 of them, and the waves of a workgroup divide k.
 static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves,
-                     int reduce, Plan* out)
+                     int reduce, Plan* out, int bits = 4)
 {
     // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
-    const long long packed_bytes = (long long)k * n / 2;
+    const long long packed_bytes = (long long)k * n * bits / 8;
+    if (bits == 8) {
+        // 8-bit fields: the per-wave kernel with 64-column tiles only
+        if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
+        tile_cols = 64;
+        if (m > 16) return W4A16_ERR_UNSUPPORTED;
+    }
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
     // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
-    if (!dp && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
+    if (!dp && bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
         // more than 16 rows come here only when the streaming kernel can take them
         const bool asked = tile_cols == kStreamTileCols || m > 16;
         const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
@@ -1272,10 +1281,10 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
     return W4A16_OK;
 }
 
-template <int V, int IPG, int MODE, int WMAX, int GC>
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
 static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_kernel<V, IPG, MODE, WMAX, GC>;
+    auto kern = gemm_kernel<V, IPG, MODE, WMAX, GC, BITS>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -1346,6 +1355,37 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
     case 1: return launch_mode<V, 1>(a, waves, lds_bytes, mode, stream);
     case 2: return launch_mode<V, 2>(a, waves, lds_bytes, mode, stream);
     default: return launch_mode<V, 4>(a, waves, lds_bytes, mode, stream);
+    }
+}
+
+// ---- 8-bit fields: 64-column tiles, at most four waves per workgroup
+template <int IPG, int MODE>
+static int launch8_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
+{
+    if (waves > 4) return W4A16_ERR_UNSUPPORTED;
+    if (a.groups_base >= 2) return launch_bound<4, IPG, MODE, 4, 2, 8>(a, waves, lds_bytes, stream);
+    return launch_bound<4, IPG, MODE, 4, 0, 8>(a, waves, lds_bytes, stream);
+}
+
+template <int IPG>
+static int launch8_mode(const GemmArgs& a, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+{
+    switch (mode) {
+    case kDirect: return launch8_one<IPG, kDirect>(a, waves, lds_bytes, stream);
+    case kAtomicF32: return launch8_one<IPG, kAtomicF32>(a, waves, lds_bytes, stream);
+    case kAtomicPkF16: return launch8_one<IPG, kAtomicPkF16>(a, waves, lds_bytes, stream);
+    case kWorkspace: return launch8_one<IPG, kWorkspace>(a, waves, lds_bytes, stream);
+    case kAtomicFixed: return launch8_one<IPG, kAtomicFixed>(a, waves, lds_bytes, stream);
+    default: return launch8_one<IPG, kAtomicPkF16Phase>(a, waves, lds_bytes, stream);
+    }
+}
+
+static int launch8_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+{
+    switch (ipg) {
+    case 1: return launch8_mode<1>(a, waves, lds_bytes, mode, stream);
+    case 2: return launch8_mode<2>(a, waves, lds_bytes, mode, stream);
+    default: return launch8_mode<4>(a, waves, lds_bytes, mode, stream);
     }
 }
 
@@ -1521,7 +1561,7 @@ static void read_tuning_env()
 
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
                     int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves, int reduce,
-                    bool even_split, void* stream_v)
+                    bool even_split, void* stream_v, int bits = 4)
 {
     if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
     read_tuning_env();
@@ -1529,22 +1569,24 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (rc != W4A16_OK) return rc;
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
+    if ((unsigned long long)k * (unsigned long long)n * (unsigned)bits / 8 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
     // More than 16 rows (beyond the paper's regime): the streaming kernel takes up to 64 rows as
     // row tiles of one launch, so the weights stream once per 64 rows; whatever it does not
     // cover (data-parallel kernel, group sizes below 128, the other tile widths and reductions)
     // runs as one launch per 16 rows.
-    const int rows_per_launch = stream_rows_ok(group_size, dp, tile_cols, waves, reduce) ? 16 * kStreamMaxRowTiles : 16;
+    const int rows_per_launch =
+        bits == 4 && stream_rows_ok(group_size, dp, tile_cols, waves, reduce) ? 16 * kStreamMaxRowTiles : 16;
     if (m > rows_per_launch) {
         for (int r = 0; r < m; r += rows_per_launch) {
             const int mm = m - r < rows_per_launch ? m - r : rows_per_launch;
             rc = run_gemm((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros, (_Float16*)C + (size_t)r * n, mm,
-                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v);
+                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v, bits);
             if (rc != W4A16_OK) return rc;
         }
         return W4A16_OK;
     }
     Plan plan;
-    rc = make_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce, &plan);
+    rc = make_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce, &plan, bits);
     if (rc != W4A16_OK) return rc;
     if (plan.tile_cols == kStreamTileCols) {
         if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
@@ -1614,6 +1656,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
             if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
         }
     }
+    if (bits == 8) return launch8_ipg(a, ipg, plan.waves, lds_bytes, mode, stream);
     switch (V) {
     case 1: return launch_ipg<1>(a, ipg, plan.waves, lds_bytes, mode, stream);
     case 2: return launch_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
@@ -1657,6 +1700,27 @@ int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, c
         if (rc != W4A16_OK) return rc;
     }
     return W4A16_OK;
+}
+
+int w8a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+               int k, int group_size, int split_k, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
+                           W4A16_REDUCE_AUTO, true, stream, 8);
+}
+
+int w8a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+                  int k, int group_size, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
+                           true, stream, 8);
+}
+
+long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size)
+{
+    if (m < 1 || n < 8 || group_size < 8 || k < group_size) return 0;
+    const long long g = k / group_size;
+    return (long long)k * n + g * n * 2 + g * (n / 4) * 4 + (long long)m * k * 2 + (long long)m * n * 2;
 }
 
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,

@@ -88,6 +88,47 @@ __device__ __forceinline__ half8_t unpack_shift(uint32_t word, ZeroConst c, uint
     return __builtin_bit_cast(half8_t, packed);
 }
 
+// 8-bit fields (Section 2 remarks that the method carries over to other n-bit schemes): a word
+// holds four consecutive k of a column, so a lane's B operand is two words.  A byte OR-ed
+// into the mantissa of fp16 1024.0 is 1024 + q exactly (q <= 255 < 2^10); v_perm_b32 builds
+// two such halves per instruction from the word and a register of 0x64 bytes, in the order
+// of k, so the activation operand needs no reordering.
+struct ZeroConst8 {
+    uint32_t lo;  // two copies of fp16 -(1024 + z), z <= 255
+};
+
+__device__ __forceinline__ ZeroConst8 zero_const8(uint32_t z)
+{
+    ZeroConst8 c;
+    c.lo = 0xE400E400u | z | (z << 16);
+    return c;
+}
+
+// 0x64 in every byte, kept in a vector register (see magic_1024x2: one literal per VOP3).
+__device__ __forceinline__ uint32_t magic_64x4()
+{
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, 0x64646464" : "=v"(v));
+    return v;
+}
+
+// Fields 0..3 of w0 and 0..3 of w1 (k = 8 consecutive values) minus the zero point, as fp16.
+__device__ __forceinline__ half8_t unpack_shift8(uint32_t w0, uint32_t w1, ZeroConst8 c, uint32_t magic64)
+{
+    const half2_t clo = __builtin_bit_cast(half2_t, c.lo);
+    const uint32_t t0 = __builtin_amdgcn_perm(magic64, w0, 0x04010400u);  // 1024 + {f0, f1}
+    const uint32_t t1 = __builtin_amdgcn_perm(magic64, w0, 0x04030402u);  // 1024 + {f2, f3}
+    const uint32_t t2 = __builtin_amdgcn_perm(magic64, w1, 0x04010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(magic64, w1, 0x04030402u);
+    const half2_t h0 = __builtin_bit_cast(half2_t, t0) + clo;
+    const half2_t h1 = __builtin_bit_cast(half2_t, t1) + clo;
+    const half2_t h2 = __builtin_bit_cast(half2_t, t2) + clo;
+    const half2_t h3 = __builtin_bit_cast(half2_t, t3) + clo;
+    u32x4_t packed = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                      __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
+    return __builtin_bit_cast(half8_t, packed);
+}
+
 // Eight consecutive activations {a0..a7} (four registers, two per register) reordered to the
 // slot order of unpack_shift: {a0,a4}, {a1,a5}, {a2,a6}, {a3,a7}.
 __device__ __forceinline__ half8_t permute_activations(u32x4_t d)
@@ -173,10 +214,17 @@ __device__ __forceinline__ float scale_of(const ScaleBits<V>& s, int j)
 }
 
 // ------------------------------------------------------------------------------------------
-// One MFMA step (32 consecutive k) of a lane: V weight words and its 8 activations.
-template <int V>
+// One MFMA step (32 consecutive k) of a lane: V weight words (BITS = 4: eight k each) or twice
+// V words (BITS = 8: word rows 2 kg and 2 kg + 1 of the step's eight, four k each) and its 8
+// activations.
+template <int V, int BITS = 4>
 struct StepRegs {
     Words<V> w;
+    u32x4_t a;
+};
+template <int V>
+struct StepRegs<V, 8> {
+    Words<V> w, w1;
     u32x4_t a;
 };
 
@@ -192,7 +240,7 @@ struct ParamRegs {
 // valid columns of the matrix instead, and a lane whose activation row is >= m reads row m-1;
 // in both cases what it computes lands in accumulator entries that are never stored.
 struct LaneMap {
-    uint32_t off_w;   // ((lane / 16) * n + col0) * 4       into qweight
+    uint32_t off_w;   // ((lane / 16) * n + col0) * 4       into qweight (8-bit fields: twice the row)
     uint32_t off_z;   // (col0 / 8) * 4                     into a qzeros row
     uint32_t off_s;   // col0 * 2                           into a scales row
     uint32_t off_a;   // (row * k + 8 * (lane / 16)) * 2    into A, row = min(lane % 16, m - 1)
@@ -207,35 +255,42 @@ struct Tensors {
     int param_shift;
 };
 
-template <int V, int IPG>
-__device__ __forceinline__ void issue_step(StepRegs<V>& r, const LaneMap& lm, const Tensors& t, int gi, int it)
+template <int V, int IPG, int BITS = 4>
+__device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, int gi, int it)
 {
     const uint32_t step = (uint32_t)gi * IPG + it;  // MFMA step index along k: k = 32 * step
     r.a = __builtin_amdgcn_raw_buffer_load_b128(t.A, lm.off_a, step * 64u, 0);
-    r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
+    if constexpr (BITS == 8) {
+        // eight word rows per step
+        r.w.load(t.qweight, lm.off_w, step * 32u * (uint32_t)t.n);
+        r.w1.load(t.qweight, lm.off_w, (step * 32u + 4u) * (uint32_t)t.n);
+    } else {
+        r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
+    }
 }
 
-template <int V>
+template <int V, int BITS = 4>
 __device__ __forceinline__ void issue_params(ParamRegs<V>& r, const LaneMap& lm, const Tensors& t, int gi)
 {
     const uint32_t gp = (uint32_t)gi >> t.param_shift;
-    r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, gp * (uint32_t)(t.n / 8) * 4u, 0);
+    // a qzeros row is n / (fields per word) words
+    r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, gp * (uint32_t)(t.n / (32 / BITS)) * 4u, 0);
     r.s.load(t.scales, lm.off_s, gp * (uint32_t)t.n * 2u);
 }
 
 // Ring of two compute groups: half h holds the IPG steps and the parameters of one group.
-template <int V, int IPG>
+template <int V, int IPG, int BITS = 4>
 struct Ring {
-    StepRegs<V> step[2][IPG];
+    StepRegs<V, BITS> step[2][IPG];
     ParamRegs<V> par[2];
 };
 
-template <int V, int IPG, int H>
-__device__ __forceinline__ void issue_group(Ring<V, IPG>& ring, const LaneMap& lm, const Tensors& t, int gi)
+template <int V, int IPG, int H, int BITS = 4>
+__device__ __forceinline__ void issue_group(Ring<V, IPG, BITS>& ring, const LaneMap& lm, const Tensors& t, int gi)
 {
-    issue_params<V>(ring.par[H], lm, t, gi);
+    issue_params<V, BITS>(ring.par[H], lm, t, gi);
 #pragma unroll
-    for (int it = 0; it < IPG; ++it) issue_step<V, IPG>(ring.step[H][it], lm, t, gi, it);
+    for (int it = 0; it < IPG; ++it) issue_step<V, IPG, BITS>(ring.step[H][it], lm, t, gi, it);
 }
 
 // A word in memory that the last compute group of a wave samples while it still has work to
@@ -250,22 +305,24 @@ struct FlagProbe {
 // set, then acc += scale * tile in fp32.  Each step's registers are refilled with the same
 // step of group `refill` (two groups ahead) as soon as they have been consumed.  With PROBE the
 // flag is sampled once the second step's weights have arrived.
-template <int V, int IPG, int H, bool REFILL, bool PROBE>
-__device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap& lm, const Tensors& t,
+template <int V, int IPG, int H, bool REFILL, bool PROBE, int BITS = 4>
+__device__ __forceinline__ void compute_group(Ring<V, IPG, BITS>& ring, const LaneMap& lm, const Tensors& t,
                                               uint32_t magic, int refill, float4_t (&acc)[V], FlagProbe& probe)
 {
     ZeroConst zc[V];
+    ZeroConst8 zc8[V];
     float sc[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
-        zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
+        if constexpr (BITS == 8) zc8[j] = zero_const8((ring.par[H].zword >> (lm.zshift + 8 * j)) & 0xFFu);
+        else zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
         sc[j] = scale_of<V>(ring.par[H].s, j);
     }
     if constexpr (REFILL) {
         // sched_barrier: keep the instruction scheduler from sinking the refill loads to the
         // end of the loop body (it would serialise load latency and compute)
         __builtin_amdgcn_sched_barrier(0);
-        issue_params<V>(ring.par[H], lm, t, refill);
+        issue_params<V, BITS>(ring.par[H], lm, t, refill);
         __builtin_amdgcn_sched_barrier(0);
     }
     float4_t tile[V];
@@ -273,13 +330,21 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap&
     for (int j = 0; j < V; ++j) tile[j] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int it = 0; it < IPG; ++it) {
-        const half8_t a8 = permute_activations(ring.step[H][it].a);
-        half8_t b8[V];
+        half8_t a8, b8[V];
+        if constexpr (BITS == 8) {
+            // `magic` is the register of 0x64 bytes here; the fields come out in the order of k
+            a8 = __builtin_bit_cast(half8_t, ring.step[H][it].a);
 #pragma unroll
-        for (int j = 0; j < V; ++j) b8[j] = unpack_shift(ring.step[H][it].w.v[j], zc[j], magic);
+            for (int j = 0; j < V; ++j)
+                b8[j] = unpack_shift8(ring.step[H][it].w.v[j], ring.step[H][it].w1.v[j], zc8[j], magic);
+        } else {
+            a8 = permute_activations(ring.step[H][it].a);
+#pragma unroll
+            for (int j = 0; j < V; ++j) b8[j] = unpack_shift(ring.step[H][it].w.v[j], zc[j], magic);
+        }
         if constexpr (REFILL) {
             __builtin_amdgcn_sched_barrier(0);
-            issue_step<V, IPG>(ring.step[H][it], lm, t, refill, it);
+            issue_step<V, IPG, BITS>(ring.step[H][it], lm, t, refill, it);
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (PROBE) {
@@ -303,19 +368,19 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG>& ring, const LaneMap&
 // `primed()` runs once, after the loads have been issued, inside the branch that issued them:
 // a wait it contains then counts exactly the loads of that branch.  GC is what is known about
 // g_count at compile time: 1 = exactly one group, 2 = at least two, 0 = nothing.
-template <int V, int IPG, int GC, class F>
-__device__ __forceinline__ void wave_prime(Ring<V, IPG>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
+template <int V, int IPG, int GC, int BITS = 4, class F>
+__device__ __forceinline__ void wave_prime(Ring<V, IPG, BITS>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
                                            int g_count, F&& primed)
 {
-    issue_group<V, IPG, 0>(ring, lm, t, g_begin);
+    issue_group<V, IPG, 0, BITS>(ring, lm, t, g_begin);
     if constexpr (GC == 1) {
         primed();
     } else if constexpr (GC == 2) {
-        issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+        issue_group<V, IPG, 1, BITS>(ring, lm, t, g_begin + 1);
         primed();
     } else {
         if (g_count > 1) {
-            issue_group<V, IPG, 1>(ring, lm, t, g_begin + 1);
+            issue_group<V, IPG, 1, BITS>(ring, lm, t, g_begin + 1);
             primed();
         } else {
             primed();
@@ -323,43 +388,52 @@ __device__ __forceinline__ void wave_prime(Ring<V, IPG>& ring, const Tensors& t,
     }
 }
 
-template <int V, int IPG, bool PROBE, int GC>
-__device__ __forceinline__ void wave_run(Ring<V, IPG>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
+template <int V, int IPG, bool PROBE, int GC, int BITS = 4>
+__device__ __forceinline__ void wave_run(Ring<V, IPG, BITS>& ring, const Tensors& t, const LaneMap& lm, int g_begin,
                                          int g_count, float4_t (&acc)[V], FlagProbe& probe)
 {
-    const uint32_t magic = magic_1024x2();
+    uint32_t magic;
+    if constexpr (BITS == 8) magic = magic_64x4();
+    else magic = magic_1024x2();
     if constexpr (GC == 1) {
-        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, false, PROBE, BITS>(ring, lm, t, magic, 0, acc, probe);
         return;
     }
     int i = 0;
     for (; i + 3 < g_count; i += 2) {
-        compute_group<V, IPG, 0, true, false>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
-        compute_group<V, IPG, 1, true, false>(ring, lm, t, magic, g_begin + i + 3, acc, probe);
+        compute_group<V, IPG, 0, true, false, BITS>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
+        compute_group<V, IPG, 1, true, false, BITS>(ring, lm, t, magic, g_begin + i + 3, acc, probe);
     }
     const int left = g_count - i;  // 1, 2 or 3 groups; half 0 holds group i, half 1 group i + 1
     if (left == 3) {
-        compute_group<V, IPG, 0, true, false>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
-        compute_group<V, IPG, 1, false, false>(ring, lm, t, magic, 0, acc, probe);
-        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, true, false, BITS>(ring, lm, t, magic, g_begin + i + 2, acc, probe);
+        compute_group<V, IPG, 1, false, false, BITS>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, false, PROBE, BITS>(ring, lm, t, magic, 0, acc, probe);
     } else if (left == 2) {
-        compute_group<V, IPG, 0, false, false>(ring, lm, t, magic, 0, acc, probe);
-        compute_group<V, IPG, 1, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, false, false, BITS>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 1, false, PROBE, BITS>(ring, lm, t, magic, 0, acc, probe);
     } else if (left == 1) {
-        compute_group<V, IPG, 0, false, PROBE>(ring, lm, t, magic, 0, acc, probe);
+        compute_group<V, IPG, 0, false, PROBE, BITS>(ring, lm, t, magic, 0, acc, probe);
     }
 }
 
-template <int V>
+template <int V, int BITS = 4>
 __device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n, int k)
 {
     LaneMap lm;
     const int col0 = n0 + V * (lane & 15);
     const int colc = col0 < n ? col0 : 0;  // an overhanging lane reads the first columns (n >= 8 >= V)
-    lm.off_w = ((uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
-    lm.off_z = (uint32_t)(colc >> 3) * 4u;
+    if constexpr (BITS == 8) {
+        // lane group kg = lane / 16 takes word rows 2 kg and 2 kg + 1 of a step; four columns per zero word
+        lm.off_w = (2u * (uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
+        lm.off_z = (uint32_t)(colc >> 2) * 4u;
+        lm.zshift = 8 * (colc & 3);
+    } else {
+        lm.off_w = ((uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
+        lm.off_z = (uint32_t)(colc >> 3) * 4u;
+        lm.zshift = 4 * (colc & 7);
+    }
     lm.off_s = (uint32_t)colc * 2u;
-    lm.zshift = 4 * (colc & 7);
     const int mrow = lane & 15;
     const int arow = mrow < m ? mrow : m - 1;
     lm.off_a = ((uint32_t)arow * (uint32_t)k + 8u * (uint32_t)(lane >> 4)) * 2u;

@@ -75,34 +75,38 @@ def random_words(rng: np.random.Generator, shape) -> np.ndarray:
     return w.view(np.int32)
 
 
-def make_weights(rng: np.random.Generator, n: int, k: int, group_size: int):
-    """One (qweight, scales, qzeros) set drawn from `rng`, in that order."""
-    qweight = random_words(rng, (k // 8, n))
+def make_weights(rng: np.random.Generator, n: int, k: int, group_size: int, bits: int = 4):
+    """One (qweight, scales, qzeros) set drawn from `rng`, in that order.  `bits` is the field
+    width (32 // bits fields per word): uniform words are uniform independent fields at any width."""
+    fields = 32 // bits
+    qweight = random_words(rng, (k // fields, n))
     scales = rng.uniform(SCALE_LO, SCALE_HI, size=(k // group_size, n)).astype(np.float16)
-    qzeros = random_words(rng, (k // group_size, n // 8))
+    qzeros = random_words(rng, (k // group_size, n // fields))
     return qweight, scales, qzeros
 
 
-def make_inputs(m: int, n: int, k: int, group_size: int = 128, seed: int = 0) -> W4A16Inputs:
-    """The standard workload: A ~ N(0,1) rounded to fp16, 4-bit fields uniform on 0..15,
-    scales ~ U(0.001, 0.01) rounded to fp16.  Draw order: A, qweight, scales, qzeros."""
+def make_inputs(m: int, n: int, k: int, group_size: int = 128, seed: int = 0, bits: int = 4) -> W4A16Inputs:
+    """The standard workload: A ~ N(0,1) rounded to fp16, fields uniform on 0..2^bits - 1 (the
+    paper's are 4-bit), scales ~ U(0.001, 0.01) rounded to fp16.  Draw order: A, qweight,
+    scales, qzeros."""
     check_shape(m, n, k, group_size)
     rng = _rng(seed)
     A = rng.standard_normal(size=(m, k), dtype=np.float32).astype(np.float16)
-    qweight, scales, qzeros = make_weights(rng, n, k, group_size)
+    qweight, scales, qzeros = make_weights(rng, n, k, group_size, bits)
     return W4A16Inputs(A, qweight, scales, qzeros, m, n, k, group_size, seed)
 
 
-def make_weight_sets(count: int, n: int, k: int, group_size: int = 128, seed: int = 0):
+def make_weight_sets(count: int, n: int, k: int, group_size: int = 128, seed: int = 0, bits: int = 4):
     """`count` independent weight sets for the cold-cache timing rotation.
     They come from their own Philox key (seed, 1), so none of them repeats the weights
     that make_inputs draws for the same seed."""
     check_shape(1, n, k, group_size)
     rng = np.random.Generator(np.random.Philox(key=[seed, 1]))
-    return [make_weights(rng, n, k, group_size) for _ in range(count)]
+    return [make_weights(rng, n, k, group_size, bits) for _ in range(count)]
 
 
-def algorithmic_bytes(m: int, n: int, k: int, group_size: int = 128) -> int:
+def algorithmic_bytes(m: int, n: int, k: int, group_size: int = 128, bits: int = 4) -> int:
     """Bytes every call must move at least once: packed weights + scales + zeros + A + C."""
     g = k // group_size
-    return k * n // 2 + g * n * 2 + g * (n // 8) * 4 + m * k * 2 + m * n * 2
+    fields = 32 // bits
+    return (k // fields) * n * 4 + g * n * 2 + g * (n // fields) * 4 + m * k * 2 + m * n * 2

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from gpu_util import DeviceProblem, assert_parity, dev
-from oracle_pins import np_dense_weight, random_case
+from oracle_pins import np_dense_weight, np_dense_weight_bits, random_case, random_case_bits
 from paper_2402_00025_amd import binding as b
 from paper_2402_00025_amd.inputs import make_inputs
 
@@ -539,6 +539,70 @@ def test_streamk_full_size(oracle):
         p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
         b.w4a16_gemm_streamk(*p.args(), 0)
         assert_parity(p.result(), Cref, f"streamk m={m} n={n} k={k}")
+
+
+# ------------------------------------------------------------------ 8-bit fields
+EIGHT_BIT = [
+    # m, n, k, g, split_k
+    (1, 200, 512, 128, 1),
+    (16, 200, 1024, 128, 4),      # two groups per part
+    (16, 328, 1024, 128, 8),      # one group per part, ragged last tile
+    (5, 72, 1408, 128, 0),        # 11 groups, the library's split
+    (16, 264, 2048, 128, 2),      # eight groups per workgroup: steady loop
+    (3, 136, 1024, 256, 2),       # group_size 256
+    (16, 192, 512, 64, 2),        # group_size 64
+    (9, 192, 256, 32, 4),         # group_size 32
+    (4, 64, 4096, 128, 0),        # few rows: fixed-point reduction
+    (40, 264, 1024, 128, 4),      # three launches of 16, 16, 8 rows
+    (16, 8, 256, 128, 2),         # a single 8-column strip
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k", EIGHT_BIT)
+def test_8bit_fields(oracle, m, n, k, g, split_k):
+    A, qw, s, qz = random_case_bits(m, n, k, g, 8, seed=900 + m + n)
+    Cref, _ = oracle.gemm_bits(A, qw, s, qz, g, 8)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w8a16_gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"8-bit splitk m={m} n={n} k={k} g={g} S={split_k} call {call}")
+    p.C.fill_(float("nan"))
+    b.w8a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"8-bit dp m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("split_k", [1, 4])
+def test_8bit_one_hot_rows_bit_exact(split_k):
+    """One non-zero term per row, swept over all k: pins the byte order inside a word, the two
+    word rows of a lane, the zero-point bytes and the scale columns."""
+    m, n, k, g = 16, 200, 1024, 128
+    _, qw, s, qz = random_case_bits(m, n, k, g, 8, seed=53)
+    W = np_dense_weight_bits(qw, s, qz, g, 8)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w8a16_gemm(*p.args(), split_k)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+def test_8bit_full_size(oracle):
+    """The headline shape with 8-bit fields, SplitK (library's split) and data-parallel."""
+    x = make_inputs(16, 4096, 4096, 128, seed=0, bits=8)
+    Cref, _ = oracle.gemm_bits(x.A, x.qweight, x.scales, x.qzeros, 128, 8)
+    p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+    b.w8a16_gemm(*p.args(), 0)
+    assert_parity(p.result(), Cref, "8-bit splitk 4096^2")
+    p.C.fill_(float("nan"))
+    b.w8a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "8-bit dp 4096^2")
 
 
 # ------------------------------------------------------------------ full-size configurations
