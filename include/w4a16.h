@@ -115,7 +115,10 @@ long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size);
 /*
  * Same operations with the tuning knobs exposed (0 = library default for each):
  *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
- *              waves divide the workgroup's k range), or 256 (SplitK only, group_size 128 or
+ *              waves divide the workgroup's k range), 128 (SplitK only, group_size 128 or 256:
+ *              as 64, but every wave multiplies its activations with two adjacent 64-column
+ *              strips; split_k * waves must equal k / 128, waves <= 4, split_k a power of two,
+ *              reduce W4A16_REDUCE_AUTO or W4A16_REDUCE_ATOMIC_PK_F16_PHASE), or 256 (SplitK only, group_size 128 or
  *              256: four waves own a 64-column strip each and share their activations
  *              through LDS; waves = 4 or 8, i.e. one or two such sets dividing the k range;
  *              reduce W4A16_REDUCE_ATOMIC_PK_F16 or W4A16_REDUCE_ATOMIC_PK_F16_PHASE)

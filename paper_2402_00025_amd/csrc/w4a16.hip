@@ -151,11 +151,15 @@ constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers:
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
 // BITS: width of the packed fields, 4 (the paper's) or 8 (Section 2: the method carries over to
 // other n-bit schemes; qweight is then int32 [k / 4, n] and qzeros int32 [k / g, n / 4]).
-template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
+// NS: strips of 16 V columns per wave.  2 (only with GC = 1): the wave multiplies the same
+// activations with the weights of two adjacent strips, which halves the activation traffic per
+// weight byte and the number of waves.
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
+    static_assert(NS == 1 || (NS == 2 && GC == 1 && BITS == 4), "two strips per wave: one compute group per wave");
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    constexpr int BN = 16 * V;
+    constexpr int BN = 16 * V * NS;
     constexpr bool kService = MODE == kAtomicPkF16Service;
 
     const int tid = threadIdx.x;
@@ -175,7 +179,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             const uint32_t origin_s = (uint32_t)n0 / 16u;
             const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2 * NS; ++i) {
                 const int u = lane + kWave * i;
                 const int row = u / (BN / 8), col = n0 + 8 * (u % (BN / 8));
                 const bool inside = slice == 0 && row < m && col < n;
@@ -221,7 +225,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
         const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
         const bool zeroer = slice == 0 && wave == 0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2 * NS; ++i) {
             const int u = lane + kWave * i;
             const int row = u / (BN / 8), col = n0 + 8 * (u % (BN / 8));
             const bool inside = zeroer && row < m && col < n;
@@ -286,7 +290,26 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             }
         }
     });
-    wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
+    // second strip: its parameters and weights are requested behind the first strip's, so they
+    // arrive while the first strip is being computed; the activations are the first strip's
+    Ring<V, IPG, BITS> ring1;
+    float4_t acc1[V];
+    if constexpr (NS == 2) {
+        const LaneMap lm1 = make_lane_map<V, BITS>(lane, n0 + 16 * V, m, n, k);
+        issue_params<V, BITS>(ring1.par[0], lm1, tensors, g_begin);
+#pragma unroll
+        for (int it = 0; it < IPG; ++it)
+            ring1.step[0][it].w.load(tensors.qweight, lm1.off_w, ((uint32_t)g_begin * IPG + it) * 16u * (uint32_t)n);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc1[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+        wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
+#pragma unroll
+        for (int it = 0; it < IPG; ++it) ring1.step[0][it].a = ring.step[0][it].a;
+        FlagProbe none{nullptr, 0};
+        compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, magic_1024x2(), 0, acc1, none);
+    } else {
+        wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
+    }
 
     if constexpr (MODE == kAtomicPkF16Phase) {
         if (wave == 0 && lane == 0) lds_phase[1] = early;
@@ -299,6 +322,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
         const int row = 4 * (lane >> 4) + r;
         if (row < m) {
             float* dst = red + row * BN + V * (lane & 15);
+            if constexpr (NS == 2) {
+                static_assert(NS == 1 || V == 4, "two strips per wave: 128-bit loads");
+                *(float4_t*)(dst + 16 * V) = float4_t{acc1[0][r], acc1[1][r], acc1[2][r], acc1[3][r]};
+            }
             if constexpr (V == 4) {
                 *(float4_t*)dst = float4_t{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
             } else if constexpr (V == 2) {
@@ -533,7 +560,7 @@ struct GemmRest {
     int probe_delay;
 };
 
-template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __global__ void __launch_bounds__(kWave * (WMAX + (MODE == kAtomicPkF16Service ? 1 : 0)))
 gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, _Float16* C,
             int packed, int n, int k, int tiles_rem, const GemmRest rest)
@@ -561,7 +588,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
     p.lds_wave_bytes = rest.lds_wave_bytes;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
-    gemm_body<V, IPG, MODE, WMAX, GC, BITS>(p);
+    gemm_body<V, IPG, MODE, WMAX, GC, BITS, NS>(p);
 }
 
 // Streaming SplitK kernel: the four column strips of a workgroup share their activations
@@ -1145,6 +1172,21 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         tile_cols = 64;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
     }
+    // Two strips per wave (128-column tiles, one compute group per wave, in-kernel zeroing by the
+    // service wavefront): when k is short enough for that (k / 128 = 4 split_k, a power of two),
+    // the rows make the activation traffic matter (m >= 5) and there is a workgroup per compute
+    // unit (measured up to split_k = 8, i.e. k <= 4096, and 25 MB of packed weights).  Measured 1-10 % faster than the single-strip launch and, at k = 4096 and n around
+    // 12000, than the streaming kernel.
+    if (!dp && bits == 4 && tile_cols == 0 && waves == 0 && split_k == 0 && m >= 5 && m <= 16 && group_size >= 128 &&
+        (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
+        phase_split_ok(cgroups / 4) && cgroups / 4 <= 8 && (long long)((n + 127) / 128) * (cgroups / 4) >= 256 &&
+        packed_bytes < (32ll << 20) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
+        out->split_k = cgroups / 4;
+        out->tile_cols = 128;
+        out->waves = 4;
+        out->reduce = W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
+        return W4A16_OK;
+    }
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
     // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
@@ -1191,10 +1233,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < 256) tile_cols /= 2;
         }
     }
-    if (tile_cols != 16 && tile_cols != 32 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
+    // 128 columns: two 64-column strips per wave, one compute group per wave, in-kernel zeroing
+    const bool two_strips = tile_cols == 128;
+    if (two_strips && (dp || bits != 4 || group_size < 128)) return W4A16_ERR_UNSUPPORTED;
+    if (tile_cols != 16 && tile_cols != 32 && tile_cols != 64 && !two_strips) return W4A16_ERR_UNSUPPORTED;
     const int tiles = (n + tile_cols - 1) / tile_cols;
     // 64-column tiles need more than 128 registers per lane, so at most 4 waves per workgroup
-    const int wave_cap = tile_cols == 64 ? 4 : 16;
+    const int wave_cap = tile_cols >= 64 ? 4 : 16;
     if (dp) {
         split_k = 1;
     } else if (split_k == 0) {
@@ -1230,6 +1275,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         reduce = (m <= 4 && split_k <= 64) ? W4A16_REDUCE_ATOMIC_FIXED
                  : phase_split_ok(split_k)  ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE
                                             : W4A16_REDUCE_ATOMIC_PK_F16;
+    }
+    if (two_strips) {
+        if (split_k * waves != cgroups || waves > 4 || split_k < 2) return W4A16_ERR_UNSUPPORTED;
+        if (reduce == W4A16_REDUCE_ATOMIC_FIXED && m <= 4) reduce = W4A16_REDUCE_ATOMIC_PK_F16_PHASE;  // the auto choice
+        if (reduce != W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
     }
     if (reduce < W4A16_REDUCE_ATOMIC_F32 || reduce > W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_ATOMIC_FIXED && split_k > 64) return W4A16_ERR_UNSUPPORTED;
@@ -1281,10 +1331,10 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
     return W4A16_OK;
 }
 
-template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4>
+template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_kernel<V, IPG, MODE, WMAX, GC, BITS>;
+    auto kern = gemm_kernel<V, IPG, MODE, WMAX, GC, BITS, NS>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -1597,8 +1647,8 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     hipStream_t stream = (hipStream_t)stream_v;
     const int ipg = group_size >= 128 ? 4 : group_size / 32;  // MFMA steps (32 k each) per compute group
     const int param_shift = group_size == 256 ? 1 : 0;
-    const int V = plan.tile_cols / 16;
-    if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+    const bool two_strips = plan.tile_cols == 128;
+    const int V = two_strips ? 4 : plan.tile_cols / 16;
     GemmArgs a;
     a.A = (const _Float16*)A;
     a.qweight = (const uint32_t*)qweight;
@@ -1657,6 +1707,11 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         }
     }
     if (bits == 8) return launch8_ipg(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (two_strips) {
+        if (ipg != 4 || mode != kAtomicPkF16Phase || a.groups_base != 1 || a.groups_rem != 0 || plan.waves > 4)
+            return W4A16_ERR_UNSUPPORTED;
+        return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 4, 2>(a, plan.waves, lds_bytes, stream);
+    }
     switch (V) {
     case 1: return launch_ipg<1>(a, ipg, plan.waves, lds_bytes, mode, stream);
     case 2: return launch_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);

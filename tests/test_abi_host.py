@@ -96,7 +96,7 @@ def test_plan_is_consistent():
                 pl = b.w4a16_plan(m, nk, nk, 128, dp=dp)
                 groups = nk // 128
                 assert groups % pl["split_k"] == 0
-                assert pl["tile_cols"] in (16, 32, 64, 256) and 1 <= pl["waves"] <= 16
+                assert pl["tile_cols"] in (16, 32, 64, 128, 256) and 1 <= pl["waves"] <= 16
                 # k parts of a workgroup: all its waves, or (256-column tiles) sets of four
                 kparts = pl["waves"] // 4 if pl["tile_cols"] == 256 else pl["waves"]
                 assert (groups // pl["split_k"]) % kparts == 0

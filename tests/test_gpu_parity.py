@@ -482,6 +482,47 @@ def test_auto_plan_awkward_k(oracle):
         assert_parity(p.result(), Cref, f"dp m={m} n={n}")
 
 
+# ------------------------------------------------------------------ two strips per wave
+TWO_STRIPS = [
+    # m, n, k, g, split_k, waves: 128-column tiles, one compute group per wave (split_k * waves = k / 128)
+    (16, 256, 1024, 128, 2, 4),
+    (16, 200, 1024, 128, 2, 4),     # second tile: one full strip and 8 columns of the other
+    (7, 264, 512, 128, 4, 1),       # third tile has only its first 8 columns
+    (16, 136, 2048, 256, 4, 4),     # group_size 256
+    (3, 72, 1024, 128, 8, 1),       # first strip 64 columns, second 8
+    (16, 1024, 4096, 128, 8, 4),
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k,waves", TWO_STRIPS)
+def test_two_strips_per_wave(oracle, m, n, k, g, split_k, waves):
+    A, qw, s, qz = random_case(m, n, k, g, seed=600 + m + n)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(3):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, 128, waves, 0)
+        assert_parity(p.result(), Cref, f"two strips m={m} n={n} k={k} S={split_k} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+def test_two_strips_one_hot_bit_exact():
+    m, n, k, g = 16, 200, 1024, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=57)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), 2, 128, 4, 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 # ------------------------------------------------------------------ StreamK variant
 STREAMK = [
     # m, n, k, g, workgroups
