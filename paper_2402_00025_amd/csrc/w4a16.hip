@@ -606,7 +606,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
 //                         the steady loop, when a load issued after the count has been consumed,
 //                         samples the flag before the last groups and does not join the last
 //                         barrier, behind which all waves add into C, before it has seen it.
-template <int D, int MODE, bool ODD, int MT>
+template <int D, int MODE, int MT>
 __device__ __forceinline__ void stream_body(const StreamArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -627,7 +627,13 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     // of the workgroup: the host allows a remainder only with one k part per workgroup)
     const int part = slice * p.wk + kpart;
     const int g_begin = part * p.groups_base + (part < p.groups_rem ? part : p.groups_rem);
-    const int G = p.groups_base + (part < p.groups_rem ? 1 : 0);
+    const int G_real = p.groups_base + (part < p.groups_rem ? 1 : 0);
+    // Ring depth 2 walks the groups in pairs.  An odd count is evened out by a phantom group
+    // behind the last one: it is loaded (the next part's data, or zeros behind the end of k) and
+    // multiplied like the others, and its product is dropped (a second drain path for odd
+    // counts made the compiler wait for every load in flight before either drain).
+    const int G = D == 2 ? (G_real + 1) & ~1 : G_real;
+    const float last_keep = G == G_real ? 1.f : 0.f;
     const int n0 = (tile * kStreamStrips + strip) * 64;
 
     const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
@@ -732,7 +738,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     // steady state: D groups are consumed and the next D requested, as long as those exist
     int c = 0;
     for (; c + 2 * D <= G; c += D) {
-        stream_groups<D, 0, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
+        stream_groups<D, 0, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc, 1.f);
         if constexpr (kPhase) {
             if (!published && c >= D) publish();
         }
@@ -743,19 +749,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
             sample = __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // D to 2 D - 1 groups are left.  ODD (D == 2 only): a k part may have an odd count, then
-    // three are left: one beyond the ring, requested on the way.
-    bool three_left = false;
-    if constexpr (ODD) three_left = G - c == 3;
-    if (three_left) {
-        if constexpr (ODD) {
-            stream_group<D, 0, true, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-            stream_group<D, 1, false, true, MT>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
-            stream_group<D, 0, false, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
-        }
-    } else {
-        stream_groups<D, 0, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-    }
+    stream_groups<D, 0, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc, last_keep);
 
     // ---- every wave's tile -> LDS (behind the chunks); after the barrier the k parts are added
     // and the sums leave with consecutive lanes on consecutive column pairs
@@ -840,7 +834,7 @@ struct StreamRest {
     int probe_delay;
 };
 
-template <int D, int MODE, bool ODD, int MT>
+template <int D, int MODE, int MT>
 __global__ void __launch_bounds__(kWave * (MT > 1 ? 4 : 8))
 gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
                    _Float16* C, int packed, int n, int k, int split_rem, const StreamRest rest)
@@ -865,8 +859,7 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.errors = rest.errors;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
-    static_assert(!ODD || D == 2, "odd group counts need no code of their own at ring depth 1");
-    stream_body<D, MODE, ODD, MT>(p);
+    stream_body<D, MODE, MT>(p);
 }
 
 // StreamK decomposition (the paper's Conclusion names it as the successor of SplitK to explore):
@@ -876,8 +869,8 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
 // T = tiles x groups iterations: a run that may end one tile and begin the next.  Every piece
 // of a tile (a "segment") is computed like a k slice of the streaming SplitK kernel and added
 // to C with packed-fp16 atomics (C zeroed by the fill kernel); a segment that is a whole tile
-// is stored.  Segments have any length >= 1, so the drain of the two-group ring handles one,
-// two or three groups left.
+// is stored.  Segments have any length >= 1; an odd one runs a phantom group more, as in
+// stream_body.
 __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_raw, int tile, int g_begin, int G,
                                                 int groups)
 {
@@ -912,8 +905,7 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     sl.ring = lds_raw;
 
     // prologue as in stream_body.  The ring is primed with two groups even when the segment has
-    // one: the second then belongs to the next segment of the tile or lies behind the end of k
-    // (the buffer returns zeros); it is loaded and not used.
+    // one: the second then is the phantom group.
     u32x4_t a_in[D][1];
 #pragma unroll
     for (int h = 0; h < D; ++h)
@@ -933,18 +925,13 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     for (int j = 0; j < 4; ++j) acc[0][j] = float4_t{0.f, 0.f, 0.f, 0.f};
     const uint32_t magic = magic_1024x2();
 
+    // an odd count is evened out by a phantom group whose product is dropped (see stream_body)
+    const int Ge = (G + 1) & ~1;
+    const float last_keep = Ge == G ? 1.f : 0.f;
     int c = 0;
-    for (; c + 2 * D <= G; c += D) stream_groups<D, 0, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-    const int left = G - c;  // 1 (only when G == 1), 2 or 3
-    if (left == 3) {
-        stream_group<D, 0, true, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-        stream_group<D, 1, false, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c + 1, g_begin, acc);
-        stream_group<D, 0, false, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c + 2, g_begin, acc);
-    } else if (left == 2) {
-        stream_groups<D, 0, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-    } else {
-        stream_group<D, 0, false, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc);
-    }
+    for (; c + 2 * D <= Ge; c += D)
+        stream_groups<D, 0, true, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc, 1.f);
+    stream_groups<D, 0, false, 1>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc, last_keep);
 
     // the tile -> LDS; column pairs leave as in stream_body
     float* red_all = (float*)(lds_raw + 2 * kChunkBytes);
@@ -1177,7 +1164,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // the rows make the activation traffic matter (m >= 5) and there is a workgroup per compute
     // unit (measured up to split_k = 8, i.e. k <= 4096, and 25 MB of packed weights).  Measured 1-10 % faster than the single-strip launch and, at k = 4096 and n around
     // 12000, than the streaming kernel.
-    if (!dp && bits == 4 && tile_cols == 0 && waves == 0 && split_k == 0 && m >= 5 && m <= 16 && group_size >= 128 &&
+    if (!dp && bits == 4 && tile_cols == 0 && waves == 0 && split_k == 0 && m >= 2 && m <= 16 && group_size >= 128 &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
         phase_split_ok(cgroups / 4) && cgroups / 4 <= 8 && (long long)((n + 127) / 128) * (cgroups / 4) >= 256 &&
         packed_bytes < (32ll << 20) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
@@ -1198,15 +1185,29 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
                                reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
         int S = split_k;
+        int stream_waves = waves;
         if (S == 0) {
             // about one workgroup per compute unit (160 to 319 of them), at least two groups each
             S = 1;
             while (S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
             if (stiles * S < g_stream_min_blocks && S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2) S *= 2;
+            // Where that count sits badly on 256 compute units (under 200 or over 256), 128-192
+            // workgroups of eight waves do better, if each of their two k parts gets a long run
+            // (eight groups or more): twice the loads in flight per compute unit.
+            if (waves == 0 && m <= 16 && (stiles * S < 200 || stiles * S > 256)) {
+                int S8 = 1;
+                while (stiles * S8 * 2 <= 192) S8 *= 2;
+                if (stiles * S8 >= 128 && cgroups % (2 * S8) == 0 && cgroups / (2 * S8) >= 8) {
+                    S = S8;
+                    stream_waves = 2 * kStreamStrips;
+                }
+            }
         }
-        const bool worth = m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= g_stream_min_blocks && S <= cgroups;
+        const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
+        const bool worth = m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks && S <= cgroups;
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
+            waves = stream_waves;
             if (waves == 0) waves = kStreamStrips;
             if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
             if (m > 16 * kStreamMaxRowTiles || (m > 16 && waves != kStreamStrips)) return W4A16_ERR_UNSUPPORTED;
@@ -1440,10 +1441,10 @@ static int launch8_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, 
 }
 
 // ---- launch of the streaming SplitK kernel
-template <int D, int MODE, bool ODD, int MT>
+template <int D, int MODE, int MT>
 static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_stream_kernel<D, MODE, ODD, MT>;
+    auto kern = gemm_stream_kernel<D, MODE, MT>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -1466,24 +1467,20 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
-template <int D, bool ODD, int MT>
+template <int D, int MT>
 static int launch_stream_mode(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
-    if (mode == kDirect) return launch_stream_one<D, kDirect, ODD, MT>(a, lds_bytes, stream);
-    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, ODD, MT>(a, lds_bytes, stream);
-    return launch_stream_one<D, kAtomicPkF16Phase, ODD, MT>(a, lds_bytes, stream);
+    if (mode == kDirect) return launch_stream_one<D, kDirect, MT>(a, lds_bytes, stream);
+    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, MT>(a, lds_bytes, stream);
+    return launch_stream_one<D, kAtomicPkF16Phase, MT>(a, lds_bytes, stream);
 }
 
 template <int MT>
 static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
     // ring depth: two groups in flight per wave when every k part has at least two
-    if (a.groups_base >= 2 && g_stream_depth >= 2) {
-        if (a.groups_rem == 0 && a.groups_base % 2 == 0)
-            return launch_stream_mode<2, false, MT>(a, lds_bytes, mode, stream);
-        return launch_stream_mode<2, true, MT>(a, lds_bytes, mode, stream);
-    }
-    return launch_stream_mode<1, false, MT>(a, lds_bytes, mode, stream);
+    if (a.groups_base >= 2 && g_stream_depth >= 2) return launch_stream_mode<2, MT>(a, lds_bytes, mode, stream);
+    return launch_stream_mode<1, MT>(a, lds_bytes, mode, stream);
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,

@@ -42,7 +42,8 @@ struct StreamArgs {
     int split_k;
     int wk;               // k parts per workgroup; working waves = 4 * wk (2 only with m <= 16)
     // compute groups (128 consecutive k) per k part: part i = slice * wk + kpart gets groups_base,
-    // the first groups_rem parts one more (groups_rem > 0 only with wk == 1); groups_base >= D
+    // the first groups_rem parts one more (groups_rem > 0 only with wk == 1); groups_base >= D.
+    // At ring depth 2 a part with an odd count runs one phantom group more, whose product is dropped.
     int groups_base;
     int groups_rem;
     int param_shift;      // log2(compute groups per quantisation group)
@@ -101,10 +102,14 @@ struct StreamLane {
 // range.  REFILL: request the weights and the chunk quarters of group cc + D.  NEXT: there is a
 // group cc + 1: publish its chunk quarters, meet the other waves, fetch the next operands.
 // The unpacked weights of a step serve all MT row tiles.
+// `last_keep` says whether the contribution of a wave's last group (the one without NEXT) counts:
+// 1, or 0 when that group is a phantom that only evens out an odd count (its loads read the
+// next part's data or, behind the end of k, zeros; its product is dropped).
 template <int D, int H, bool REFILL, bool NEXT, int MT>
 __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
                                              const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
-                                             uint32_t magic, int cc, int g_begin, float4_t (&acc)[MT][4])
+                                             uint32_t magic, int cc, int g_begin, float4_t (&acc)[MT][4],
+                                             float last_keep)
 {
     ZeroConst zc[4];
     float sc[4];
@@ -148,7 +153,17 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
 #pragma unroll
     for (int rt = 0; rt < MT; ++rt)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[rt][j] += sc[j] * tile[rt][j];
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (NEXT) {
+                acc[rt][j] += sc[j] * tile[rt][j];
+            } else {
+                // a select, not a product with 0: the phantom's operands are someone else's data
+                // and need not be finite
+                const float4_t add = sc[j] * tile[rt][j];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[rt][j][r] += last_keep != 0.f ? add[r] : 0.f;
+            }
+        }
     if constexpr (NEXT) {
         char* buf = sl.ring + ((cc + 1) & 1) * (MT * kChunkBytes);
 #pragma unroll
@@ -165,13 +180,14 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
 template <int D, int H, bool REFILL, int MT>
 __device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
                                               const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
-                                              uint32_t magic, int c0, int g_begin, float4_t (&acc)[MT][4])
+                                              uint32_t magic, int c0, int g_begin, float4_t (&acc)[MT][4],
+                                              float last_keep)
 {
     if constexpr (H < D) {
         // the last group of the wave has no successor
         constexpr bool kNext = REFILL || (H + 1 < D);
-        stream_group<D, H, REFILL, kNext, MT>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc);
-        stream_groups<D, H + 1, REFILL, MT>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc);
+        stream_group<D, H, REFILL, kNext, MT>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc, last_keep);
+        stream_groups<D, H + 1, REFILL, MT>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc, last_keep);
     }
 }
 
