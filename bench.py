@@ -257,6 +257,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
+    ap.add_argument("--shape", default="16,4096,4096",
+                    help="m,n,k of the timed workload (default: the headline workload; another shape runs "
+                         "without the tables, e.g. for a profile of the streaming kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 256 MiB device copies (reference traffic for rocprofv3 counter runs)")
     args = ap.parse_args()
@@ -274,13 +277,15 @@ def main():
         calibrate_copy()
     dev_name = torch.cuda.get_device_name(0)
     g = 128
-    m, n, k = 16, 4096, 4096
+    m, n, k = (int(x) for x in args.shape.split(","))
+    if (m, n, k) != (16, 4096, 4096):
+        args.no_sweep = True   # the tables belong to the headline run
 
     def nsets(n_, k_):
         per = n_ * k_ // 2
         return max(2, -(-ROTATE_BYTES // per))
 
-    log(f"[bench] device {dev_name}; building workload m={m} n=k={n} ({nsets(n, k)} weight sets)")
+    log(f"[bench] device {dev_name}; building workload m={m} n={n} k={k} ({nsets(n, k)} weight sets)")
     w = Workload(m, n, k, g, nsets(n, k), seed=args.seed)
     plan = binding.w4a16_plan(m, n, k, g, split_k=args.split_k)
 
@@ -418,11 +423,11 @@ def main():
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 x int4 -> f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"m={m}, n=k={n}, group_size={g}, split_k={plan['split_k']}, "
-                               f"weights rotated over {len(w.sets)} sets (cold HBM)", "seed": args.seed},
+        "config": {"workload": f"m={m}, n={n}, k={k}, group_size={g}, split_k={plan['split_k']}, "
+                               f"tile_cols={plan['tile_cols']}, weights rotated over {len(w.sets)} sets (cold HBM)", "seed": args.seed},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k),
-                     "kernel": "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
+                     "kernel": "w4a16::gemm_stream_kernel (SplitK)" if plan["tile_cols"] == 256 else "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
         "cpu_baseline": cpu,
         "extra": extra,
     }
