@@ -121,14 +121,17 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
                                  ctypes.c_void_p(current_stream().cuda_stream))
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_ex")
-    elif kind in ("splitk8", "dp8"):
+    elif kind in ("splitk_bits", "dp_bits"):
+        gemm = {2: L.w2a16_gemm, 8: L.w8a16_gemm}[w.bits]
+        gemm_dp = {2: L.w2a16_gemm_dp, 8: L.w8a16_gemm_dp}[w.bits]
+
         def call(i):
             qw, s, qz = ptrs[i % nsets]
             st = ctypes.c_void_p(current_stream().cuda_stream)
-            rc = (L.w8a16_gemm(A, qw, s, qz, C, m, n, k, g, split_k, st) if kind == "splitk8"
-                  else L.w8a16_gemm_dp(A, qw, s, qz, C, m, n, k, g, st))
+            rc = (gemm(A, qw, s, qz, C, m, n, k, g, split_k, st) if kind == "splitk_bits"
+                  else gemm_dp(A, qw, s, qz, C, m, n, k, g, st))
             if rc:
-                raise binding.W4A16Error(rc, "w8a16_gemm")
+                raise binding.W4A16Error(rc, f"w{w.bits}a16_gemm")
     elif kind == "streamk":
         def call(i):
             qw, s, qz = ptrs[i % nsets]
@@ -403,20 +406,21 @@ def main():
                 f"{2.0 * mm * 8192 * 8192 / e / 1e12:.0f} TFLOP/s")
         del wb
         extra["row_tiles_nk8192"] = rows
-        # 8-bit fields through the same kernels (twice the weight bytes per call)
+        # 8-bit and 2-bit fields through the same kernels (twice / half the weight bytes per call)
         rows = []
-        for nk in (4096, 8192):
-            wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk))), seed=args.seed, bits=8)
-            for mm in (1, 16):
-                wm = wb.with_m(mm)
-                _, e = time_calls(make_call(wm, "splitk8", split_k=0), 200, 30)
-                _, e_dp = time_calls(make_call(wm, "dp8"), 200, 30)
-                rows.append({"m": mm, "n": nk, "k": nk, "bits": 8, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
-                             "splitk_GBps": wm.bytes / e / 1e9, "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
-                log(f"[bench] 8-bit m={mm:2d} n=k={nk}: splitk {e * 1e6:7.2f} us, dp {e_dp * 1e6:7.2f} us, "
-                    f"{wm.bytes / e / 1e9:.0f} GB/s")
-            del wb
-        extra["eight_bit_fields"] = rows
+        for bits in (8, 2):
+            for nk in (4096, 8192):
+                wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk * bits // 8))), seed=args.seed, bits=bits)
+                for mm in (1, 16):
+                    wm = wb.with_m(mm)
+                    _, e = time_calls(make_call(wm, "splitk_bits", split_k=0), 200, 30)
+                    _, e_dp = time_calls(make_call(wm, "dp_bits"), 200, 30)
+                    rows.append({"m": mm, "n": nk, "k": nk, "bits": bits, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
+                                 "splitk_GBps": wm.bytes / e / 1e9, "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
+                    log(f"[bench] {bits}-bit m={mm:2d} n=k={nk}: splitk {e * 1e6:7.2f} us, dp {e_dp * 1e6:7.2f} us, "
+                        f"{wm.bytes / e / 1e9:.0f} GB/s")
+                del wb
+        extra["other_field_widths"] = rows
 
     out = {
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",

@@ -113,6 +113,18 @@ int w8a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size);
 
 /*
+ * 2-bit fields, sixteen per word, in the same way:
+ *     qweight  int32  [k / 16, n]        field i (bits 2i, 2i+1) of word (r, j) is q[16r + i][j], 0..3
+ *     qzeros   int32  [k / g, n / 16]    field i of word (gi, c) is z[gi][16c + i]
+ * n must be a multiple of 16 (W4A16_ERR_SHAPE otherwise).
+ */
+int w2a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+               int m, int n, int k, int group_size, int split_k, void* stream);
+int w2a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                  int m, int n, int k, int group_size, void* stream);
+long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size);
+
+/*
  * Same operations with the tuning knobs exposed (0 = library default for each):
  *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
  *              waves divide the workgroup's k range), 128 (SplitK only, group_size 128 or 256:

@@ -149,8 +149,9 @@ constexpr int kPhaseMaxSplit = 64;          // split_k of the phase protocol: a 
 constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
-// BITS: width of the packed fields, 4 (the paper's) or 8 (Section 2: the method carries over to
-// other n-bit schemes; qweight is then int32 [k / 4, n] and qzeros int32 [k / g, n / 4]).
+// BITS: width of the packed fields, 4 (the paper's), 2 or 8 (Section 2: the method carries over
+// to other n-bit schemes; qweight is then int32 [k / f, n] and qzeros int32 [k / g, n / f] with
+// f = 32 / BITS fields per word).
 // NS: strips of 16 V columns per wave.  2 (only with GC = 1): the wave multiplies the same
 // activations with the weights of two adjacent strips, which halves the activation traffic per
 // weight byte and the number of waves.
@@ -158,6 +159,7 @@ template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
     static_assert(NS == 1 || (NS == 2 && GC == 1 && BITS == 4), "two strips per wave: one compute group per wave");
+    static_assert(BITS == 4 || V == 4, "2-bit and 8-bit fields: 64-column tiles");
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V * NS;
     constexpr bool kService = MODE == kAtomicPkF16Service;
@@ -1153,8 +1155,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
     const long long packed_bytes = (long long)k * n * bits / 8;
-    if (bits == 8) {
-        // 8-bit fields: the per-wave kernel with 64-column tiles only
+    if (bits != 4) {
+        // 2-bit and 8-bit fields: the per-wave kernel with 64-column tiles only
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
         tile_cols = 64;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
@@ -1409,34 +1411,35 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
     }
 }
 
-// ---- 8-bit fields: 64-column tiles, at most four waves per workgroup
-template <int IPG, int MODE>
-static int launch8_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
+// ---- 2-bit and 8-bit fields: 64-column tiles, at most four waves per workgroup
+template <int IPG, int MODE, int BITS>
+static int launchn_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
     if (waves > 4) return W4A16_ERR_UNSUPPORTED;
-    if (a.groups_base >= 2) return launch_bound<4, IPG, MODE, 4, 2, 8>(a, waves, lds_bytes, stream);
-    return launch_bound<4, IPG, MODE, 4, 0, 8>(a, waves, lds_bytes, stream);
+    if (a.groups_base >= 2) return launch_bound<4, IPG, MODE, 4, 2, BITS>(a, waves, lds_bytes, stream);
+    return launch_bound<4, IPG, MODE, 4, 0, BITS>(a, waves, lds_bytes, stream);
 }
 
-template <int IPG>
-static int launch8_mode(const GemmArgs& a, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+template <int IPG, int BITS>
+static int launchn_mode(const GemmArgs& a, int waves, size_t lds_bytes, int mode, hipStream_t stream)
 {
     switch (mode) {
-    case kDirect: return launch8_one<IPG, kDirect>(a, waves, lds_bytes, stream);
-    case kAtomicF32: return launch8_one<IPG, kAtomicF32>(a, waves, lds_bytes, stream);
-    case kAtomicPkF16: return launch8_one<IPG, kAtomicPkF16>(a, waves, lds_bytes, stream);
-    case kWorkspace: return launch8_one<IPG, kWorkspace>(a, waves, lds_bytes, stream);
-    case kAtomicFixed: return launch8_one<IPG, kAtomicFixed>(a, waves, lds_bytes, stream);
-    default: return launch8_one<IPG, kAtomicPkF16Phase>(a, waves, lds_bytes, stream);
+    case kDirect: return launchn_one<IPG, kDirect, BITS>(a, waves, lds_bytes, stream);
+    case kAtomicF32: return launchn_one<IPG, kAtomicF32, BITS>(a, waves, lds_bytes, stream);
+    case kAtomicPkF16: return launchn_one<IPG, kAtomicPkF16, BITS>(a, waves, lds_bytes, stream);
+    case kWorkspace: return launchn_one<IPG, kWorkspace, BITS>(a, waves, lds_bytes, stream);
+    case kAtomicFixed: return launchn_one<IPG, kAtomicFixed, BITS>(a, waves, lds_bytes, stream);
+    default: return launchn_one<IPG, kAtomicPkF16Phase, BITS>(a, waves, lds_bytes, stream);
     }
 }
 
-static int launch8_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, int mode, hipStream_t stream)
+template <int BITS>
+static int launchn_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, int mode, hipStream_t stream)
 {
     switch (ipg) {
-    case 1: return launch8_mode<1>(a, waves, lds_bytes, mode, stream);
-    case 2: return launch8_mode<2>(a, waves, lds_bytes, mode, stream);
-    default: return launch8_mode<4>(a, waves, lds_bytes, mode, stream);
+    case 1: return launchn_mode<1, BITS>(a, waves, lds_bytes, mode, stream);
+    case 2: return launchn_mode<2, BITS>(a, waves, lds_bytes, mode, stream);
+    default: return launchn_mode<4, BITS>(a, waves, lds_bytes, mode, stream);
     }
 }
 
@@ -1617,6 +1620,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (!aligned16(A) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
     if ((unsigned long long)k * (unsigned long long)n * (unsigned)bits / 8 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+    if (bits == 2 && (n % 16) != 0) return W4A16_ERR_SHAPE;  // a zero word holds sixteen columns
     // More than 16 rows (beyond the paper's regime): the streaming kernel takes up to 64 rows as
     // row tiles of one launch, so the weights stream once per 64 rows; whatever it does not
     // cover (data-parallel kernel, group sizes below 128, the other tile widths and reductions)
@@ -1703,7 +1707,8 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
             if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
         }
     }
-    if (bits == 8) return launch8_ipg(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (bits == 8) return launchn_ipg<8>(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (bits == 2) return launchn_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
     if (two_strips) {
         if (ipg != 4 || mode != kAtomicPkF16Phase || a.groups_base != 1 || a.groups_rem != 0 || plan.waves > 4)
             return W4A16_ERR_UNSUPPORTED;
@@ -1766,6 +1771,27 @@ int w8a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 {
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
                            true, stream, 8);
+}
+
+int w2a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+               int k, int group_size, int split_k, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
+                           W4A16_REDUCE_AUTO, true, stream, 2);
+}
+
+int w2a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+                  int k, int group_size, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
+                           true, stream, 2);
+}
+
+long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size)
+{
+    if (m < 1 || n < 16 || group_size < 16 || k < group_size) return 0;
+    const long long g = k / group_size;
+    return (long long)k * n / 4 + g * n * 2 + g * (n / 16) * 4 + (long long)m * k * 2 + (long long)m * n * 2;
 }
 
 long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size)

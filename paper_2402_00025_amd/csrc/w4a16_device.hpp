@@ -129,6 +129,47 @@ __device__ __forceinline__ half8_t unpack_shift8(uint32_t w0, uint32_t w1, ZeroC
     return __builtin_bit_cast(half8_t, packed);
 }
 
+// 2-bit fields: a word holds sixteen consecutive k of a column, a lane's B operand is one half
+// of it (`half_shift` = 0 or 16).  With y = h | h << 14 the pairs {f0,f1}, {f2,f3}, {f4,f5} sit
+// at bits (0,16), (4,20), (8,24) of y, inside the mantissa of fp16 1024.0 in both halves, and
+// {f6,f7} at bits (0,16) of y >> 12: a mask-or gives 1024 + q, 1024 + 16 q or 1024 + 256 q, and a
+// packed add or fma (by 1/16 or 1/256) leaves q - z exactly, in the order of k.
+struct ZeroConst2 {
+    uint32_t c0;  // two copies of fp16 -(1024 + z)
+    uint32_t c4;  // two copies of fp16 -(64 + z)
+    uint32_t c8;  // two copies of fp16 -(4 + z)
+};
+
+__device__ __forceinline__ ZeroConst2 zero_const2(uint32_t z)
+{
+    ZeroConst2 c;
+    const uint32_t zz = z | (z << 16);
+    c.c0 = 0xE400E400u | zz;         // ulp 1
+    c.c4 = 0xD400D400u | (zz << 4);  // ulp 1/16
+    c.c8 = 0xC400C400u | (zz << 8);  // ulp 1/256
+    return c;
+}
+
+__device__ __forceinline__ half8_t unpack_shift2(uint32_t word, int half_shift, ZeroConst2 c, uint32_t magic)
+{
+    const half2_t k16 = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const half2_t k256 = {(_Float16)0.00390625f, (_Float16)0.00390625f};
+    const uint32_t h = (word >> half_shift) & 0xFFFFu;
+    const uint32_t y = h | (h << 14);
+    const uint32_t y2 = y >> 12;
+    const uint32_t t0 = (y & 0x00030003u) | magic;   // 1024 + {f0, f1}
+    const uint32_t t1 = (y & 0x00300030u) | magic;   // 1024 + 16 {f2, f3}
+    const uint32_t t2 = (y & 0x03000300u) | magic;   // 1024 + 256 {f4, f5}
+    const uint32_t t3 = (y2 & 0x00030003u) | magic;  // 1024 + {f6, f7}
+    const half2_t h0 = __builtin_bit_cast(half2_t, t0) + __builtin_bit_cast(half2_t, c.c0);
+    const half2_t h1 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t1), k16, __builtin_bit_cast(half2_t, c.c4));
+    const half2_t h2 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t2), k256, __builtin_bit_cast(half2_t, c.c8));
+    const half2_t h3 = __builtin_bit_cast(half2_t, t3) + __builtin_bit_cast(half2_t, c.c0);
+    u32x4_t packed = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                      __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
+    return __builtin_bit_cast(half8_t, packed);
+}
+
 // Eight consecutive activations {a0..a7} (four registers, two per register) reordered to the
 // slot order of unpack_shift: {a0,a4}, {a1,a5}, {a2,a6}, {a3,a7}.
 __device__ __forceinline__ half8_t permute_activations(u32x4_t d)
@@ -245,6 +286,7 @@ struct LaneMap {
     uint32_t off_s;   // col0 * 2                           into a scales row
     uint32_t off_a;   // (row * k + 8 * (lane / 16)) * 2    into A, row = min(lane % 16, m - 1)
     int zshift;       // 4 * (col0 % 8)
+    int half_shift;   // 2-bit fields only: which half of the word the lane's eight k are (0 or 16)
 };
 
 // Scalar view of the problem.  A "compute group" is 32 * IPG consecutive k; a quantisation
@@ -264,6 +306,9 @@ __device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& 
         // eight word rows per step
         r.w.load(t.qweight, lm.off_w, step * 32u * (uint32_t)t.n);
         r.w1.load(t.qweight, lm.off_w, (step * 32u + 4u) * (uint32_t)t.n);
+    } else if constexpr (BITS == 2) {
+        // two word rows per step, each shared by two lane groups
+        r.w.load(t.qweight, lm.off_w, step * 8u * (uint32_t)t.n);
     } else {
         r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
     }
@@ -311,10 +356,12 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG, BITS>& ring, const La
 {
     ZeroConst zc[V];
     ZeroConst8 zc8[V];
+    ZeroConst2 zc2[V];
     float sc[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         if constexpr (BITS == 8) zc8[j] = zero_const8((ring.par[H].zword >> (lm.zshift + 8 * j)) & 0xFFu);
+        else if constexpr (BITS == 2) zc2[j] = zero_const2((ring.par[H].zword >> (lm.zshift + 2 * j)) & 0x3u);
         else zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
         sc[j] = scale_of<V>(ring.par[H].s, j);
     }
@@ -337,6 +384,10 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG, BITS>& ring, const La
 #pragma unroll
             for (int j = 0; j < V; ++j)
                 b8[j] = unpack_shift8(ring.step[H][it].w.v[j], ring.step[H][it].w1.v[j], zc8[j], magic);
+        } else if constexpr (BITS == 2) {
+            a8 = __builtin_bit_cast(half8_t, ring.step[H][it].a);
+#pragma unroll
+            for (int j = 0; j < V; ++j) b8[j] = unpack_shift2(ring.step[H][it].w.v[j], lm.half_shift, zc2[j], magic);
         } else {
             a8 = permute_activations(ring.step[H][it].a);
 #pragma unroll
@@ -421,6 +472,7 @@ template <int V, int BITS = 4>
 __device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n, int k)
 {
     LaneMap lm;
+    lm.half_shift = 0;
     const int col0 = n0 + V * (lane & 15);
     const int colc = col0 < n ? col0 : 0;  // an overhanging lane reads the first columns (n >= 8 >= V)
     if constexpr (BITS == 8) {
@@ -428,6 +480,13 @@ __device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n,
         lm.off_w = (2u * (uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
         lm.off_z = (uint32_t)(colc >> 2) * 4u;
         lm.zshift = 8 * (colc & 3);
+    } else if constexpr (BITS == 2) {
+        // lane groups 0, 1 take the two halves of word row 0 of a step, lane groups 2, 3 of row 1;
+        // sixteen columns per zero word
+        lm.off_w = ((uint32_t)(lane >> 5) * (uint32_t)n + (uint32_t)colc) * 4u;
+        lm.off_z = (uint32_t)(colc >> 4) * 4u;
+        lm.zshift = 2 * (colc & 15);
+        lm.half_shift = 16 * ((lane >> 4) & 1);
     } else {
         lm.off_w = ((uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
         lm.off_z = (uint32_t)(colc >> 3) * 4u;

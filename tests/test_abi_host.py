@@ -15,7 +15,7 @@ HEADER = (ROOT / "include" / "w4a16.h").read_text()
 
 def declared_functions():
     body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
-    return sorted(set(re.findall(r"\b(w[48]a16_[a-z_0-9]+)\s*\(", body)))
+    return sorted(set(re.findall(r"\b(w[248]a16_[a-z_0-9]+)\s*\(", body)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -84,6 +84,8 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w8a16_gemm(p, p, p, p, p, 1, 1020, 1024, 128, 4, None) == b.ERR_SHAPE
     assert L.w8a16_gemm(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
     assert L.w8a16_gemm_dp(p, p, p, p, odd, 1, 1024, 1024, 128, None) == b.ERR_UNSUPPORTED
+    assert L.w2a16_gemm(p, p, p, p, p, 1, 1032, 1024, 128, 4, None) == b.ERR_SHAPE     # n % 16
+    assert L.w2a16_gemm_dp(None, p, p, p, p, 1, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL
@@ -156,6 +158,10 @@ def test_8bit_algorithmic_bytes():
         expect = k * n + (k // 128) * n * 2 + (k // 128) * n + m * k * 2 + m * n * 2
         assert b.w8a16_algorithmic_bytes(m, n, k, 128) == expect
         assert inputs.algorithmic_bytes(m, n, k, 128, bits=8) == expect
+    for (m, n, k) in ((1, 1024, 1024), (16, 4096, 4096)):
+        expect = k * n // 4 + (k // 128) * n * 2 + (k // 128) * (n // 16) * 4 + m * k * 2 + m * n * 2
+        assert b.w2a16_algorithmic_bytes(m, n, k, 128) == expect
+        assert inputs.algorithmic_bytes(m, n, k, 128, bits=2) == expect
     x = inputs.make_inputs(2, 64, 256, 128, seed=5, bits=8)
     assert x.qweight.shape == (64, 64) and x.qzeros.shape == (2, 16) and x.scales.shape == (2, 64)
 

@@ -646,6 +646,57 @@ def test_8bit_full_size(oracle):
     assert_parity(p.result(), Cref, "8-bit dp 4096^2")
 
 
+# ------------------------------------------------------------------ 2-bit fields
+TWO_BIT = [
+    # m, n, k, g, split_k   (n a multiple of 16)
+    (1, 208, 512, 128, 1),
+    (16, 208, 1024, 128, 4),
+    (16, 336, 1024, 128, 8),      # ragged last tile
+    (5, 80, 1408, 128, 0),        # 11 groups, the library's split
+    (16, 272, 2048, 128, 2),
+    (3, 144, 1024, 256, 2),
+    (16, 192, 512, 64, 2),
+    (9, 192, 256, 32, 4),
+    (40, 272, 1024, 128, 4),
+    (16, 16, 256, 128, 2),
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k", TWO_BIT)
+def test_2bit_fields(oracle, m, n, k, g, split_k):
+    A, qw, s, qz = random_case_bits(m, n, k, g, 2, seed=950 + m + n)
+    Cref, _ = oracle.gemm_bits(A, qw, s, qz, g, 2)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w2a16_gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"2-bit splitk m={m} n={n} k={k} g={g} S={split_k} call {call}")
+    p.C.fill_(float("nan"))
+    b.w2a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"2-bit dp m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("split_k", [1, 4])
+def test_2bit_one_hot_rows_bit_exact(split_k):
+    """One non-zero term per row, swept over all k: pins the field order inside a word, the word
+    halves of the lane groups, the zero-point fields and the scale columns."""
+    m, n, k, g = 16, 208, 1024, 128
+    _, qw, s, qz = random_case_bits(m, n, k, g, 2, seed=59)
+    W = np_dense_weight_bits(qw, s, qz, g, 2)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w2a16_gemm(*p.args(), split_k)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
