@@ -697,6 +697,60 @@ def test_2bit_one_hot_rows_bit_exact(split_k):
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
 
 
+# ------------------------------------------------------------------ seeded random shapes
+def _random_shapes(count, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = []
+    for _ in range(count):
+        g = int(rng.choice([32, 64, 128, 128, 128, 256]))
+        groups = int(rng.integers(1, 25))
+        k = g * groups
+        n = 8 * int(rng.integers(1, 90))
+        m = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 11, 15, 16, 17, 31, 33, 64, 70]))
+        out.append((m, n, k, g))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k,g", _random_shapes(48, seed=2024))
+def test_random_shapes_library_plan(oracle, m, n, k, g):
+    """Whatever launch the library picks for a shape (per-wave, two strips, streaming with one
+    or several row tiles, uneven shares), SplitK, data-parallel and StreamK agree with the oracle."""
+    A, qw, s, qz = random_case(m, n, k, g, seed=1000 + m + n + k)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"auto m={m} n={n} k={k} g={g} call {call} plan {b.w4a16_plan(m, n, k, g)}")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"dp m={m} n={n} k={k} g={g}")
+    if g >= 128:
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_streamk(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"streamk m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("m,n,k,split_k,tile_cols,waves", [
+    (16, 8192, 2048, 0, 0, 0),       # two strips per wave by the plan, split_k 4
+    (8, 16400, 1024, 0, 0, 0),       # two strips, split_k 2, ragged last tile
+    (3, 8192, 2048, 0, 0, 0),        # two strips at few rows (in-kernel zeroing instead of fixed-point adds)
+    (16, 5632, 8192, 4, 256, 8),     # eight-wave streaming workgroups, two k parts of eight groups
+    (9, 5632, 16384, 0, 0, 0),       # the plan's own eight-wave choice
+    (16, 2304, 4096, 0, 0, 0),       # under-filled launch
+])
+def test_medium_shapes_plan_variants(oracle, m, n, k, split_k, tile_cols, waves):
+    x = make_inputs(m, n, k, 128, seed=5)
+    Cref, _ = oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, 128)
+    p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, 0)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} call {call} plan {b.w4a16_plan(m, n, k, 128)}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
