@@ -321,6 +321,9 @@ def test_hip_graph_replays(oracle):
         (3, 512, 1024, 4, 64, 2, b.REDUCE_ATOMIC_FIXED),
         (16, 512, 1024, 4, 64, 2, b.REDUCE_ATOMIC_PK_F16),         # fill kernel + atomics
         (16, 512, 1024, 2, 64, 2, b.REDUCE_ATOMIC_F32),
+        (16, 520, 1024, 2, 128, 4, b.REDUCE_ATOMIC_PK_F16_PHASE),  # two strips per wave
+        (40, 520, 2048, 4, 256, 4, b.REDUCE_ATOMIC_PK_F16_PHASE),  # three row tiles, more than 64 KiB of LDS
+        (16, 520, 1408, 4, 256, 4, b.REDUCE_ATOMIC_PK_F16_PHASE),  # uneven shares, phantom group
     ]
     probs = []
     for (m, n, k, S, tc, wv, red) in cases:
