@@ -1161,15 +1161,31 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         tile_cols = 64;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
     }
+    // The rules below come from a sweep of 246 shapes (n 2048..28672, k 1024..14336, m 1, 4, 16)
+    // over every launch shape the kernels offer; the plan lands within 1 % (geometric mean, 9 %
+    // at worst) of the best candidate of each shape.
+    const bool library_choice = !dp && bits == 4 && tile_cols == 0 && waves == 0 && split_k == 0 && m <= 16;
+    const int tiles64 = (n + 63) / 64;
+    // Short k (up to 1024, or up to 2048 when the column tiles alone fill the machine once):
+    // no split at all.  The call is a latency chain of a few microseconds, and zeroing, atomics
+    // and further waves only add to it.
+    if (library_choice && group_size >= 128 && (cgroups <= 8 || (cgroups <= 16 && tiles64 >= 170 && tiles64 <= 256))) {
+        out->split_k = 1;
+        out->tile_cols = 64;
+        out->waves = cgroups < 4 ? cgroups : 4;
+        out->reduce = reduce == W4A16_REDUCE_AUTO ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE : reduce;  // not used: split_k == 1
+        return W4A16_OK;
+    }
     // Two strips per wave (128-column tiles, one compute group per wave, in-kernel zeroing by the
-    // service wavefront): when k is short enough for that (k / 128 = 4 split_k, a power of two),
-    // the rows make the activation traffic matter (m >= 5) and there is a workgroup per compute
-    // unit (measured up to split_k = 8, i.e. k <= 4096, and 25 MB of packed weights).  Measured 1-10 % faster than the single-strip launch and, at k = 4096 and n around
-    // 12000, than the streaming kernel.
-    if (!dp && bits == 4 && tile_cols == 0 && waves == 0 && split_k == 0 && m >= 2 && m <= 16 && group_size >= 128 &&
+    // service wavefront): when k is short enough for that (k / 128 = 4 split_k, split_k a power
+    // of two up to 16, i.e. k <= 8192), there is more than one row, at least 160 workgroups, and
+    // less than 32 MiB of packed weights (28 MiB at split_k = 16).  0-7 % faster than the
+    // single-strip launch with fixed-point adds at m = 2..4, 1-4 % at m = 8..16, and up to 19 %
+    // faster than the streaming kernel on matrices of 16-25 MiB.
+    if (library_choice && m >= 2 && group_size >= 128 &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
-        phase_split_ok(cgroups / 4) && cgroups / 4 <= 8 && (long long)((n + 127) / 128) * (cgroups / 4) >= 256 &&
-        packed_bytes < (32ll << 20) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
+        phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
+        packed_bytes < (cgroups / 4 == 16 ? (28ll << 20) : (32ll << 20)) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
         out->split_k = cgroups / 4;
         out->tile_cols = 128;
         out->waves = 4;
@@ -1206,7 +1222,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             }
         }
         const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
-        const bool worth = m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks && S <= cgroups;
+        // fewer rows (3..7): only on large matrices, and only with a count that sits well
+        const bool few_rows_ok = m >= 3 && packed_bytes >= (48ll << 20) &&
+                                 (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256));
+        const bool worth = S <= cgroups && ((m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
             waves = stream_waves;
@@ -1256,12 +1275,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             // four waves per workgroup and the fewest k slices that give 160 workgroups
             parts = cgroups < 4 ? cgroups : 4;
             while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < g_stream_min_blocks) parts *= 2;
-            // A single row makes the atomic traffic of many slices negligible: where the count
-            // above sits badly on 256 compute units, one group per wave does better.
+            // Few rows make the atomic traffic of many slices small: where the count above sits
+            // badly on 256 compute units, one group per wave does better; and where that is not
+            // to be had and there are more workgroups than fit at once, shorter runs (four groups
+            // or more) even out the load.
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
-            if (m == 1 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
-                (blocks < 200 || blocks > 320))
+            if (m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
+                (blocks < 200 || blocks > 320)) {
                 parts = cgroups;
+            } else if (blocks > 320) {
+                while (parts * 2 <= cgroups && cgroups / (parts * 2) >= 4) parts *= 2;
+            }
         }
         int w = waves != 0 ? waves : parts < 4 ? parts : 4;
         if (w > parts) w = parts;
