@@ -1148,7 +1148,8 @@ static bool phase_split_ok(int split_k)
 // range (their tiles are added in LDS, which keeps the atomic traffic down); the rest of the k
 // parallelism is split_k.
 // Data-parallel: the only source of workgroups is the column tiling, so tiles shrink (64, 32,
-// 16 columns) until there are about 256 of them, and the waves of a workgroup divide k.
+// 16 columns) until there are at least 160 of them, and four or eight waves of a workgroup
+// divide k.
 static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves,
                      int reduce, Plan* out, int bits = 4)
 {
@@ -1251,8 +1252,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     }
     if (tile_cols == 0) {
         tile_cols = 64;
-        if (dp) {
-            while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < 256) tile_cols /= 2;
+        if (dp && bits == 4) {
+            // narrower tiles until there are 160 workgroups (sweeps: 160-256 workgroups beat both
+            // fewer, wider tiles and more than 256 narrow ones)
+            while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < g_stream_min_blocks) tile_cols /= 2;
         }
     }
     // 128 columns: two 64-column strips per wave, one compute group per wave, in-kernel zeroing
@@ -1260,8 +1263,6 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     if (two_strips && (dp || bits != 4 || group_size < 128)) return W4A16_ERR_UNSUPPORTED;
     if (tile_cols != 16 && tile_cols != 32 && tile_cols != 64 && !two_strips) return W4A16_ERR_UNSUPPORTED;
     const int tiles = (n + tile_cols - 1) / tile_cols;
-    // 64-column tiles need more than 128 registers per lane, so at most 4 waves per workgroup
-    const int wave_cap = tile_cols >= 64 ? 4 : 16;
     if (dp) {
         split_k = 1;
     } else if (split_k == 0) {
@@ -1293,7 +1294,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         if (waves == 0) waves = w;
     }
     if (split_k < 1 || split_k > cgroups) return W4A16_ERR_SPLIT;
-    if (waves == 0) waves = largest_wave_split(cgroups, split_k, dp ? wave_cap : 4);
+    // data-parallel, narrow tiles: eight waves divide k for up to four rows, four beyond (sweeps)
+    if (waves == 0) waves = largest_wave_split(cgroups, split_k, dp && tile_cols < 64 && m <= 4 ? 8 : 4);
     if (waves < 1 || waves > 16 || (long long)split_k * waves > cgroups) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_AUTO) {
         // few rows: the arrival-counting fixed-point adds finish in one round trip with no
