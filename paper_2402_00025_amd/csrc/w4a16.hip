@@ -1171,9 +1171,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // no split at all.  The call is a latency chain of a few microseconds, and zeroing, atomics
     // and further waves only add to it.
     if (library_choice && group_size >= 128 && (cgroups <= 8 || (cgroups <= 16 && tiles64 >= 170 && tiles64 <= 256))) {
+        // the launch of the data-parallel kernel: narrower tiles until there are 160 workgroups
+        int tc = 64;
+        while (tc > 16 && (n + tc - 1) / tc < g_stream_min_blocks) tc /= 2;
+        const int wv = tc < 64 && m <= 4 ? 8 : 4;
         out->split_k = 1;
-        out->tile_cols = 64;
-        out->waves = cgroups < 4 ? cgroups : 4;
+        out->tile_cols = tc;
+        out->waves = cgroups < wv ? largest_wave_split(cgroups, 1, wv) : wv;
         out->reduce = reduce == W4A16_REDUCE_AUTO ? W4A16_REDUCE_ATOMIC_PK_F16_PHASE : reduce;  // not used: split_k == 1
         return W4A16_OK;
     }
