@@ -1092,8 +1092,9 @@ constexpr int kMaxDevices = 64;
 // the device.
 constexpr int kSpinLimit = 1 << 17;
 // 64-cycle sleeps before a sample of the tile flag (service wave: before every sample; in-wave
-// protocol: between learning the call count and the early sample).
-static int g_probe_delay = 2;
+// protocol: between learning the call count and the early sample).  Measured flat from 0 to 16
+// with a slight optimum at 8-16 (fewer polls on the way to memory), worse from 32 on.
+static int g_probe_delay = 8;
 // Deepest weight ring (compute groups in flight per wave) the streaming kernel may use: 1 or 2.
 static int g_stream_depth = 2;
 // Persistent workgroups of the StreamK variant when the caller leaves the choice to the library.
