@@ -754,6 +754,30 @@ def test_medium_shapes_plan_variants(oracle, m, n, k, split_k, tile_cols, waves)
     assert b.w4a16_phase_timeouts() == 0
 
 
+# ------------------------------------------------------------------ extremes of the shape range
+@pytest.mark.parametrize("m,n,k,g,split_k", [
+    (4, 66048, 256, 128, 2),      # n beyond the 65536 columns the in-kernel zeroing covers: fill kernel instead
+    (16, 66048, 512, 128, 0),     # the library's own choice there
+    (9, 66048, 2048, 128, 4),     # streaming kernel beyond 65536 columns: fill kernel + atomics
+    (9, 8, 65536, 128, 0),        # one 8-column strip, 512 groups
+    (16, 8, 65536, 128, 64),      # 64 slices of 8 groups
+    (1, 16, 32768, 32, 16),       # group_size 32: 1024 compute groups
+    (64, 72, 16384, 128, 0),      # four row tiles on a narrow matrix
+])
+def test_extreme_shapes(oracle, m, n, k, g, split_k):
+    A, qw, s, qz = random_case(m, n, k, g, seed=1100 + m + n % 97)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, 0, 0, 0)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} g={g} S={split_k} call {call} plan {b.w4a16_plan(min(m, 64), n, k, g, split_k=split_k)}")
+    p.C.fill_(float("nan"))
+    b.w4a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"dp m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _full(oracle, m, nk, seed=0):
     x = make_inputs(m, nk, nk, 128, seed=seed)
