@@ -23,8 +23,8 @@
  * points with group_size 128 or 256 (and, for w4a16_gemm_ex, tile_cols 0 or 256, waves 0 or 4,
  * reduce AUTO, ATOMIC_PK_F16 or ATOMIC_PK_F16_PHASE) take up to 64 rows per launch as row tiles
  * that share one pass over the weights; everything else, the data-parallel kernel included,
- * runs one launch per 16 rows, each streaming the weights again.  n a multiple of 8; g (group_size) one of 32, 64, 128, 256;
- * k a multiple of g; k * n < 2^32.  A split_k requested from w4a16_gemm must cut k into equal
+ * runs one launch per 16 rows, each streaming the weights again.  n a multiple of 8;
+ * g (group_size) one of 32, 64, 128, 256; k a multiple of g; k * n < 2^32.  A split_k requested from w4a16_gemm must cut k into equal
  * shares of whole groups (k / split_k a multiple of g), as Algorithm 1 has it.  The library's own
  * choice (split_k == 0) and w4a16_gemm_ex are not bound by that: they deal out k in compute
  * groups (min(g, 128) consecutive k) to the k parts in order, the first ones getting one group
