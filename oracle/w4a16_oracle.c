@@ -30,7 +30,9 @@
  * Parity status: all functions below are pinned by tests/test_oracle_*.py against closed
  * forms, exact-rational brute force, numpy's float16 and matmul, and pack/unpack bijection;
  * the functions for other field widths (end of the file) by hand-written words, numpy byte
- * views, exact rationals, closed forms, numpy's matmul and, at 4 bits, the 4-bit functions.
+ * views, exact rationals, closed forms, numpy's matmul and, at 4 bits, the 4-bit functions;
+ * the product with a group index per row by the contiguous case, numpy's matmul over a
+ * gathered dense weight, invariance under reordering of the rows, and exact rationals.
  * Unpinned: agreement with the bit layout of the authors' own kernel and with real GPTQ
  * checkpoints (the paper prints neither).
  */
@@ -365,6 +367,53 @@ int w4a16_oracle_gemm_bits(const uint16_t* A, const int32_t* qweight, const uint
                 const float wv = (float)(qv - zv) * sv; /* exact */
                 const float av = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
                 sum += (double)av * (double)wv;
+            }
+            Cref[(size_t)i * n + j] = sum;
+            if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(sum);
+        }
+    }
+    return used;
+}
+
+/* ---------------------------------------------------------------- group index per row
+ *
+ * GPTQ's activation ordering (outside the paper, which has contiguous groups): the group of row
+ * kk is g_idx[kk], any value in [0, groups), instead of kk / g.  4-bit fields as in Section 2:
+ *     W[kk][j] = (q[kk][j] - z[g_idx[kk]][j]) * s[g_idx[kk]][j]
+ * Written on its own; with g_idx[kk] = kk / g it must reproduce w4a16_oracle_gemm.
+ * Returns the OpenMP threads used or a negative number on bad arguments (-6: a g_idx entry
+ * outside [0, groups)). */
+int w4a16_oracle_gemm_gidx(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
+                           const int32_t* qzeros, const int32_t* g_idx, double* Cref, uint16_t* C16,
+                           int m, int n, int k, int groups, int threads)
+{
+    if (!A || !qweight || !scales || !qzeros || !g_idx || !Cref) return -1;
+    if (m < 1 || n < 8 || n % 8 || k < 8 || k % 8 || groups < 1) return -2;
+    for (int kk = 0; kk < k; ++kk)
+        if (g_idx[kk] < 0 || g_idx[kk] >= groups) return -6;
+
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < n; ++j) {
+        for (int i = 0; i < m; ++i) {
+            double sum = 0.0;
+            for (int kk = 0; kk < k; ++kk) {
+                const int row_group = g_idx[kk];
+                const int qf = (int)(((uint32_t)qweight[(size_t)(kk / 8) * n + j] >> (4 * (kk % 8))) & 0xFu);
+                const int zf = (int)(((uint32_t)qzeros[(size_t)row_group * (n / 8) + j / 8] >> (4 * (j % 8))) & 0xFu);
+                const float sf = w4a16_oracle_half_to_float(scales[(size_t)row_group * n + j]);
+                const float wf = (float)(qf - zf) * sf; /* exact */
+                const float af = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
+                sum += (double)af * (double)wf;
             }
             Cref[(size_t)i * n + j] = sum;
             if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(sum);

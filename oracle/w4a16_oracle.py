@@ -70,6 +70,8 @@ class Oracle:
             fn.restype = ctypes.c_int
         lib.w4a16_oracle_gemm_bits.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 6
         lib.w4a16_oracle_gemm_bits.restype = ctypes.c_int
+        lib.w4a16_oracle_gemm_gidx.argtypes = [_u16p, _i32p, _u16p, _i32p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 5
+        lib.w4a16_oracle_gemm_gidx.restype = ctypes.c_int
         self.lib = lib
 
     # ---- fp16 conversions (round to nearest even; the paper does not name a mode)
@@ -229,6 +231,31 @@ class Oracle:
             m, n, k, group_size, bits, threads)
         if rc < 0:
             raise OracleError(f"w4a16_oracle_gemm_bits rejected its arguments (code {rc})")
+        return Cref, C16
+
+
+    # ---- group index per row (GPTQ's activation ordering; outside the paper)
+    def gemm_gidx(self, A, qweight, scales, qzeros, g_idx, threads: int = 0):
+        """Cref (float64 [m, n]) and its fp16 rounding with W[kk] = (q[kk] - z[g_idx[kk]]) * s[g_idx[kk]]."""
+        A = _c(A, np.float16)
+        qweight = _c(qweight, np.int32)
+        scales = _c(scales, np.float16)
+        qzeros = _c(qzeros, np.int32)
+        g_idx = _c(g_idx, np.int32)
+        m, k = A.shape
+        r, n = qweight.shape
+        groups = scales.shape[0]
+        if r * 8 != k or g_idx.shape != (k,) or scales.shape != (groups, n) or qzeros.shape != (groups, n // 8):
+            raise OracleError("shapes do not match")
+        Cref = np.empty((m, n), np.float64)
+        C16 = np.empty((m, n), np.float16)
+        rc = self.lib.w4a16_oracle_gemm_gidx(
+            _ptr(A.view(np.uint16), ctypes.c_uint16), _ptr(qweight, ctypes.c_int32),
+            _ptr(scales.view(np.uint16), ctypes.c_uint16), _ptr(qzeros, ctypes.c_int32),
+            _ptr(g_idx, ctypes.c_int32), _ptr(Cref, ctypes.c_double), _ptr(C16.view(np.uint16), ctypes.c_uint16),
+            m, n, k, groups, threads)
+        if rc < 0:
+            raise OracleError(f"w4a16_oracle_gemm_gidx rejected its arguments (code {rc})")
         return Cref, C16
 
 

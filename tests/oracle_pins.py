@@ -443,6 +443,76 @@ def pin_bits_closed_forms_and_one_hot(o):
     assert np.array_equal(C16.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16))
 
 
+# --------------------------------------------------------------------------- group index per row
+def random_act_order(k, g, seed):
+    """A group map as GPTQ's activation ordering makes it: a random order of the rows, cut into
+    runs of g; row perm[i] belongs to group i // g."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    perm = rng.permutation(k).astype(np.int32)
+    g_idx = np.empty(k, np.int32)
+    g_idx[perm] = np.arange(k, dtype=np.int32) // g
+    return g_idx
+
+
+def pin_gidx_contiguous_is_plain(o):
+    A, qw, s, qz = random_case(5, 72, 512, 128, seed=41)
+    g_idx = (np.arange(512) // 128).astype(np.int32)
+    Cg, Cg16 = o.gemm_gidx(A, qw, s, qz, g_idx)
+    C4, C416 = o.gemm(A, qw, s, qz, 128)
+    assert np.array_equal(Cg.view(np.uint64), C4.view(np.uint64))
+    assert np.array_equal(Cg16.view(np.uint16), C416.view(np.uint16))
+
+
+def pin_gidx_matmul_library(o):
+    """numpy float64 matmul over a dense weight gathered with g_idx by numpy indexing."""
+    for (m, n, k, g, seed) in ((5, 96, 512, 128, 1), (16, 64, 256, 32, 2), (1, 200, 384, 64, 3)):
+        A, qw, s, qz = random_case(m, n, k, g, seed)
+        g_idx = random_act_order(k, g, seed + 100)
+        q = np_unpack_qweight(qw).astype(np.int64)
+        z = np_unpack_qzeros(qz).astype(np.int64)[g_idx]            # [k, n]
+        sc = s.astype(np.float64)[g_idx]
+        W = (q - z) * sc
+        ref = A.astype(np.float64) @ W
+        absdot = np.abs(A.astype(np.float64)) @ np.abs(W)
+        C64, C16 = o.gemm_gidx(A, qw, s, qz, g_idx)
+        assert np.all(np.abs(C64 - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+        assert np.array_equal(C16.view(np.uint16), C64.astype(np.float16).view(np.uint16))
+        # the group map matters: the contiguous one gives another result
+        Cplain, _ = o.gemm(A, qw, s, qz, g)
+        assert np.abs(Cplain - C64).max() > 1e-3 * np.abs(C64).max()
+
+
+def pin_gidx_row_permutation_invariance(o):
+    """Reordering the rows of W, with their group indices, and the columns of A alike leaves every
+    term of every sum unchanged; only the order of an fp64 summation moves."""
+    m, n, k, g = 4, 64, 256, 64
+    A, qw, s, qz = random_case(m, n, k, g, seed=43)
+    g_idx = random_act_order(k, g, seed=44)
+    C0, _ = o.gemm_gidx(A, qw, s, qz, g_idx)
+    P = np.random.Generator(np.random.Philox(45)).permutation(k)
+    qw_p = o.pack_qweight(o.unpack_qweight(qw)[P])
+    Cp, _ = o.gemm_gidx(A[:, P], qw_p, s, qz, g_idx[P])
+    assert np.all(np.abs(Cp - C0) <= 1e-12 * (np.abs(C0) + 1))
+    # sorting the rows by group makes the groups contiguous: the plain product applies
+    order = np.argsort(g_idx, kind="stable")
+    Cs, _ = o.gemm(A[:, order], o.pack_qweight(o.unpack_qweight(qw)[order]), s, qz, g)
+    assert np.all(np.abs(Cs - C0) <= 1e-12 * (np.abs(C0) + 1))
+
+
+def pin_gidx_tiny_vs_fractions(o):
+    m, n, k, g = 2, 8, 16, 8
+    A, qw, s, qz = random_case(m, n, k, g, seed=47)
+    g_idx = np.array([1, 0, 0, 1, 1, 1, 0, 0, 0, 1, 0, 1, 1, 0, 1, 0], np.int32)
+    q = np_unpack_qweight(qw)
+    z = np_unpack_qzeros(qz)
+    Cref, _ = o.gemm_gidx(A, qw, s, qz, g_idx)
+    for i in range(m):
+        for j in range(n):
+            ex = sum(Fraction(float(A[i, kk])) * (int(q[kk, j]) - int(z[g_idx[kk], j])) * Fraction(float(s[g_idx[kk], j]))
+                     for kk in range(k))
+            assert abs(Fraction(float(Cref[i, j])) - ex) <= abs(ex) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+
+
 ALL_PINS = [
     pin_half_to_float_exhaustive,
     pin_double_to_half_rounding,
@@ -463,4 +533,8 @@ ALL_PINS = [
     pin_bits_matmul_library,
     pin_bits_tiny_vs_fractions,
     pin_bits_closed_forms_and_one_hot,
+    pin_gidx_contiguous_is_plain,
+    pin_gidx_matmul_library,
+    pin_gidx_row_permutation_invariance,
+    pin_gidx_tiny_vs_fractions,
 ]

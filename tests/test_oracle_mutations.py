@@ -58,6 +58,11 @@ MUTATIONS = [
      "z[(size_t)gi * n + j] = (uint8_t)field_of_width(qzeros, (size_t)gi * (n / 8) + j / f, j % f, bits);", 0),
     ("bits_pack_field_order", "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * i);",
      "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * (f - 1 - i));", 0),
+    ("gidx_ignored", "const int row_group = g_idx[kk];", "const int row_group = kk / (k / groups);", 0),
+    ("gidx_scale_from_row_position", "const float sf = w4a16_oracle_half_to_float(scales[(size_t)row_group * n + j]);",
+     "const float sf = w4a16_oracle_half_to_float(scales[(size_t)(kk / (k / groups)) * n + j]);", 0),
+    ("gidx_zero_from_row_position", "qzeros[(size_t)row_group * (n / 8) + j / 8]", "qzeros[(size_t)(kk / (k / groups)) * (n / 8) + j / 8]", 0),
+    ("gidx_zero_point_dropped", "const float wf = (float)(qf - zf) * sf;", "const float wf = (float)(qf) * sf;", 0),
     ("dequant_drops_zero_point", "W[(size_t)kk * n + j] = (float)(q - z) * s;", "W[(size_t)kk * n + j] = (float)(q) * s;", 0),
 ]
 
