@@ -61,7 +61,10 @@ extern "C" {
 /* How split-k partial sums reach C (Section 2.1 of the paper discusses the atomic form). */
 #define W4A16_REDUCE_AUTO 0
 #define W4A16_REDUCE_ATOMIC_F32 1   /* fp32 atomic adds into scratch; last block of a tile rounds to fp16 */
-#define W4A16_REDUCE_ATOMIC_PK_F16 2 /* packed-fp16 atomic adds straight into C (C zeroed by a fill kernel) */
+#define W4A16_REDUCE_ATOMIC_PK_F16 2 /* packed-fp16 atomic adds straight into C (C zeroed by a fill kernel); every
+                                       add rounds to fp16, so the error grows like sqrt(split_k) * 2e-4: the
+                                       library's own choice of split_k stays at 32 or below with this flavour and
+                                       the next but one, a requested split_k is taken as given */
 #define W4A16_REDUCE_WORKSPACE 3    /* plain fp32 partial tiles in scratch; last block sums them in fixed order */
 #define W4A16_REDUCE_ATOMIC_FIXED 4 /* 64-bit fixed-point atomic adds that also count arrivals: one round trip,
                                        order-independent (bit-reproducible) sum; split_k <= 64; partial sums
@@ -123,6 +126,28 @@ int w2a16_gemm(const void* A, const void* qweight, const void* scales, const voi
 int w2a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                   int m, int n, int k, int group_size, void* stream);
 long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size);
+
+/*
+ * Activation ordering (GPTQ's act-order; outside the paper, whose groups are contiguous runs of
+ * k): the group of row kk is g_idx[kk] instead of kk / g, W[kk, j] = (q[kk, j] - z[g_idx[kk], j])
+ * * s[g_idx[kk], j], where g_idx (device, int32 [k]) gives every group exactly g rows.
+ *
+ * w4a16_actorder_prepare, once per weight matrix: perm (device, int32 [k]) <- the rows sorted
+ * by group, ascending row order inside a group; qweight_sorted (device, int32 [k / 8, n], not
+ * qweight itself) <- the rows of qweight in that order; *status (device, int32) <- 0, or 1 when
+ * some group does not have exactly g rows (then perm and qweight_sorted are unusable; no access
+ * leaves the buffers whatever g_idx holds).  Asynchronous on `stream` like everything else; it
+ * clears *status with a memset node, so it is not meant to be captured in a HIP graph.
+ *
+ * w4a16_gemm_actorder, per call: A_work (device, fp16 [m, k], 16-byte aligned, caller's scratch,
+ * not A) <- A[:, perm], then the SplitK GEMM of A_work with qweight_sorted, scales and qzeros as
+ * w4a16_gemm does it (same rules for split_k).  The gather is one more small kernel per call.
+ */
+int w4a16_actorder_prepare(const void* qweight, const void* g_idx, void* qweight_sorted, void* perm, void* status,
+                           int n, int k, int group_size, void* stream);
+int w4a16_gemm_actorder(const void* A, const void* qweight_sorted, const void* scales, const void* qzeros,
+                        const void* perm, void* A_work, void* C, int m, int n, int k, int group_size, int split_k,
+                        void* stream);
 
 /*
  * Same operations with the tuning knobs exposed (0 = library default for each):

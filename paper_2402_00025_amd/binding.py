@@ -25,7 +25,7 @@ EXPORTS = (
     "w4a16_check",
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
-    "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes",
+    "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
 )
 
 _lib = None
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
     L.w8a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
     L.w8a16_algorithmic_bytes.argtypes = [ci] * 4
     L.w8a16_algorithmic_bytes.restype = ctypes.c_longlong
+    L.w4a16_actorder_prepare.argtypes = [vp] * 5 + [ci] * 3 + [vp]
+    L.w4a16_gemm_actorder.argtypes = [vp] * 7 + [ci] * 5 + [vp]
     L.w2a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w2a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
     L.w2a16_algorithmic_bytes.argtypes = [ci] * 4
@@ -155,6 +157,17 @@ def w2a16_gemm_dp(A, qweight, scales, qzeros, C, m, n, k, group_size, stream=Non
 
 def w2a16_algorithmic_bytes(m, n, k, group_size) -> int:
     return int(lib().w2a16_algorithmic_bytes(m, n, k, group_size))
+
+
+def w4a16_actorder_prepare(qweight, g_idx, qweight_sorted, perm, status, n, k, group_size, stream=None) -> None:
+    _check(lib().w4a16_actorder_prepare(_p(qweight), _p(g_idx), _p(qweight_sorted), _p(perm), _p(status), n, k,
+                                        group_size, _stream(stream)), "w4a16_actorder_prepare")
+
+
+def w4a16_gemm_actorder(A, qweight_sorted, scales, qzeros, perm, A_work, C, m, n, k, group_size, split_k=0,
+                        stream=None) -> None:
+    _check(lib().w4a16_gemm_actorder(_p(A), _p(qweight_sorted), _p(scales), _p(qzeros), _p(perm), _p(A_work), _p(C),
+                                     m, n, k, group_size, split_k, _stream(stream)), "w4a16_gemm_actorder")
 
 
 def w4a16_gemm_streamk(A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups=0, stream=None) -> None:

@@ -50,14 +50,17 @@ enum : int {
 };
 
 // kAtomicFixed: one 64-bit integer atomic add per output element and workgroup.
-//   bits 56..63  arrivals so far (split_k <= 64)
-//   bits  0..55  sum of (partial * 2^33 + 2^50): fixed point, biased so it never goes negative
+//   bits 57..63  arrivals so far (split_k <= 64)
+//   bits  0..56  sum of (partial * 2^33 + 2^50): fixed point, biased so it never goes negative;
+//                every term is below 2^51 (|partial| is clamped below 2^17), so 64 of them stay
+//                below 2^57 and never reach the arrival count
 // The add returns the previous word, so the workgroup that sees split_k - 1 earlier arrivals
 // holds the complete sum (previous + its own) and finishes the element: one memory round trip,
 // no separate ticket, and a sum that does not depend on arrival order (integer addition).
 constexpr int kFixedFracBits = 33;
 constexpr uint64_t kFixedBias = 1ull << 50;
-constexpr uint64_t kFixedArrival = 1ull << 56;
+constexpr int kFixedArrivalShift = 57;
+constexpr uint64_t kFixedArrival = 1ull << kFixedArrivalShift;
 constexpr uint64_t kFixedSumMask = kFixedArrival - 1;
 constexpr float kFixedClamp = 131071.0f;  // |partial| < 2^17 keeps partial * 2^33 inside the bias
 
@@ -78,7 +81,7 @@ __device__ __forceinline__ float fixed_total(uint64_t word, int split_k)
 // with the total in *total and resets the word to zero for the next call.
 __device__ __forceinline__ bool fixed_finish(uint64_t* word, uint64_t old, uint64_t mine, int split_k, float* total)
 {
-    if ((int)(old >> 56) != split_k - 1) return false;
+    if ((int)(old >> kFixedArrivalShift) != split_k - 1) return false;
     *total = fixed_total(old + mine, split_k);
     __hip_atomic_store(word, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return true;
@@ -1018,6 +1021,76 @@ __global__ void fill_zero_kernel(uint32_t* p, size_t words)
     if (i < words) p[i] = 0u;
 }
 
+// ---- activation ordering (GPTQ's act-order; outside the paper, whose groups are contiguous) ----
+// The group of row kk is g_idx[kk].  Such a map comes from quantising the rows in some order and
+// cutting that order into runs of g, so sorting the rows by group (stably) makes the groups
+// contiguous again: with perm = the sorted order, C = sum_i A[:, perm[i]] W[perm[i], :], which is
+// the plain product of the gathered activations with the reordered weight rows.  The weights are
+// static, so they are reordered once (prepare); a call gathers the activations (m x k fp16, one
+// small kernel) and runs the ordinary GEMM.
+
+// perm[b * g + i] = the i-th row (in ascending row order) whose group is b.  One workgroup per
+// group walks all rows 256 at a time; a group that does not have exactly g rows sets *status.
+__global__ void __launch_bounds__(256)
+actorder_perm_kernel(const int32_t* __restrict__ g_idx, int32_t* __restrict__ perm, int32_t* status, int k, int g)
+{
+    __shared__ int wave_total[4];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int count = 0;  // rows of this group found so far (uniform)
+    for (int base = 0; base < k; base += 256) {
+        const int r = base + tid;
+        const bool mine = r < k && g_idx[r] == b;
+        const unsigned long long ballot = __ballot(mine);
+        const int rank = __popcll(ballot & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_total[wave] = __popcll(ballot);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) before += wave_total[w];
+            total += wave_total[w];
+        }
+        const int pos = count + before + rank;
+        if (mine && pos < g) perm[(size_t)b * g + pos] = r;
+        count += total;
+        __syncthreads();
+    }
+    if (tid == 0 && count != g) atomicOr(status, 1);
+}
+
+// Row i of the reordered matrix is row perm[i] of the given one: every output word gathers its
+// eight 4-bit fields.  Entries of perm outside [0, k) (only possible when *status was set) are
+// clamped, so the kernel stays inside its buffers whatever g_idx held.
+__global__ void actorder_repack_kernel(const uint32_t* __restrict__ qweight, const int32_t* __restrict__ perm,
+                                       uint32_t* __restrict__ out, int n, int k)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t words = (size_t)(k / 8) * n;
+    if (idx >= words) return;
+    const int R = (int)(idx / n), j = (int)(idx % n);
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int src = perm[8 * R + i];
+        src = src < 0 ? 0 : (src >= k ? k - 1 : src);
+        word |= field(qweight[(size_t)(src >> 3) * n + j], src & 7) << (4 * i);
+    }
+    out[idx] = word;
+}
+
+// A_work[i][t] = A[i][perm[t]].
+__global__ void actorder_gather_kernel(const _Float16* __restrict__ A, const int32_t* __restrict__ perm,
+                                       _Float16* __restrict__ A_work, int m, int k)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)m * k) return;
+    const int i = (int)(idx / k), t = (int)(idx % k);
+    int src = perm[t];
+    src = src < 0 ? 0 : (src >= k ? k - 1 : src);
+    A_work[idx] = A[(size_t)i * k + src];
+}
+
 // ---- test probes: the same unpack_shift / zero_const / field routines as the GEMM ----------
 // q_u8[kk][j] and z_u8[gi][j]; one thread per packed word.
 __global__ void unpack_kernel(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* q_u8, uint8_t* z_u8,
@@ -1212,9 +1285,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         int stream_waves = waves;
         if (S == 0) {
             // about one workgroup per compute unit (160 to 319 of them), at least two groups each
+            // (at most 32 slices: the packed-fp16 adds round once per slice)
             S = 1;
-            while (S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
-            if (stiles * S < g_stream_min_blocks && S * 2 <= kPhaseMaxSplit && cgroups / (S * 2) >= 2) S *= 2;
+            while (S * 2 <= 32 && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
+            if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2) S *= 2;
             // Where that count sits badly on 256 compute units (under 200 or over 256), 128-192
             // workgroups of eight waves do better, if each of their two k parts gets a long run
             // (eight groups or more): twice the loads in flight per compute unit.
@@ -1296,6 +1370,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         int w = waves != 0 ? waves : parts < 4 ? parts : 4;
         if (w > parts) w = parts;
         split_k = parts / w;
+        // The library's own choice stays where the reduction is accurate: every packed-fp16 add
+        // rounds, so the error grows like sqrt(split_k) * 2e-4 (1.1e-3 at 32, against the
+        // tolerance of 2e-3); the fixed-point adds used for up to four rows take 64 slices.
+        const int split_cap = m <= 4 ? 64 : 32;
+        if (split_k > split_cap) split_k = split_cap;
         if (waves == 0) waves = w;
     }
     if (split_k < 1 || split_k > cgroups) return W4A16_ERR_SPLIT;
@@ -1830,6 +1909,40 @@ long long w8a16_algorithmic_bytes(int m, int n, int k, int group_size)
     if (m < 1 || n < 8 || group_size < 8 || k < group_size) return 0;
     const long long g = k / group_size;
     return (long long)k * n + g * n * 2 + g * (n / 4) * 4 + (long long)m * k * 2 + (long long)m * n * 2;
+}
+
+int w4a16_actorder_prepare(const void* qweight, const void* g_idx, void* qweight_sorted, void* perm, void* status,
+                           int n, int k, int group_size, void* stream)
+{
+    if (!qweight || !g_idx || !qweight_sorted || !perm || !status) return W4A16_ERR_NULL;
+    int rc = w4a16::check_args(1, n, k, group_size, 1);
+    if (rc != W4A16_OK) return rc;
+    if (qweight == qweight_sorted) return W4A16_ERR_UNSUPPORTED;  // not in place
+    hipStream_t st = (hipStream_t)stream;
+    if (!w4a16::W4A16_HIP(hipMemsetAsync(status, 0, sizeof(int32_t), st))) return W4A16_ERR_HIP;
+    hipLaunchKernelGGL(w4a16::actorder_perm_kernel, dim3((unsigned)(k / group_size)), dim3(256), 0, st,
+                       (const int32_t*)g_idx, (int32_t*)perm, (int32_t*)status, k, group_size);
+    if (!w4a16::W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    const size_t words = (size_t)(k / 8) * n;
+    hipLaunchKernelGGL(w4a16::actorder_repack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                       (const uint32_t*)qweight, (const int32_t*)perm, (uint32_t*)qweight_sorted, n, k);
+    return w4a16::W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
+}
+
+int w4a16_gemm_actorder(const void* A, const void* qweight_sorted, const void* scales, const void* qzeros,
+                        const void* perm, void* A_work, void* C, int m, int n, int k, int group_size, int split_k,
+                        void* stream)
+{
+    if (!A || !qweight_sorted || !scales || !qzeros || !perm || !A_work || !C) return W4A16_ERR_NULL;
+    int rc = w4a16::check_args(m, n, k, group_size, split_k);
+    if (rc != W4A16_OK) return rc;
+    if (!w4a16::aligned16(A_work) || A_work == A) return W4A16_ERR_UNSUPPORTED;
+    const size_t elems = (size_t)m * k;
+    hipLaunchKernelGGL(w4a16::actorder_gather_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (const _Float16*)A, (const int32_t*)perm, (_Float16*)A_work, m, k);
+    if (!w4a16::W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    return w4a16::run_gemm(A_work, qweight_sorted, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
+                           W4A16_REDUCE_AUTO, true, stream);
 }
 
 int w4a16_gemm_ex(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,

@@ -86,6 +86,13 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w8a16_gemm_dp(p, p, p, p, odd, 1, 1024, 1024, 128, None) == b.ERR_UNSUPPORTED
     assert L.w2a16_gemm(p, p, p, p, p, 1, 1032, 1024, 128, 4, None) == b.ERR_SHAPE     # n % 16
     assert L.w2a16_gemm_dp(None, p, p, p, p, 1, 1024, 1024, 128, None) == b.ERR_NULL
+    q = ctypes.c_void_p(8192)
+    assert L.w4a16_actorder_prepare(p, p, q, p, None, 1024, 1024, 128, None) == b.ERR_NULL
+    assert L.w4a16_actorder_prepare(p, p, q, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
+    assert L.w4a16_actorder_prepare(p, p, p, p, p, 1024, 1024, 128, None) == b.ERR_UNSUPPORTED   # in place
+    assert L.w4a16_gemm_actorder(p, p, p, p, p, None, p, 1, 1024, 1024, 128, 0, None) == b.ERR_NULL
+    assert L.w4a16_gemm_actorder(p, p, p, p, p, q, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
+    assert L.w4a16_gemm_actorder(p, p, p, p, p, p, p, 1, 1024, 1024, 128, 0, None) == b.ERR_UNSUPPORTED  # A_work is A
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from gpu_util import DeviceProblem, assert_parity, dev
-from oracle_pins import np_dense_weight, np_dense_weight_bits, random_case, random_case_bits
+from oracle_pins import np_dense_weight, np_dense_weight_bits, random_act_order, random_case, random_case_bits
 from paper_2402_00025_amd import binding as b
 from paper_2402_00025_amd.inputs import make_inputs
 
@@ -754,13 +754,34 @@ def test_medium_shapes_plan_variants(oracle, m, n, k, split_k, tile_cols, waves)
     assert b.w4a16_phase_timeouts() == 0
 
 
+def test_phase_protocol_64_slices_one_hot_bit_exact():
+    """The in-kernel zeroing with its largest split (64 slices): one non-zero term per row, so
+    the 63 other packed-fp16 adds of every element are exact zeros and the result is exact."""
+    m, n, k, g = 16, 72, 8192, 128
+    _, qw, s, qz = random_case(m, n, k, g, seed=61)
+    W = np_dense_weight(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, 16 * m):
+        rows = [(base + 131 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w4a16_gemm_ex(*p.args(), 64, 64, 1, b.REDUCE_ATOMIC_PK_F16_PHASE)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ extremes of the shape range
 @pytest.mark.parametrize("m,n,k,g,split_k", [
     (4, 66048, 256, 128, 2),      # n beyond the 65536 columns the in-kernel zeroing covers: fill kernel instead
     (16, 66048, 512, 128, 0),     # the library's own choice there
     (9, 66048, 2048, 128, 4),     # streaming kernel beyond 65536 columns: fill kernel + atomics
     (9, 8, 65536, 128, 0),        # one 8-column strip, 512 groups
-    (16, 8, 65536, 128, 64),      # 64 slices of 8 groups
+    (4, 8, 65536, 128, 64),       # 64 slices of 8 groups, fixed-point adds
+    (16, 8, 65536, 128, 32),      # 32 slices with packed-fp16 adds (more would leave too little of the tolerance)
     (1, 16, 32768, 32, 16),       # group_size 32: 1024 compute groups
     (64, 72, 16384, 128, 0),      # four row tiles on a narrow matrix
 ])
@@ -776,6 +797,58 @@ def test_extreme_shapes(oracle, m, n, k, g, split_k):
     b.w4a16_gemm_dp(*p.args())
     assert_parity(p.result(), Cref, f"dp m={m} n={n} k={k} g={g}")
     assert b.w4a16_phase_timeouts() == 0
+
+
+# ------------------------------------------------------------------ activation ordering (group index per row)
+@pytest.mark.parametrize("m,n,k,g,split_k", [
+    (1, 200, 512, 128, 0),
+    (16, 264, 1024, 128, 4),
+    (7, 136, 1408, 128, 0),       # 11 groups
+    (16, 192, 512, 32, 2),
+    (9, 72, 1024, 256, 2),
+    (40, 264, 1024, 128, 0),      # more than 16 rows
+    (16, 4096, 4096, 128, 0),     # the headline shape
+])
+def test_activation_ordering(oracle, m, n, k, g, split_k):
+    import torch
+    A, qw, s, qz = random_case(m, n, k, g, seed=1200 + m + n % 89)
+    g_idx = random_act_order(k, g, seed=1300 + k)
+    Cref, _ = oracle.gemm_gidx(A, qw, s, qz, g_idx)
+    p = DeviceProblem(A, qw, s, qz, g)
+    d_gidx = dev(g_idx)
+    qw_sorted = torch.empty_like(p.qweight)
+    perm = torch.full((k,), -1, dtype=torch.int32, device="cuda")
+    status = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    A_work = torch.empty_like(p.A)
+    b.w4a16_actorder_prepare(p.qweight, d_gidx, qw_sorted, perm, status, n, k, g)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    order = np.argsort(g_idx, kind="stable")
+    assert np.array_equal(perm.cpu().numpy(), order)
+    assert np.array_equal(oracle.unpack_qweight(qw_sorted.cpu().numpy()), oracle.unpack_qweight(qw)[order])
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_actorder(p.A, qw_sorted, p.scales, p.qzeros, perm, A_work, p.C, m, n, k, g, split_k)
+        assert_parity(p.result(), Cref, f"act-order m={m} n={n} k={k} g={g} S={split_k} call {call}")
+    # the plain product of the same buffers is something else: the group map matters
+    if k // g > 1:
+        b.w4a16_gemm(*p.args(), 0)
+        assert np.abs(p.result().astype(np.float64) - Cref).max() > 1e-2 * np.abs(Cref).max()
+
+
+def test_activation_ordering_rejects_bad_group_map():
+    import torch
+    n, k, g = 64, 512, 128
+    _, qw, s, qz = random_case(1, n, k, g, seed=5)
+    for bad in (np.zeros(k, np.int32),                                  # every row in group 0
+                np.concatenate([np.arange(k - 1) // g, [99]]).astype(np.int32),   # an index outside the groups
+                np.full(k, -5, np.int32)):
+        qws = torch.empty((k // 8, n), dtype=torch.int32, device="cuda")
+        perm = torch.full((k,), 1 << 30, dtype=torch.int32, device="cuda")   # garbage the kernel must not follow
+        status = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        b.w4a16_actorder_prepare(dev(qw), dev(bad), qws, perm, status, n, k, g)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 1
 
 
 # ------------------------------------------------------------------ full-size configurations
