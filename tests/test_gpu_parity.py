@@ -774,6 +774,28 @@ def test_phase_protocol_64_slices_one_hot_bit_exact():
     assert b.w4a16_phase_timeouts() == 0
 
 
+# ------------------------------------------------------------------ reduction flavours at their limits
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves,reduce", [
+    (5, 72, 16384, 128, 128, 64, 1, 1),      # 128 slices, fp32 atomics + ticket
+    (5, 72, 16384, 128, 128, 64, 1, 3),      # 128 slices, workspace summed in slice order
+    (16, 72, 8192, 128, 64, 64, 1, 4),       # 64 slices, fixed-point adds at 16 rows
+    (16, 136, 8192, 128, 63, 64, 1, 4),      # 63 slices: 64 groups dealt unevenly
+    (3, 65536, 256, 128, 2, 64, 1, 5),       # the last tile origin the in-kernel zeroing covers
+    (16, 65536, 512, 128, 4, 256, 4, 5),     # the same for the streaming kernel
+    (16, 65536, 512, 128, 4, 128, 1, 5),     # and for two strips per wave
+    (2, 72, 8192, 32, 64, 64, 4, 4),         # group_size 32: 256 compute groups, one per wave
+])
+def test_reduction_limits(oracle, m, n, k, g, split_k, tile_cols, waves, reduce):
+    A, qw, s, qz = random_case(m, n, k, g, seed=1400 + m + k % 71)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(3):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, reduce)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} g={g} S={split_k} tile={tile_cols} reduce={reduce} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ extremes of the shape range
 @pytest.mark.parametrize("m,n,k,g,split_k", [
     (4, 66048, 256, 128, 2),      # n beyond the 65536 columns the in-kernel zeroing covers: fill kernel instead
