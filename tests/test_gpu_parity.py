@@ -796,6 +796,43 @@ def test_reduction_limits(oracle, m, n, k, g, split_k, tile_cols, waves, reduce)
     assert b.w4a16_phase_timeouts() == 0
 
 
+def test_random_call_sequence(oracle):
+    """120 calls in random order over a pool of problems and launch variants that share the
+    library's per-device scratch (flags and counts of several split factors, fixed-point words,
+    tickets, workspace): every call must leave that state right for whichever call comes next."""
+    rng = np.random.Generator(np.random.Philox(77))
+    pool = []
+    for (m, n, k, g) in ((16, 520, 2048, 128), (3, 520, 2048, 128), (9, 1032, 1024, 128), (16, 264, 4096, 256),
+                         (5, 200, 1408, 128), (40, 520, 2048, 128)):
+        A, qw, s, qz = random_case(m, n, k, g, seed=1500 + m + n)
+        Cref, _ = oracle.gemm(A, qw, s, qz, g)
+        cg = k // 128
+        variants = [(0, 0, 0, 0), (1, 64, 4, 0)]
+        if m <= 16:
+            for S in (2, 4, 8):
+                if S * 4 <= cg:
+                    variants += [(S, 64, 4, r) for r in (1, 2, 3, 4, 5)]
+                    variants += [(S, 256, 4, 5), (S, 256, 4, 2), (S, 32, 2, 5)]
+            if cg % 4 == 0 and cg // 4 in (2, 4, 8):
+                variants.append((cg // 4, 128, 4, 0))
+            variants += [("dp",), ("streamk", 0), ("streamk", 5)]
+        else:
+            variants += [(2, 256, 4, 5), (4, 0, 0, 0), ("dp",)]
+        pool.append((DeviceProblem(A, qw, s, qz, g), Cref, variants))
+    for step in range(120):
+        p, Cref, variants = pool[int(rng.integers(len(pool)))]
+        v = variants[int(rng.integers(len(variants)))]
+        p.C.fill_(float("nan"))
+        if v[0] == "dp":
+            b.w4a16_gemm_dp(*p.args())
+        elif v[0] == "streamk":
+            b.w4a16_gemm_streamk(*p.args(), v[1])
+        else:
+            b.w4a16_gemm_ex(*p.args(), *v)
+        assert_parity(p.result(), Cref, f"step {step}: m={p.m} n={p.n} k={p.k} g={p.g} variant {v}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ extremes of the shape range
 @pytest.mark.parametrize("m,n,k,g,split_k", [
     (4, 66048, 256, 128, 2),      # n beyond the 65536 columns the in-kernel zeroing covers: fill kernel instead
