@@ -421,6 +421,40 @@ def main():
                         f"{wm.bytes / e / 1e9:.0f} GB/s")
                 del wb
         extra["other_field_widths"] = rows
+        # activation ordering on the headline shape: rows sorted by group once, activations gathered per call
+        kk = w.k
+        rng = np.random.Generator(np.random.Philox(args.seed + 17))
+        order = rng.permutation(kk).astype(np.int32)
+        g_idx = np.empty(kk, np.int32)
+        g_idx[order] = np.arange(kk, dtype=np.int32) // g
+        d_gidx = torch.from_numpy(g_idx).cuda()
+        perm = torch.empty(kk, dtype=torch.int32, device="cuda")
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        A_work = torch.empty_like(w.A)
+        sorted_sets = []
+        for (qw_t, s_t, qz_t) in w.sets:
+            qs = torch.empty_like(qw_t)
+            binding.w4a16_actorder_prepare(qw_t, d_gidx, qs, perm, status, w.n, kk, g)
+            sorted_sets.append((qs, s_t, qz_t))
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        L = binding.lib()
+        import ctypes
+        vp = ctypes.c_void_p
+        ptrs = [tuple(vp(t.data_ptr()) for t in st) for st in sorted_sets]
+
+        def call_actorder(i):
+            qs, sc, qz = ptrs[i % len(ptrs)]
+            rc = L.w4a16_gemm_actorder(vp(w.A.data_ptr()), qs, sc, qz, vp(perm.data_ptr()), vp(A_work.data_ptr()),
+                                       vp(w.C.data_ptr()), w.m, w.n, kk, g, 0, vp(torch.cuda.current_stream().cuda_stream))
+            if rc:
+                raise binding.W4A16Error(rc, "w4a16_gemm_actorder")
+        call_actorder.nsets = len(ptrs)
+        _, e_ao = time_calls(call_actorder, sweep_steps, sweep_warm)
+        extra["activation_ordering_m16_nk4096"] = {"us_per_call": e_ao * 1e6, "plain_us_per_call": ev * 1e6,
+                                                   "note": "one more small launch per call (the gather of A[:, perm])"}
+        log(f"[bench] activation ordering m={w.m} n=k={w.n}: {e_ao * 1e6:.2f} us per call against {ev * 1e6:.2f} plain")
+        del sorted_sets
 
     out = {
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",
