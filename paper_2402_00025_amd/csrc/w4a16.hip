@@ -1353,15 +1353,20 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
         } else {
             // four waves per workgroup and the fewest k slices that give 160 workgroups
+            // (group sizes below 128 make the groups short and the parameter traffic large: sweeps
+            // put their optimum at about 450 workgroups or more, and never at one group per wave)
+            const int want_blocks = group_size < 128 ? 448 : g_stream_min_blocks;
             parts = cgroups < 4 ? cgroups : 4;
-            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < g_stream_min_blocks) parts *= 2;
+            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < want_blocks) parts *= 2;
             // Few rows make the atomic traffic of many slices small: where the count above sits
             // badly on 256 compute units, one group per wave does better; and where that is not
             // to be had and there are more workgroups than fit at once, shorter runs (four groups
             // or more) even out the load.
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
-            if (m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
-                (blocks < 200 || blocks > 320)) {
+            if (group_size < 128) {
+                // as chosen above
+            } else if (m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
+                       (blocks < 200 || blocks > 320)) {
                 parts = cgroups;
             } else if (blocks > 320) {
                 while (parts * 2 <= cgroups && cgroups / (parts * 2) >= 4) parts *= 2;
