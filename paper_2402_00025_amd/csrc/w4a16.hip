@@ -1365,7 +1365,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
             if (group_size < 128) {
                 // as chosen above
-            } else if (m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
+            } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
                        (blocks < 200 || blocks > 320)) {
                 parts = cgroups;
             } else if (blocks > 320) {
