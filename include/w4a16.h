@@ -141,7 +141,9 @@ long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size);
  *
  * w4a16_gemm_actorder, per call: A_work (device, fp16 [m, k], 16-byte aligned, caller's scratch,
  * not A) <- A[:, perm], then the SplitK GEMM of A_work with qweight_sorted, scales and qzeros as
- * w4a16_gemm does it (same rules for split_k).  The gather is one more small kernel per call.
+ * w4a16_gemm does it (same rules for split_k).  The gather is one more small kernel per call; a
+ * caller whose previous operation can write A[:, perm] itself passes that to w4a16_gemm together
+ * with qweight_sorted and needs no gather.
  */
 int w4a16_actorder_prepare(const void* qweight, const void* g_idx, void* qweight_sorted, void* perm, void* status,
                            int n, int k, int group_size, void* stream);
