@@ -37,8 +37,9 @@
  *
  * Split-k scratch: depending on the reduction flavour (W4A16_REDUCE_*) the split-k entry points
  * keep partial sums, arrival counters or per-tile flags in library-owned per-device scratch
- * buffers (at most 16 * n 64-bit words, split_k * m * n floats for the workspace flavour, and a
- * few words per column tile), allocated on the first call that needs them and left consistent
+ * buffers (at most 16 * n 64-bit words, split_k * m * n floats for the workspace flavour, and,
+ * for the in-kernel zeroing, 16 KiB * (1 + split_k) per distinct split_k used), allocated on the
+ * first call that needs them and left consistent
  * for the next call by the kernel itself.  Two split-k calls that overlap in time on the same
  * device (different streams) would share that scratch and must not be issued; calls on one
  * stream are safe.
@@ -72,7 +73,7 @@ extern "C" {
 #define W4A16_REDUCE_ATOMIC_PK_F16_PHASE 5 /* packed-fp16 atomic adds straight into C with no launch before the
                                        GEMM kernel: the first k slice's workgroup zeroes its tile of C inside
                                        the kernel and the others wait for that through a per-tile flag;
-                                       split_k a power of two, 2..64; n <= 65536 */
+                                       split_k 2..64; n <= 65536 */
 
 /*
  * SplitK kernel (Algorithm 1): the grid is (column tiles) x split_k; every workgroup owns one
@@ -156,7 +157,7 @@ int w4a16_gemm_actorder(const void* A, const void* qweight_sorted, const void* s
  *   tile_cols  output columns per workgroup: 16, 32 or 64 (every wave owns the whole tile and the
  *              waves divide the workgroup's k range), 128 (SplitK only, group_size 128 or 256:
  *              as 64, but every wave multiplies its activations with two adjacent 64-column
- *              strips; split_k * waves must equal k / 128, waves <= 4, split_k a power of two,
+ *              strips; split_k * waves must equal k / 128, waves <= 4, split_k 2..64,
  *              reduce W4A16_REDUCE_AUTO or W4A16_REDUCE_ATOMIC_PK_F16_PHASE), or 256 (SplitK only, group_size 128 or
  *              256: four waves own a 64-column strip each and share their activations
  *              through LDS; waves = 4 or 8, i.e. one or two such sets dividing the k range;

@@ -148,7 +148,7 @@ __device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcn
 // group per wave), so that the extra wave costs no occupancy.
 // WMAX (4 or 16) is the largest number of working waves the instantiation may be launched with;
 // the small one lets the compiler use more than 128 registers per lane.
-constexpr int kPhaseMaxSplit = 64;          // split_k of the phase protocol: a power of two up to this
+constexpr int kPhaseMaxSplit = 64;          // largest split_k of the phase protocol
 constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
@@ -1140,14 +1140,14 @@ struct DeviceScratch {
     Buffer partials;  // workspace mode: fp32 [split_k, m, n]; no invariant
     Buffer fixed;     // fixed-point mode: uint64 [16, n]; all zero whenever no call is running
     Buffer tickets;   // uint32 per column tile; all zero whenever no call is running
-    Buffer phase;     // phase mode, uint32: per split_k = 2^j (j = 1..6) flags [kPhaseOrigins] and counts
-                      // [kPhaseOrigins][split_k]; then the error count [1]
+    // phase mode, uint32: one buffer per split_k in use (2..kPhaseMaxSplit), allocated on the first
+    // call with that split_k: flags [kPhaseOrigins], then counts [kPhaseOrigins][split_k]
+    Buffer phase_level[kPhaseMaxSplit + 1];
+    Buffer phase_err;  // the error count [1]
 };
-// Word offsets inside DeviceScratch::phase for split_k = 2^j.
-static size_t phase_flags_offset(int j) { return (size_t)(j - 1) * kPhaseOrigins; }
-static size_t phase_counts_offset(int j) { return 6 * (size_t)kPhaseOrigins + (size_t)kPhaseOrigins * ((1u << j) - 2u); }
-static size_t phase_errors_offset() { return phase_counts_offset(7); }
-static size_t phase_words() { return phase_errors_offset() + 1; }
+// Word offset of the counts inside a level's buffer, and the buffer's size in words.
+static size_t phase_counts_offset() { return kPhaseOrigins; }
+static size_t phase_level_words(int split_k) { return (size_t)kPhaseOrigins * (1 + (size_t)split_k); }
 // Text of the last failed HIP call on this host thread (for W4A16_ERR_HIP diagnostics).
 static thread_local char g_hip_detail[256] = "";
 
@@ -1207,11 +1207,8 @@ struct Plan {
     int split_k, tile_cols, waves, reduce;
 };
 
-// The phase protocol keeps one set of words per split_k: powers of two up to kPhaseMaxSplit.
-static bool phase_split_ok(int split_k)
-{
-    return split_k >= 2 && split_k <= kPhaseMaxSplit && (split_k & (split_k - 1)) == 0;
-}
+// The phase protocol keeps one set of words per split_k, for any split_k up to kPhaseMaxSplit.
+static bool phase_split_ok(int split_k) { return split_k >= 2 && split_k <= kPhaseMaxSplit; }
 
 // Launch shape, from sweeps on MI355X (256 compute units, 1024 SIMDs).
 //
@@ -1289,10 +1286,18 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             S = 1;
             while (S * 2 <= 32 && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
             if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2) S *= 2;
+            // A split_k that is no power of two fills the machine where the powers of two leave it
+            // under-filled or spill over it: the largest one with at most 256 workgroups, if that
+            // gives 200 or more and runs of four groups or more (n = 5120, k = 13824: 12 slices, 240
+            // workgroups, 11.6 us against 12.8 with 8 slices).
+            const int s_fill = 256 / stiles < 32 ? 256 / stiles : 32;
+            const bool fill = s_fill >= 3 && (s_fill & (s_fill - 1)) != 0 && stiles * s_fill >= 200 &&
+                              (stiles * S < 224 || stiles * S > 256) && cgroups / s_fill >= 4;
+            if (fill) S = s_fill;
             // Where that count sits badly on 256 compute units (under 200 or over 256), 128-192
             // workgroups of eight waves do better, if each of their two k parts gets a long run
             // (eight groups or more): twice the loads in flight per compute unit.
-            if (waves == 0 && m <= 16 && (stiles * S < 200 || stiles * S > 256)) {
+            if (!fill && waves == 0 && m <= 16 && (stiles * S < 200 || stiles * S > 256)) {
                 int S8 = 1;
                 while (stiles * S8 * 2 <= 192) S8 *= 2;
                 if (stiles * S8 >= 128 && cgroups % (2 * S8) == 0 && cgroups / (2 * S8) >= 8) {
@@ -1424,10 +1429,13 @@ static int grow(Buffer& b, size_t bytes, bool* grew)
     return W4A16_OK;
 }
 
+// phase_split: 0, or the split_k whose flags and counts the call needs (*phase <- that level's
+// buffer, *phase_err <- the error word).
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
-                          bool want_phase, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
-                          uint32_t** phase)
+                          int phase_split, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
+                          uint32_t** phase, uint32_t** phase_err)
 {
+    if (phase_split < 0 || phase_split > kPhaseMaxSplit) return W4A16_ERR_UNSUPPORTED;
     int dev = 0;
     if (!W4A16_HIP(hipGetDevice(&dev))) return W4A16_ERR_HIP;
     if (dev < 0 || dev >= kMaxDevices) return W4A16_ERR_UNSUPPORTED;
@@ -1438,14 +1446,18 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
     if (rc == W4A16_OK) rc = grow(s.partials, partial_floats * sizeof(float), &grew);
     if (rc == W4A16_OK) rc = grow(s.fixed, fixed_words * sizeof(uint64_t), &grew);
     if (rc == W4A16_OK) rc = grow(s.tickets, ticket_count * sizeof(uint32_t), &grew);
-    if (rc == W4A16_OK && want_phase) rc = grow(s.phase, phase_words() * sizeof(uint32_t), &grew);
+    if (rc == W4A16_OK && phase_split) {
+        rc = grow(s.phase_level[phase_split], phase_level_words(phase_split) * sizeof(uint32_t), &grew);
+        if (rc == W4A16_OK) rc = grow(s.phase_err, sizeof(uint32_t), &grew);
+    }
     if (rc != W4A16_OK) return rc;
     if (grew && !W4A16_HIP(hipDeviceSynchronize())) return W4A16_ERR_HIP;
     *sums = (float*)s.sums.ptr;
     *partials = (float*)s.partials.ptr;
     *fixed = (uint64_t*)s.fixed.ptr;
     *tickets = (uint32_t*)s.tickets.ptr;
-    *phase = (uint32_t*)s.phase.ptr;
+    *phase = phase_split ? (uint32_t*)s.phase_level[phase_split].ptr : nullptr;
+    *phase_err = (uint32_t*)s.phase_err.ptr;
     return W4A16_OK;
 }
 
@@ -1602,8 +1614,8 @@ static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, 
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
-                          bool want_phase, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
-                          uint32_t** phase);
+                          int phase_split, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
+                          uint32_t** phase, uint32_t** phase_err);
 
 // tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
 // m <= 64; more than 16 rows need waves = 4.
@@ -1650,14 +1662,12 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
             if (!phase_split_ok(split_k) || (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
             float *sums = nullptr, *partials = nullptr;
             uint64_t* fixed = nullptr;
-            uint32_t *tickets = nullptr, *phase = nullptr;
-            const int rc = ensure_scratch(0, 0, 0, 0, true, &sums, &partials, &fixed, &tickets, &phase);
+            uint32_t *tickets = nullptr, *phase = nullptr, *phase_err = nullptr;
+            const int rc = ensure_scratch(0, 0, 0, 0, split_k, &sums, &partials, &fixed, &tickets, &phase, &phase_err);
             if (rc != W4A16_OK) return rc;
-            int j = 0;
-            while ((1 << j) < split_k) ++j;
-            a.flags = phase + phase_flags_offset(j);
-            a.counts = phase + phase_counts_offset(j);
-            a.errors = phase + phase_errors_offset();
+            a.flags = phase;
+            a.counts = phase + phase_counts_offset();
+            a.errors = phase_err;
             mode = kAtomicPkF16Phase;
         } else {
             const size_t words = (size_t)m * n / 2;
@@ -1800,20 +1810,19 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         if (mode != kAtomicPkF16) {
             float *sums = nullptr, *partials = nullptr;
             uint64_t* fixed = nullptr;
-            uint32_t* phase = nullptr;
+            uint32_t *phase = nullptr, *phase_err = nullptr;
             if (mode == kAtomicPkF16Phase && (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
             rc = ensure_scratch(mode == kAtomicF32 ? (size_t)16 * n : 0,
                                 mode == kWorkspace ? (size_t)plan.split_k * m * n : 0,
                                 mode == kAtomicFixed ? (size_t)16 * n : 0, (size_t)a.tiles,
-                                mode == kAtomicPkF16Phase, &sums, &partials, &fixed, &a.tickets, &phase);
+                                mode == kAtomicPkF16Phase ? plan.split_k : 0, &sums, &partials, &fixed, &a.tickets,
+                                &phase, &phase_err);
             if (rc != W4A16_OK) return rc;
             a.scratch = mode == kAtomicF32 ? sums : mode == kWorkspace ? partials : (float*)fixed;
             if (mode == kAtomicPkF16Phase) {
-                int j = 0;
-                while ((1 << j) < plan.split_k) ++j;
-                a.flags = phase + phase_flags_offset(j);
-                a.counts = phase + phase_counts_offset(j);
-                a.errors = phase + phase_errors_offset();
+                a.flags = phase;
+                a.counts = phase + phase_counts_offset();
+                a.errors = phase_err;
             }
         } else {
             const size_t words = (size_t)m * n / 2;
@@ -2050,10 +2059,10 @@ long long w4a16_phase_timeouts(void)
     if (dev < 0 || dev >= w4a16::kMaxDevices) return W4A16_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(w4a16::g_mutex);
     const w4a16::DeviceScratch& s = w4a16::g_scratch[dev];
-    if (!s.phase.ptr) return 0;
+    if (!s.phase_err.ptr) return 0;
     uint32_t count = 0;
     if (hipDeviceSynchronize() != hipSuccess) return W4A16_ERR_HIP;
-    if (hipMemcpy(&count, (const uint32_t*)s.phase.ptr + w4a16::phase_errors_offset(), sizeof(count),
+    if (hipMemcpy(&count, (const uint32_t*)s.phase_err.ptr, sizeof(count),
                   hipMemcpyDeviceToHost) != hipSuccess)
         return W4A16_ERR_HIP;
     return (long long)count;
@@ -2071,7 +2080,9 @@ int w4a16_release_scratch(void)
     if (s.partials.ptr) (void)hipFree(s.partials.ptr);
     if (s.fixed.ptr) (void)hipFree(s.fixed.ptr);
     if (s.tickets.ptr) (void)hipFree(s.tickets.ptr);
-    if (s.phase.ptr) (void)hipFree(s.phase.ptr);
+    for (w4a16::Buffer& level : s.phase_level)
+        if (level.ptr) (void)hipFree(level.ptr);
+    if (s.phase_err.ptr) (void)hipFree(s.phase_err.ptr);
     s = w4a16::DeviceScratch{};
     return W4A16_OK;
 }

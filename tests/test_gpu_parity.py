@@ -833,6 +833,26 @@ def test_random_call_sequence(oracle):
     assert b.w4a16_phase_timeouts() == 0
 
 
+@pytest.mark.parametrize("m,n,k,g,split_k,tile_cols,waves", [
+    (16, 200, 1536, 128, 3, 64, 4),       # three slices of four groups, per-wave kernel
+    (9, 328, 1920, 128, 5, 64, 1),        # five slices of three groups
+    (16, 520, 3072, 128, 6, 256, 4),      # streaming kernel, six slices
+    (16, 520, 1664, 128, 13, 256, 4),     # thirteen slices of one group: ring depth 1
+    (7, 264, 5120, 128, 10, 128, 4),      # two strips per wave, ten slices
+    (16, 264, 3584, 128, 7, 64, 4),       # seven slices, service wavefront (one group per wave)
+])
+def test_phase_protocol_any_split(oracle, m, n, k, g, split_k, tile_cols, waves):
+    """The in-kernel zeroing keeps its flags and counts per split_k, for any split_k up to 64."""
+    A, qw, s, qz = random_case(m, n, k, g, seed=1600 + m + k % 53)
+    Cref, _ = oracle.gemm(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(3):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_ex(*p.args(), split_k, tile_cols, waves, b.REDUCE_ATOMIC_PK_F16_PHASE)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} S={split_k} tile={tile_cols} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ extremes of the shape range
 @pytest.mark.parametrize("m,n,k,g,split_k", [
     (4, 66048, 256, 128, 2),      # n beyond the 65536 columns the in-kernel zeroing covers: fill kernel instead
