@@ -1253,15 +1253,15 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         return W4A16_OK;
     }
     // Two strips per wave (128-column tiles, one compute group per wave, in-kernel zeroing by the
-    // service wavefront): when k is short enough for that (k / 128 = 4 split_k, split_k a power
-    // of two up to 16, i.e. k <= 8192), there is more than one row, at least 160 workgroups, and
-    // less than 32 MiB of packed weights (28 MiB at split_k = 16).  0-7 % faster than the
+    // service wavefront): when k is short enough for that (k / 128 = 4 split_k with split_k up
+    // to 16, i.e. k <= 8192), there is more than one row, at least 160 workgroups, and less
+    // than 32 MiB of packed weights (25 MiB beyond split_k = 8).  0-7 % faster than the
     // single-strip launch with fixed-point adds at m = 2..4, 1-4 % at m = 8..16, and up to 19 %
     // faster than the streaming kernel on matrices of 16-25 MiB.
     if (library_choice && m >= 2 && group_size >= 128 &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
         phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
-        packed_bytes < (cgroups / 4 == 16 ? (28ll << 20) : (32ll << 20)) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
+        packed_bytes < (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20)) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
         out->split_k = cgroups / 4;
         out->tile_cols = 128;
         out->waves = 4;
