@@ -142,6 +142,50 @@ def test_uneven_k_shares_host_rules():
                 assert tiles * pl["split_k"] >= 160, (m, n, k, dp, pl)
 
 
+def test_plan_invariants_over_a_grid_of_shapes():
+    """Whatever the library picks must be a launch the kernels accept: enough compute groups for
+    every k part, the exact-fit condition of the two-strip launch, equal parts for eight-wave
+    streaming workgroups, a reduction flavour that takes the split, and a split small enough
+    for the accuracy of the packed-fp16 adds."""
+    ns = (8, 72, 1024, 2304, 4096, 4360, 5120, 6144, 9216, 11008, 12288, 14336, 22016, 28672, 66048)
+    ks = (128, 512, 1024, 1408, 2048, 4096, 5120, 7168, 8192, 11008, 13824, 28672)
+    count = 0
+    for g in (32, 64, 128, 256):
+        for m in (1, 3, 4, 5, 8, 16, 17, 40, 64):
+            for n in ns:
+                for k in ks:
+                    if k % g or n * k >= 1 << 31:
+                        continue
+                    for dp in (False, True):
+                        pl = b.w4a16_plan(m, n, k, g, dp=dp)
+                        S, tc, wv, red = pl["split_k"], pl["tile_cols"], pl["waves"], pl["reduce"]
+                        cg = k // min(g, 128)
+                        assert tc in (16, 32, 64, 128, 256) and 1 <= wv <= 16 and S >= 1, (m, n, k, g, dp, pl)
+                        kparts = wv // 4 if tc == 256 else wv
+                        assert S * kparts <= cg, (m, n, k, g, dp, pl)
+                        if dp:
+                            assert S == 1 and tc in (16, 32, 64)
+                            continue
+                        if tc == 128:
+                            assert S * wv == cg and g >= 128 and 2 <= S <= 64 and n <= 65536 and m <= 16
+                        if tc == 256:
+                            assert g >= 128 and wv in (4, 8)
+                            if wv == 8:
+                                assert cg % (2 * S) == 0 and m <= 16
+                        else:
+                            assert m <= 16 or g < 128        # more rows go to the streaming kernel where it applies
+                        if S > 1:
+                            assert red in (1, 2, 3, 4, 5)
+                            if red == 5:
+                                assert S <= 64 and n <= 65536
+                            if red == 4:
+                                assert S <= 64
+                            if red in (2, 5):
+                                assert S <= 32, (m, n, k, g, pl)     # the library's own choice keeps the fp16 adds accurate
+                        count += 1
+    assert count > 3000
+
+
 def test_algorithmic_bytes():
     """The library, the input module and the figures derived from the paper's profile agree."""
     for (m, nk, expect) in ((1, 1024, 548864), (1, 4096, 8732672), (16, 4096, 8978432), (1, 8192, 34897920),
