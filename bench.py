@@ -132,6 +132,15 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
                   else gemm_dp(A, qw, s, qz, C, m, n, k, g, st))
             if rc:
                 raise binding.W4A16Error(rc, f"w{w.bits}a16_gemm")
+    elif kind == "read":
+        nbytes = w.sets[0][0].numel() * 4
+        read_shape = split_k   # the probe's launch shape rides in the split_k argument
+
+        def call(i):
+            qw, _s, _qz = ptrs[i % nsets]
+            rc = L.w4a16_read_probe(qw, nbytes, read_shape, ctypes.c_void_p(current_stream().cuda_stream))
+            if rc:
+                raise binding.W4A16Error(rc, "w4a16_read_probe")
     elif kind == "streamk":
         def call(i):
             qw, s, qz = ptrs[i % nsets]
@@ -323,6 +332,17 @@ def main():
              "eager_us_per_call_400_steps": ev_eager * 1e6,
              "eager_note": "eager launches from Python cost the host ~7-8 us per call (two launches), so long eager "
                            "runs of the small shapes are host-bound"}
+
+    # the achievable ceiling on this machine: a plain read of the packed weights alone, same protocol
+    ev_read = min(time_calls(make_call(w, "read", split_k=shape), min(args.steps, 400), 50)[1] for shape in range(5))
+    packed_bytes = w.sets[0][0].numel() * 4
+    extra["plain_read_of_packed_weights"] = {"bytes": packed_bytes, "us_per_launch": ev_read * 1e6,
+                                             "note": "best of the probe's five launch shapes",
+                                             "GBps": packed_bytes / ev_read / 1e9,
+                                             "frac_of_peak": packed_bytes / ev_read / 1e9 / HBM_PEAK_GBPS,
+                                             "gemm_over_read": ev / ev_read}
+    log(f"[bench] plain read of the packed weights ({packed_bytes / 2**20:.0f} MiB): {ev_read * 1e6:.2f} us per launch, "
+        f"{packed_bytes / ev_read / 1e9:.0f} GB/s; the GEMM takes {ev / ev_read:.2f}x that")
 
     if not args.no_sweep:
         sweep_steps, sweep_warm = 400, 50

@@ -196,6 +196,16 @@ int w4a16_unpack(const void* qweight, const void* qzeros, void* q_u8, void* z_u8
 int w4a16_dequant(const void* qweight, const void* scales, const void* qzeros, void* W,
                   int n, int k, int group_size, void* stream);
 
+/*
+ * Measurement probe: a plain coalesced read of `bytes` (a multiple of 16) from a 16-byte aligned
+ * device buffer, result discarded.  Timed like a GEMM call on the same buffers it gives the
+ * ceiling that any kernel which has to read them can reach on this machine.  `shape` 0..4
+ * picks one of five launch shapes (loads in flight per lane x workgroups x threads: 8 x one
+ * pass x 256, 8 x 2048 x 256, 4 x 2048 x 512, 2 x 8192 x 256, 1 x 16384 x 256); which is fastest
+ * depends on the size, so a bench takes the best of them.
+ */
+int w4a16_read_probe(const void* buffer, long long bytes, int shape, void* stream);
+
 /* Bytes every call has to move at least once: qweight + scales + qzeros + A + C. */
 long long w4a16_algorithmic_bytes(int m, int n, int k, int group_size);
 

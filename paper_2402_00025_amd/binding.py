@@ -26,6 +26,7 @@ EXPORTS = (
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
     "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
+    "w4a16_read_probe",
 )
 
 _lib = None
@@ -66,6 +67,7 @@ def lib() -> ctypes.CDLL:
     L.w8a16_algorithmic_bytes.restype = ctypes.c_longlong
     L.w4a16_actorder_prepare.argtypes = [vp] * 5 + [ci] * 3 + [vp]
     L.w4a16_gemm_actorder.argtypes = [vp] * 7 + [ci] * 5 + [vp]
+    L.w4a16_read_probe.argtypes = [vp, ctypes.c_longlong, ci, vp]
     L.w2a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w2a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
     L.w2a16_algorithmic_bytes.argtypes = [ci] * 4
@@ -168,6 +170,10 @@ def w4a16_gemm_actorder(A, qweight_sorted, scales, qzeros, perm, A_work, C, m, n
                         stream=None) -> None:
     _check(lib().w4a16_gemm_actorder(_p(A), _p(qweight_sorted), _p(scales), _p(qzeros), _p(perm), _p(A_work), _p(C),
                                      m, n, k, group_size, split_k, _stream(stream)), "w4a16_gemm_actorder")
+
+
+def w4a16_read_probe(buffer, nbytes, shape=0, stream=None) -> None:
+    _check(lib().w4a16_read_probe(_p(buffer), nbytes, shape, _stream(stream)), "w4a16_read_probe")
 
 
 def w4a16_gemm_streamk(A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups=0, stream=None) -> None:

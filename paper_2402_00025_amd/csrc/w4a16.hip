@@ -1091,6 +1091,25 @@ __global__ void actorder_gather_kernel(const _Float16* __restrict__ A, const int
     A_work[idx] = A[(size_t)i * k + src];
 }
 
+// ---- measurement probe: a plain coalesced read of a buffer (U 16-byte loads in flight per
+// lane, grid-stride), the ceiling any kernel that has to read those bytes can reach
+template <int U>
+__global__ void __launch_bounds__(512) read_probe_kernel(const u32x4_t* __restrict__ p, size_t vecs, uint32_t* sink)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    for (; i + (U - 1) * stride < vecs; i += U * stride) {
+        u32x4_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u];
+    }
+    for (; i < vecs; i += stride) acc ^= p[i];
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && sink) sink[0] = acc.x;  // keeps the loads alive
+}
+
 // ---- test probes: the same unpack_shift / zero_const / field routines as the GEMM ----------
 // q_u8[kk][j] and z_u8[gi][j]; one thread per packed word.
 __global__ void unpack_kernel(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* q_u8, uint8_t* z_u8,
@@ -2024,6 +2043,30 @@ int w4a16_dequant(const void* qweight, const void* scales, const void* qzeros, v
     hipLaunchKernelGGL(w4a16::dequant_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        (const uint32_t*)qweight, (const _Float16*)scales, (const uint32_t*)qzeros, (_Float16*)W, n,
                        k, group_size);
+    return w4a16::W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
+}
+
+int w4a16_read_probe(const void* buffer, long long bytes, int shape, void* stream)
+{
+    if (!buffer) return W4A16_ERR_NULL;
+    if (bytes < 16 || (bytes % 16) != 0 || !w4a16::aligned16(buffer)) return W4A16_ERR_SHAPE;
+    const size_t vecs = (size_t)bytes / 16;
+    const w4a16::u32x4_t* p = (const w4a16::u32x4_t*)buffer;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t* none = nullptr;
+    switch (shape) {
+    case 0: {  // one pass: every lane issues its eight loads and is done
+        const size_t blocks = (vecs + 256 * 8 - 1) / (256 * 8);
+        hipLaunchKernelGGL(w4a16::read_probe_kernel<8>, dim3((unsigned)(blocks < 65535 ? blocks : 65535)), dim3(256), 0, st,
+                           p, vecs, none);
+        break;
+    }
+    case 1: hipLaunchKernelGGL(w4a16::read_probe_kernel<8>, dim3(2048), dim3(256), 0, st, p, vecs, none); break;
+    case 2: hipLaunchKernelGGL(w4a16::read_probe_kernel<4>, dim3(2048), dim3(512), 0, st, p, vecs, none); break;
+    case 3: hipLaunchKernelGGL(w4a16::read_probe_kernel<2>, dim3(8192), dim3(256), 0, st, p, vecs, none); break;
+    case 4: hipLaunchKernelGGL(w4a16::read_probe_kernel<1>, dim3(16384), dim3(256), 0, st, p, vecs, none); break;
+    default: return W4A16_ERR_UNSUPPORTED;
+    }
     return w4a16::W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
