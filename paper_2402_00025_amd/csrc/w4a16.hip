@@ -1264,7 +1264,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // the launch of the data-parallel kernel: narrower tiles until there are 160 workgroups
         int tc = 64;
         while (tc > 16 && (n + tc - 1) / tc < g_stream_min_blocks) tc /= 2;
-        const int wv = tc < 64 && m <= 4 ? 8 : 4;
+        const int wv = tc < 64 && m <= 12 ? 8 : 4;
         out->split_k = 1;
         out->tile_cols = tc;
         out->waves = cgroups < wv ? largest_wave_split(cgroups, 1, wv) : wv;
@@ -1407,8 +1407,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         if (waves == 0) waves = w;
     }
     if (split_k < 1 || split_k > cgroups) return W4A16_ERR_SPLIT;
-    // data-parallel, narrow tiles: eight waves divide k for up to four rows, four beyond (sweeps)
-    if (waves == 0) waves = largest_wave_split(cgroups, split_k, dp && tile_cols < 64 && m <= 4 ? 8 : 4);
+    // data-parallel, narrow tiles: eight waves divide k for up to twelve rows, four beyond (sweeps)
+    if (waves == 0) waves = largest_wave_split(cgroups, split_k, dp && tile_cols < 64 && m <= 12 ? 8 : 4);
     if (waves < 1 || waves > 16 || (long long)split_k * waves > cgroups) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_AUTO) {
         // few rows: the arrival-counting fixed-point adds finish in one round trip with no
