@@ -276,7 +276,7 @@ def main():
                     help="also run plain 256 MiB device copies (reference traffic for rocprofv3 counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU; the kernel has no multi-GPU path (see DESIGN.md). Use --gpus 1.")
+        log("bench.py: this build runs on ONE GPU; the kernel has no multi-GPU path. Use --gpus 1.")
         sys.exit(2)
 
     import torch
