@@ -389,10 +389,12 @@ def main():
                 res.append({"split_k": S, "us": e * 1e6, "GBps": wb.bytes / e / 1e9,
                             "frac_of_peak": wb.bytes / e / 1e9 / HBM_PEAK_GBPS})
             _, e_dp = time_calls(make_call(wb, "dp"), 200, 30)
-            extra[key] = {"splitk": res, "dp_us": e_dp * 1e6}
+            e_rd = min(time_calls(make_call(wb, "read", split_k=shape), 200, 30)[1] for shape in range(5))
+            extra[key] = {"splitk": res, "dp_us": e_dp * 1e6, "plain_read_of_packed_weights_us": e_rd * 1e6}
             best = min(res, key=lambda r: r["us"])
             log(f"[bench] m={mm} n=k={nk}: best split_k={best['split_k']} {best['us']:.2f} us "
-                f"({best['GBps']:.0f} GB/s, {100 * best['frac_of_peak']:.1f}% of peak), dp {e_dp * 1e6:.2f} us")
+                f"({best['GBps']:.0f} GB/s, {100 * best['frac_of_peak']:.1f}% of peak), dp {e_dp * 1e6:.2f} us, "
+                f"plain read of the packed weights {e_rd * 1e6:.2f} us")
             del wb
 
         # non-square shapes: the linear layers of llama-7B/13B/70B style decoders (fused qkv,
