@@ -1277,7 +1277,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // than 32 MiB of packed weights (25 MiB beyond split_k = 8).  0-7 % faster than the
     // single-strip launch with fixed-point adds at m = 2..4, 1-4 % at m = 8..16, and up to 19 %
     // faster than the streaming kernel on matrices of 16-25 MiB.
-    if (library_choice && m >= 2 && group_size >= 128 &&
+    // (not where the 64-column tiles alone give 200-256 workgroups: one workgroup per tile over
+    // all of k, stored without atomics, is 4-7 % faster there)
+    if (library_choice && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
         phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
         packed_bytes < (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20)) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
@@ -1288,7 +1290,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         return W4A16_OK;
     }
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
-    // tile_cols = 256, or chosen when the activation operand is large (m >= 8) and the weight
+    // tile_cols = 256, or chosen when the activation operand is large (m >= 5) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
     if (!dp && bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
         // more than 16 rows come here only when the streaming kernel can take them
@@ -1329,7 +1331,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // fewer rows (3..7): only on large matrices, and only with a count that sits well
         const bool few_rows_ok = m >= 3 && packed_bytes >= (48ll << 20) &&
                                  (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256));
-        const bool worth = S <= cgroups && ((m >= 8 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
+        // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
+        // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
+        const bool worth = S <= cgroups && ((m >= 5 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
             waves = stream_waves;
