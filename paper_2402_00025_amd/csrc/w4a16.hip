@@ -1306,7 +1306,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             // (at most 32 slices: the packed-fp16 adds round once per slice)
             S = 1;
             while (S * 2 <= 32 && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
-            if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2) S *= 2;
+            // (with more than 16 rows a compute unit holds one workgroup, and 258 of them take two
+            // rounds: n = 11008, k = 4096, m = 32: 19.2 us with 258 against 11.9 with 215)
+            if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2 &&
+                (m <= 16 || stiles * S * 2 <= 256))
+                S *= 2;
             // A split_k that is no power of two fills the machine where the powers of two leave it
             // under-filled or spill over it: the largest one with at most 256 workgroups, if that
             // gives 200 or more and runs of four groups or more (n = 5120, k = 13824: 12 slices, 240
