@@ -1260,10 +1260,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Short k (up to 1024, or up to 2048 when the column tiles alone fill the machine once):
     // no split at all.  The call is a latency chain of a few microseconds, and zeroing, atomics
     // and further waves only add to it.
-    if (library_choice && group_size >= 128 && (cgroups <= 8 || (cgroups <= 16 && tiles64 >= 170 && tiles64 <= 256))) {
+    // A random-shape audit added: also up to k = 2176 from 130 column tiles on (n = 8848,
+    // k = 1792, m = 16: 5.6 us against 7.5 with two slices); with five rows or more (where a
+    // split costs the zeroing protocol) up to k = 3072 at 190-256 tiles, and, up to eight rows,
+    // up to k = 5632 there.
+    const bool fills_once = tiles64 >= 190 && tiles64 <= 256;
+    const bool no_split = cgroups <= 8 || (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
+                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 8 && cgroups <= 44 && fills_once)));
+    if (library_choice && group_size >= 128 && no_split) {
         // the launch of the data-parallel kernel: narrower tiles until there are 160 workgroups
         int tc = 64;
-        while (tc > 16 && (n + tc - 1) / tc < g_stream_min_blocks) tc /= 2;
+        while (tc > 16 && (n + tc - 1) / tc < g_stream_min_blocks && (n + tc / 2 - 1) / (tc / 2) <= 256) tc /= 2;
         const int wv = tc < 64 && m <= 12 ? 8 : 4;
         out->split_k = 1;
         out->tile_cols = tc;
@@ -1332,9 +1339,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             }
         }
         const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
-        // fewer rows (3..7): only on large matrices, and only with a count that sits well
-        const bool few_rows_ok = m >= 3 && packed_bytes >= (48ll << 20) &&
-                                 (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256));
+        // Fewer rows: only with a count that sits well, and only on large matrices or where the
+        // per-wave kernel's own count (64-column tiles x its split) exceeds the 256 compute units
+        // and one group per wave is not to be had (n = 18584, k = 12032, m = 2: 291 workgroups of the per-wave
+        // kernel take 35.2 us, 219 of the streaming kernel 24.1).
+        int pw_parts = cgroups < 4 ? cgroups : 4;
+        while (pw_parts >= 4 && pw_parts * 2 <= cgroups && tiles64 * (pw_parts / 4) < g_stream_min_blocks) pw_parts *= 2;
+        const int pw_blocks = tiles64 * (pw_parts >= 4 ? pw_parts / 4 : 1);
+        const bool pw_one_group = m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20);
+        const bool pw_bad = pw_blocks > 256 && !pw_one_group;
+        const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256)) &&
+                                 ((m >= 3 && packed_bytes >= (48ll << 20)) || (packed_bytes > (8ll << 20) && pw_bad));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
         const bool worth = S <= cgroups && ((m >= 5 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
@@ -1366,7 +1381,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         if (dp && bits == 4) {
             // narrower tiles until there are 160 workgroups (sweeps: 160-256 workgroups beat both
             // fewer, wider tiles and more than 256 narrow ones)
-            while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < g_stream_min_blocks) tile_cols /= 2;
+            // ... but never beyond 256 (n = 8848: 139 tiles of 64 take 5.6 us, 277 of 32 take 7.4)
+            while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < g_stream_min_blocks &&
+                   (n + tile_cols / 2 - 1) / (tile_cols / 2) <= 256)
+                tile_cols /= 2;
         }
     }
     // 128 columns: two 64-column strips per wave, one compute group per wave, in-kernel zeroing
@@ -1398,9 +1416,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             if (group_size < 128) {
                 // as chosen above
             } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
-                       (blocks < 200 || blocks > 320)) {
+                       (blocks < 200 || blocks > 256)) {
                 parts = cgroups;
-            } else if (blocks > 320) {
+            } else if (blocks > 256) {
                 while (parts * 2 <= cgroups && cgroups / (parts * 2) >= 4) parts *= 2;
             }
         }
