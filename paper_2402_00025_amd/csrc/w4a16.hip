@@ -1344,10 +1344,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // and one group per wave is not to be had (n = 18584, k = 12032, m = 2: 291 workgroups of the per-wave
         // kernel take 35.2 us, 219 of the streaming kernel 24.1).
         int pw_parts = cgroups < 4 ? cgroups : 4;
-        while (pw_parts >= 4 && pw_parts * 2 <= cgroups && tiles64 * (pw_parts / 4) < g_stream_min_blocks) pw_parts *= 2;
+        while (pw_parts >= 4 && pw_parts * 2 <= cgroups && tiles64 * (pw_parts / 4) < g_stream_min_blocks &&
+               tiles64 * (pw_parts / 2) <= 256)
+            pw_parts *= 2;
         const int pw_blocks = tiles64 * (pw_parts >= 4 ? pw_parts / 4 : 1);
         const bool pw_one_group = m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20);
-        const bool pw_bad = pw_blocks > 256 && !pw_one_group;
+        // (or stays under 160 while the streaming kernel's slices keep five groups or more)
+        const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
         const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256)) &&
                                  ((m >= 3 && packed_bytes >= (48ll << 20)) || (packed_bytes > (8ll << 20) && pw_bad));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
@@ -1407,7 +1410,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             // put their optimum at about 450 workgroups or more, and never at one group per wave)
             const int want_blocks = group_size < 128 ? 448 : g_stream_min_blocks;
             parts = cgroups < 4 ? cgroups : 4;
-            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < want_blocks) parts *= 2;
+            // (never past 256 workgroups for the long groups: 140 beat 280)
+            while (parts >= 4 && parts * 2 <= cgroups && tiles * (parts / 4) < want_blocks &&
+                   (group_size < 128 || tiles * (parts / 2) <= 256))
+                parts *= 2;
             // Few rows make the atomic traffic of many slices small: where the count above sits
             // badly on 256 compute units, one group per wave does better; and where that is not
             // to be had and there are more workgroups than fit at once, shorter runs (four groups
