@@ -1260,17 +1260,22 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Short k (up to 1024, or up to 2048 when the column tiles alone fill the machine once):
     // no split at all.  The call is a latency chain of a few microseconds, and zeroing, atomics
     // and further waves only add to it.
-    // A random-shape audit added: also up to k = 2176 from 130 column tiles on (n = 8848,
-    // k = 1792, m = 16: 5.6 us against 7.5 with two slices); with five rows or more (where a
+    // A random-shape audit added: also up to k = 1536 when the data-parallel tiling gives 130-256
+    // workgroups, up to k = 2176 from 130 tiles of 64 columns on (n = 8848, k = 1792, m = 16:
+    // 5.6 us against 7.5 with two slices); with five rows or more (where a
     // split costs the zeroing protocol) up to k = 3072 at 190-256 tiles, and, up to eight rows,
     // up to k = 5632 there.
+    int dp_cols = 64;  // the data-parallel kernel's tile width: narrower until 160 workgroups, never past 256
+    while (dp_cols > 16 && (n + dp_cols - 1) / dp_cols < g_stream_min_blocks && (n + dp_cols / 2 - 1) / (dp_cols / 2) <= 256)
+        dp_cols /= 2;
+    const int dp_tiles = (n + dp_cols - 1) / dp_cols;
     const bool fills_once = tiles64 >= 190 && tiles64 <= 256;
-    const bool no_split = cgroups <= 8 || (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
+    const bool no_split = cgroups <= 8 || (cgroups <= 12 && dp_tiles >= 130 && dp_tiles <= 256) ||
+                          (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
                           (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 8 && cgroups <= 44 && fills_once)));
     if (library_choice && group_size >= 128 && no_split) {
-        // the launch of the data-parallel kernel: narrower tiles until there are 160 workgroups
-        int tc = 64;
-        while (tc > 16 && (n + tc - 1) / tc < g_stream_min_blocks && (n + tc / 2 - 1) / (tc / 2) <= 256) tc /= 2;
+        // the launch of the data-parallel kernel
+        const int tc = dp_cols;
         const int wv = tc < 64 && m <= 12 ? 8 : 4;
         out->split_k = 1;
         out->tile_cols = tc;
@@ -1313,17 +1318,16 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             // (at most 32 slices: the packed-fp16 adds round once per slice)
             S = 1;
             while (S * 2 <= 32 && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256) S *= 2;
-            // (with more than 16 rows a compute unit holds one workgroup, and 258 of them take two
-            // rounds: n = 11008, k = 4096, m = 32: 19.2 us with 258 against 11.9 with 215)
-            if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2 &&
-                (m <= 16 || stiles * S * 2 <= 256))
+            // (never past 256: n = 11008, k = 4096, m = 32: 19.2 us with 258 workgroups against 11.9
+            // with 215; n = 16576, k = 1664, m = 8: 8.8 us with 260 against 7.1 without a split)
+            if (stiles * S < g_stream_min_blocks && S * 2 <= 32 && cgroups / (S * 2) >= 2 && stiles * S * 2 <= 256)
                 S *= 2;
             // A split_k that is no power of two fills the machine where the powers of two leave it
             // under-filled or spill over it: the largest one with at most 256 workgroups, if that
             // gives 200 or more and runs of four groups or more (n = 5120, k = 13824: 12 slices, 240
             // workgroups, 11.6 us against 12.8 with 8 slices).
             const int s_fill = 256 / stiles < 32 ? 256 / stiles : 32;
-            const bool fill = s_fill >= 3 && (s_fill & (s_fill - 1)) != 0 && stiles * s_fill >= 200 &&
+            const bool fill = s_fill >= 3 && (s_fill & (s_fill - 1)) != 0 && stiles * s_fill >= 192 &&
                               (stiles * S < 224 || stiles * S > 256) && cgroups / s_fill >= 4;
             if (fill) S = s_fill;
             // Where that count sits badly on 256 compute units (under 200 or over 256), 128-192
@@ -1418,6 +1422,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             // badly on 256 compute units, one group per wave does better; and where that is not
             // to be had and there are more workgroups than fit at once, shorter runs (four groups
             // or more) even out the load.
+            // a split of any value where the powers of two leave the machine under-filled (the
+            // fixed-point adds and the zeroing protocol take any split_k up to 64): n = 2232,
+            // k = 14592, m = 4: six slices, 210 workgroups, 6.95 us against 8.0 with four
+            if (group_size >= 128 && parts >= 4 && tiles * (parts / 4) < 192) {
+                const int s_any = 256 / tiles < 64 ? 256 / tiles : 64;
+                if (s_any > parts / 4 && tiles * s_any >= 192 && s_any * 8 <= cgroups) parts = 4 * s_any;
+            }
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
             if (group_size < 128) {
                 // as chosen above
