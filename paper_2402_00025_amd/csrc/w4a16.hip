@@ -1263,8 +1263,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // A random-shape audit added: also up to k = 1536 when the data-parallel tiling gives 130-256
     // workgroups, up to k = 2176 from 130 tiles of 64 columns on (n = 8848, k = 1792, m = 16:
     // 5.6 us against 7.5 with two slices); with five rows or more (where a
-    // split costs the zeroing protocol) up to k = 3072 at 190-256 tiles, and, up to eight rows,
-    // up to k = 5632 there.
+    // split costs the zeroing protocol) up to k = 3072 at 190-256 tiles, and, up to twelve rows,
+    // up to k = 6400 there.
     int dp_cols = 64;  // the data-parallel kernel's tile width: narrower until 160 workgroups, never past 256
     while (dp_cols > 16 && (n + dp_cols - 1) / dp_cols < g_stream_min_blocks && (n + dp_cols / 2 - 1) / (dp_cols / 2) <= 256)
         dp_cols /= 2;
@@ -1272,7 +1272,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const bool fills_once = tiles64 >= 190 && tiles64 <= 256;
     const bool no_split = cgroups <= 8 || (cgroups <= 12 && dp_tiles >= 130 && dp_tiles <= 256) ||
                           (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
-                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 8 && cgroups <= 44 && fills_once)));
+                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 12 && cgroups <= 50 && fills_once)));
     if (library_choice && group_size >= 128 && no_split) {
         // the launch of the data-parallel kernel
         const int tc = dp_cols;
@@ -1355,8 +1355,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         const bool pw_one_group = m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20);
         // (or stays under 160 while the streaming kernel's slices keep five groups or more)
         const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
-        const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 200 && stiles * S <= 256)) &&
-                                 ((m >= 3 && packed_bytes >= (48ll << 20)) || (packed_bytes > (8ll << 20) && pw_bad));
+        const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256)) &&
+                                 ((m >= 3 && packed_bytes >= (48ll << 20)) ||
+                                  (packed_bytes > (8ll << 20) && pw_bad &&
+                                   (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
         const bool worth = S <= cgroups && ((m >= 5 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
