@@ -32,7 +32,10 @@
  * the functions for other field widths (end of the file) by hand-written words, numpy byte
  * views, exact rationals, closed forms, numpy's matmul and, at 4 bits, the 4-bit functions;
  * the product with a group index per row by the contiguous case, numpy's matmul over a
- * gathered dense weight, invariance under reordering of the rows, and exact rationals.
+ * gathered dense weight, invariance under reordering of the rows, and exact rationals;
+ * the 3-bit functions (last section) by hand-written words with the two values that lie
+ * across words, numpy's unpackbits over a little-endian byte view, bijection, the 4-bit
+ * product on the same field values, numpy's matmul, exact rationals and one-hot rows.
  * Unpinned: agreement with the bit layout of the authors' own kernel and with real GPTQ
  * checkpoints (the paper prints neither).
  */
@@ -414,6 +417,115 @@ int w4a16_oracle_gemm_gidx(const uint16_t* A, const int32_t* qweight, const uint
                 const float wf = (float)(qf - zf) * sf; /* exact */
                 const float af = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
                 sum += (double)af * (double)wf;
+            }
+            Cref[(size_t)i * n + j] = sum;
+            if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(sum);
+        }
+    }
+    return used;
+}
+
+/* ---------------------------------------------------------------- 3-bit fields
+ *
+ * Section 2's remark again, for a width that does not divide 32.  Reading used here (the one
+ * GPTQ checkpoints have): 32 consecutive values form a stream of 96 bits, value u at stream
+ * bits [3u, 3u + 2], low bit first; stream bit b is bit (b % 32) of word (b / 32) of three
+ * consecutive words.  Values 10 and 21 therefore lie across two words.
+ *     qweight int32 [3 k / 32, n]:  word rows 3 t, 3 t + 1, 3 t + 2 of column j are the stream of
+ *                                   k = 32 t .. 32 t + 31 of that column
+ *     qzeros  int32 [k / g, 3 n / 32]: words 3 t, 3 t + 1, 3 t + 2 of a row are the stream of
+ *                                   columns 32 t .. 32 t + 31
+ * W = (q - z) * s as before.  Everything below goes bit by bit through that definition. */
+
+static inline int stream3_bit(const int32_t* words, size_t first_word, size_t word_stride, int b)
+{
+    return (int)(((uint32_t)words[first_word + (size_t)(b / 32) * word_stride] >> (b % 32)) & 1u);
+}
+
+/* value u (0..31) of the 96-bit stream whose three words are first_word + {0, 1, 2} * word_stride */
+static inline int stream3_value(const int32_t* words, size_t first_word, size_t word_stride, int u)
+{
+    int v = 0;
+    for (int t = 0; t < 3; ++t) v |= stream3_bit(words, first_word, word_stride, 3 * u + t) << t;
+    return v;
+}
+
+static inline void stream3_store(int32_t* words, size_t first_word, size_t word_stride, int u, int value)
+{
+    for (int t = 0; t < 3; ++t) {
+        const int b = 3 * u + t;
+        uint32_t w = (uint32_t)words[first_word + (size_t)(b / 32) * word_stride];
+        w &= ~(1u << (b % 32));
+        w |= (uint32_t)((value >> t) & 1) << (b % 32);
+        words[first_word + (size_t)(b / 32) * word_stride] = (int32_t)w;
+    }
+}
+
+void w4a16_oracle_unpack_qweight_3bit(const int32_t* qweight, uint8_t* q, int n, int k)
+{
+    for (int kk = 0; kk < k; ++kk)
+        for (int j = 0; j < n; ++j)
+            q[(size_t)kk * n + j] = (uint8_t)stream3_value(qweight, (size_t)(kk / 32) * 3 * n + j, (size_t)n, kk % 32);
+}
+
+void w4a16_oracle_unpack_qzeros_3bit(const int32_t* qzeros, uint8_t* z, int n, int groups)
+{
+    const size_t row_words = (size_t)n / 32 * 3;
+    for (int gi = 0; gi < groups; ++gi)
+        for (int j = 0; j < n; ++j)
+            z[(size_t)gi * n + j] = (uint8_t)stream3_value(qzeros, (size_t)gi * row_words + (size_t)(j / 32) * 3, 1, j % 32);
+}
+
+void w4a16_oracle_pack_qweight_3bit(const uint8_t* q, int32_t* qweight, int n, int k)
+{
+    memset(qweight, 0, (size_t)k / 32 * 3 * n * sizeof(int32_t));
+    for (int kk = 0; kk < k; ++kk)
+        for (int j = 0; j < n; ++j)
+            stream3_store(qweight, (size_t)(kk / 32) * 3 * n + j, (size_t)n, kk % 32, q[(size_t)kk * n + j] & 7);
+}
+
+void w4a16_oracle_pack_qzeros_3bit(const uint8_t* z, int32_t* qzeros, int n, int groups)
+{
+    const size_t row_words = (size_t)n / 32 * 3;
+    memset(qzeros, 0, (size_t)groups * row_words * sizeof(int32_t));
+    for (int gi = 0; gi < groups; ++gi)
+        for (int j = 0; j < n; ++j)
+            stream3_store(qzeros, (size_t)gi * row_words + (size_t)(j / 32) * 3, 1, j % 32, z[(size_t)gi * n + j] & 7);
+}
+
+/* Cref (fp64 [m, n], required) and C16 (fp16 [m, n], may be NULL) <- A . W, the definition,
+ * summed over k in ascending order in an fp64 accumulator ((q - z) * s is exact in fp32).
+ * Returns the OpenMP threads used or a negative number on bad arguments. */
+int w4a16_oracle_gemm_3bit(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
+                           const int32_t* qzeros, double* Cref, uint16_t* C16,
+                           int m, int n, int k, int group_size, int threads)
+{
+    if (!A || !qweight || !scales || !qzeros || !Cref) return -1;
+    if (m < 1 || n < 32 || n % 32 || group_size < 32 || group_size % 32 || k < group_size || k % group_size) return -2;
+
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+
+    const size_t zero_row_words = (size_t)n / 32 * 3;
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < n; ++j) {
+        for (int i = 0; i < m; ++i) {
+            double sum = 0.0;
+            for (int kk = 0; kk < k; ++kk) {
+                const int group = kk / group_size;
+                const int q3 = stream3_value(qweight, (size_t)(kk / 32) * 3 * n + j, (size_t)n, kk % 32);
+                const int z3 = stream3_value(qzeros, (size_t)group * zero_row_words + (size_t)(j / 32) * 3, 1, j % 32);
+                const float s3 = w4a16_oracle_half_to_float(scales[(size_t)group * n + j]);
+                const float w3 = (float)(q3 - z3) * s3; /* exact */
+                const float a3 = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
+                sum += (double)a3 * (double)w3;
             }
             Cref[(size_t)i * n + j] = sum;
             if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(sum);

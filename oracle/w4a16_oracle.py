@@ -70,6 +70,16 @@ class Oracle:
             fn.restype = ctypes.c_int
         lib.w4a16_oracle_gemm_bits.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 6
         lib.w4a16_oracle_gemm_bits.restype = ctypes.c_int
+        for name in ("unpack_qweight_3bit", "unpack_qzeros_3bit"):
+            fn = getattr(lib, "w4a16_oracle_" + name)
+            fn.argtypes = [_i32p, _u8p, ctypes.c_int, ctypes.c_int]
+            fn.restype = None
+        for name in ("pack_qweight_3bit", "pack_qzeros_3bit"):
+            fn = getattr(lib, "w4a16_oracle_" + name)
+            fn.argtypes = [_u8p, _i32p, ctypes.c_int, ctypes.c_int]
+            fn.restype = None
+        lib.w4a16_oracle_gemm_3bit.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 5
+        lib.w4a16_oracle_gemm_3bit.restype = ctypes.c_int
         lib.w4a16_oracle_gemm_gidx.argtypes = [_u16p, _i32p, _u16p, _i32p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 5
         lib.w4a16_oracle_gemm_gidx.restype = ctypes.c_int
         self.lib = lib
@@ -234,6 +244,70 @@ class Oracle:
         return Cref, C16
 
 
+    # ---- 3-bit fields: 32 values in a 96-bit stream of three consecutive words
+    def unpack_qweight_3bit(self, qweight: np.ndarray) -> np.ndarray:
+        """int32 [3 k / 32, n] -> uint8 [k, n]."""
+        qweight = _c(qweight, np.int32)
+        r, n = qweight.shape
+        if r % 3:
+            raise OracleError("3-bit qweight has a multiple of three word rows")
+        k = r // 3 * 32
+        q = np.empty((k, n), np.uint8)
+        self.lib.w4a16_oracle_unpack_qweight_3bit(_ptr(qweight, ctypes.c_int32), _ptr(q, ctypes.c_uint8), n, k)
+        return q
+
+    def unpack_qzeros_3bit(self, qzeros: np.ndarray) -> np.ndarray:
+        """int32 [groups, 3 n / 32] -> uint8 [groups, n]."""
+        qzeros = _c(qzeros, np.int32)
+        g, c = qzeros.shape
+        if c % 3:
+            raise OracleError("a 3-bit qzeros row has a multiple of three words")
+        n = c // 3 * 32
+        z = np.empty((g, n), np.uint8)
+        self.lib.w4a16_oracle_unpack_qzeros_3bit(_ptr(qzeros, ctypes.c_int32), _ptr(z, ctypes.c_uint8), n, g)
+        return z
+
+    def pack_qweight_3bit(self, q: np.ndarray) -> np.ndarray:
+        q = _c(q, np.uint8)
+        k, n = q.shape
+        assert k % 32 == 0
+        out = np.empty((k // 32 * 3, n), np.int32)
+        self.lib.w4a16_oracle_pack_qweight_3bit(_ptr(q, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, k)
+        return out
+
+    def pack_qzeros_3bit(self, z: np.ndarray) -> np.ndarray:
+        z = _c(z, np.uint8)
+        g, n = z.shape
+        assert n % 32 == 0
+        out = np.empty((g, n // 32 * 3), np.int32)
+        self.lib.w4a16_oracle_pack_qzeros_3bit(_ptr(z, ctypes.c_uint8), _ptr(out, ctypes.c_int32), n, g)
+        return out
+
+    def gemm_3bit(self, A, qweight, scales, qzeros, group_size: int, threads: int = 0):
+        """Cref (float64 [m, n]) and its fp16 rounding for 3-bit fields: the definition, fp64
+        accumulation in ascending k."""
+        A = _c(A, np.float16)
+        qweight = _c(qweight, np.int32)
+        scales = _c(scales, np.float16)
+        qzeros = _c(qzeros, np.int32)
+        m, k = A.shape
+        r, n = qweight.shape
+        if k % 32 or r != k // 32 * 3:
+            raise OracleError("qweight rows must be 3 k / 32")
+        if group_size <= 0 or k % group_size or n % 32 or scales.shape != (k // group_size, n) \
+                or qzeros.shape != (k // group_size, n // 32 * 3):
+            raise OracleError("scales / qzeros shapes do not match k, n, group_size")
+        Cref = np.empty((m, n), np.float64)
+        C16 = np.empty((m, n), np.float16)
+        rc = self.lib.w4a16_oracle_gemm_3bit(
+            _ptr(A.view(np.uint16), ctypes.c_uint16), _ptr(qweight, ctypes.c_int32),
+            _ptr(scales.view(np.uint16), ctypes.c_uint16), _ptr(qzeros, ctypes.c_int32),
+            _ptr(Cref, ctypes.c_double), _ptr(C16.view(np.uint16), ctypes.c_uint16),
+            m, n, k, group_size, threads)
+        if rc < 0:
+            raise OracleError(f"w4a16_oracle_gemm_3bit rejected its arguments (code {rc})")
+        return Cref, C16
+
     # ---- group index per row (GPTQ's activation ordering; outside the paper)
     def gemm_gidx(self, A, qweight, scales, qzeros, g_idx, threads: int = 0):
         """Cref (float64 [m, n]) and its fp16 rounding with W[kk] = (q[kk] - z[g_idx[kk]]) * s[g_idx[kk]]."""
@@ -308,6 +382,10 @@ def dequant(qweight, scales, qzeros, group_size):
 
 def gemm_bits(A, qweight, scales, qzeros, group_size, bits, **kw):
     return default().gemm_bits(A, qweight, scales, qzeros, group_size, bits, **kw)
+
+
+def gemm_3bit(A, qweight, scales, qzeros, group_size, **kw):
+    return default().gemm_3bit(A, qweight, scales, qzeros, group_size, **kw)
 
 
 def gemm(A, qweight, scales, qzeros, group_size, **kw):

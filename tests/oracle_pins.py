@@ -443,6 +443,138 @@ def pin_bits_closed_forms_and_one_hot(o):
     assert np.array_equal(C16.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16))
 
 
+# --------------------------------------------------------------------------- 3-bit fields
+def np_unpack_stream3(words3: np.ndarray) -> np.ndarray:
+    """numpy restatement: [..., 3] words of a 96-bit stream -> [..., 32] values, through a
+    little-endian byte view and unpackbits (bit b of the stream is bit b % 8 of byte b // 8)."""
+    w = np.ascontiguousarray(words3).astype("<u4")
+    by = w.view(np.uint8).reshape(*w.shape[:-1], 12)
+    bit = np.unpackbits(by, axis=-1, bitorder="little").reshape(*w.shape[:-1], 32, 3)
+    return (bit[..., 0] + 2 * bit[..., 1] + 4 * bit[..., 2]).astype(np.uint8)
+
+
+def np_unpack_rows_3bit(qweight: np.ndarray) -> np.ndarray:
+    r, n = qweight.shape
+    w3 = qweight.view(np.uint32).reshape(r // 3, 3, n).transpose(0, 2, 1)        # [k/32, n, 3]
+    return np.ascontiguousarray(np_unpack_stream3(w3).transpose(0, 2, 1)).reshape(r // 3 * 32, n)
+
+
+def np_unpack_cols_3bit(qzeros: np.ndarray) -> np.ndarray:
+    g, c = qzeros.shape
+    return np_unpack_stream3(qzeros.view(np.uint32).reshape(g, c // 3, 3)).reshape(g, c // 3 * 32)
+
+
+def random_case_3bit(m, n, k, g, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    qw = rng.integers(0, 1 << 32, size=(k // 32 * 3, n), dtype=np.uint32).view(np.int32)
+    s = rng.uniform(0.001, 0.01, size=(k // g, n)).astype(np.float16)
+    qz = rng.integers(0, 1 << 32, size=(k // g, n // 32 * 3), dtype=np.uint32).view(np.int32)
+    return A, qw, s, qz
+
+
+def np_dense_weight_3bit(qweight, scales, qzeros, group_size) -> np.ndarray:
+    q = np_unpack_rows_3bit(qweight).astype(np.int64)
+    z = np.repeat(np_unpack_cols_3bit(qzeros).astype(np.int64), group_size, axis=0)
+    s = np.repeat(scales.astype(np.float64), group_size, axis=0)
+    return (q - z) * s
+
+
+def pin_3bit_known_words(o):
+    """Hand-written streams.  Octal digits are 3-bit values: the 96-bit number whose octal
+    digits, from the least significant, are the 32 values, cut into three 32-bit words."""
+    vals = [(5 * u + 3) % 8 for u in range(32)]
+    big = sum(v << (3 * u) for u, v in enumerate(vals))
+    words = np.array([(big >> (32 * t)) & 0xFFFFFFFF for t in range(3)], dtype=np.uint32).view(np.int32)
+    col = np.zeros((3, 32), np.int32)
+    col[:, 7] = words
+    q = o.unpack_qweight_3bit(col)
+    assert q[:, 7].tolist() == vals and not q[:, :7].any() and not q[:, 8:].any()
+    z = o.unpack_qzeros_3bit(words.reshape(1, 3))
+    assert z[0].tolist() == vals
+    # the two values that lie across words, alone: value 10 = bits 30, 31 of word 0 and bit 0 of
+    # word 1; value 21 = bit 31 of word 1 and bits 0, 1 of word 2
+    one = np.zeros((32, 32), np.uint8)
+    one[10, 0] = 7
+    one[21, 1] = 5
+    one[31, 2] = 6
+    w = o.pack_qweight_3bit(one).view(np.uint32)
+    assert w[:, 0].tolist() == [0xC0000000, 0x00000001, 0]
+    assert w[:, 1].tolist() == [0, 0x80000000, 0x00000002]
+    assert w[:, 2].tolist() == [0, 0, 0xC0000000]
+    zrow = np.zeros((1, 64), np.uint8)
+    zrow[0, 32 + 10] = 3
+    zrow[0, 32 + 21] = 6
+    wz = o.pack_qzeros_3bit(zrow).view(np.uint32)
+    assert wz[0].tolist() == [0, 0, 0, 0xC0000000, 0x00000000, 0x00000003]
+
+
+def pin_3bit_unpack_library_and_bijection(o):
+    rng = np.random.Generator(np.random.Philox(41))
+    words = rng.integers(0, 1 << 32, size=(9, 64), dtype=np.uint32).view(np.int32)
+    q = o.unpack_qweight_3bit(words)
+    assert q.shape == (96, 64) and int(q.max()) == 7
+    assert np.array_equal(q, np_unpack_rows_3bit(words))
+    assert np.array_equal(o.pack_qweight_3bit(q), words)
+    zw = rng.integers(0, 1 << 32, size=(5, 6), dtype=np.uint32).view(np.int32)
+    z = o.unpack_qzeros_3bit(zw)
+    assert z.shape == (5, 64)
+    assert np.array_equal(z, np_unpack_cols_3bit(zw))
+    assert np.array_equal(o.pack_qzeros_3bit(z), zw)
+    fields = rng.integers(0, 8, size=(64, 32), dtype=np.uint8)
+    assert np.array_equal(o.unpack_qweight_3bit(o.pack_qweight_3bit(fields)), fields)
+    assert np.array_equal(o.unpack_qzeros_3bit(o.pack_qzeros_3bit(fields)), fields)
+
+
+def pin_3bit_is_the_4bit_product_on_the_same_fields(o):
+    """Fields 0..7 packed at 3 bits and at 4 bits give the same product, bit for bit (same sum order)."""
+    m, n, k, g = 4, 64, 256, 64
+    rng = np.random.Generator(np.random.Philox(43))
+    A = rng.standard_normal((m, k), dtype=np.float32).astype(np.float16)
+    q = rng.integers(0, 8, size=(k, n), dtype=np.uint8)
+    z = rng.integers(0, 8, size=(k // g, n), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.01, size=(k // g, n)).astype(np.float16)
+    C3, C316 = o.gemm_3bit(A, o.pack_qweight_3bit(q), s, o.pack_qzeros_3bit(z), g)
+    C4, C416 = o.gemm(A, o.pack_qweight(q), s, o.pack_qzeros(z), g)
+    assert np.array_equal(C3, C4)
+    assert np.array_equal(C316.view(np.uint16), C416.view(np.uint16))
+
+
+def pin_3bit_matmul_library(o):
+    for (m, n, k, g, seed) in ((5, 96, 512, 128, 1), (16, 64, 256, 64, 2), (1, 160, 384, 128, 4), (3, 32, 96, 32, 5)):
+        A, qw, s, qz = random_case_3bit(m, n, k, g, seed)
+        W = np_dense_weight_3bit(qw, s, qz, g)
+        ref = A.astype(np.float64) @ W
+        absdot = np.abs(A.astype(np.float64)) @ np.abs(W)
+        C64, C16 = o.gemm_3bit(A, qw, s, qz, g)
+        assert np.all(np.abs(C64 - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+        assert np.array_equal(C16.view(np.uint16), C64.astype(np.float16).view(np.uint16))
+
+
+def pin_3bit_tiny_vs_fractions_and_one_hot(o):
+    """Exact rationals on a tiny case with two groups; one-hot rows pick rows of W exactly,
+    among them k = 10, 21 (across words) and the rows next to a stream boundary."""
+    m, n, k, g = 2, 32, 64, 32
+    A, qw, s, qz = random_case_3bit(m, n, k, g, seed=47)
+    q = np_unpack_rows_3bit(qw)
+    z = np_unpack_cols_3bit(qz)
+    Cref, _ = o.gemm_3bit(A, qw, s, qz, g)
+    for i in range(m):
+        for j in range(0, n, 3):
+            ex = sum(Fraction(float(A[i, kk])) * (int(q[kk, j]) - int(z[kk // g, j])) * Fraction(float(s[kk // g, j]))
+                     for kk in range(k))
+            assert abs(Fraction(float(Cref[i, j])) - ex) <= abs(ex) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 60)
+    _, qw, s, qz = random_case_3bit(8, 96, 256, 128, seed=53)
+    W = np_dense_weight_3bit(qw, s, qz, 128)
+    rows = [0, 10, 21, 31, 32, 127, 128, 255]
+    A1 = np.zeros((8, 256), np.float16)
+    for i, r in enumerate(rows):
+        A1[i, r] = 1.0
+    Cref, C16 = o.gemm_3bit(A1, qw, s, qz, 128)
+    assert np.array_equal(Cref, W[rows, :])
+    assert np.array_equal(C16.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16))
+
+
 # --------------------------------------------------------------------------- group index per row
 def random_act_order(k, g, seed):
     """A group map as GPTQ's activation ordering makes it: a random order of the rows, cut into
@@ -533,6 +665,11 @@ ALL_PINS = [
     pin_bits_matmul_library,
     pin_bits_tiny_vs_fractions,
     pin_bits_closed_forms_and_one_hot,
+    pin_3bit_known_words,
+    pin_3bit_unpack_library_and_bijection,
+    pin_3bit_is_the_4bit_product_on_the_same_fields,
+    pin_3bit_matmul_library,
+    pin_3bit_tiny_vs_fractions_and_one_hot,
     pin_gidx_contiguous_is_plain,
     pin_gidx_matmul_library,
     pin_gidx_row_permutation_invariance,

@@ -58,6 +58,17 @@ MUTATIONS = [
      "z[(size_t)gi * n + j] = (uint8_t)field_of_width(qzeros, (size_t)gi * (n / 8) + j / f, j % f, bits);", 0),
     ("bits_pack_field_order", "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * i);",
      "word |= ((uint32_t)q[(size_t)(f * r + i) * n + j] & mask) << (bits * (f - 1 - i));", 0),
+    ("stream3_value_bit_order", "3 * u + t) << t;", "3 * u + t) << (2 - t);", 0),
+    ("stream3_word_of_a_bit", "words[first_word + (size_t)(b / 32) * word_stride] >> (b % 32)) & 1u);",
+     "words[first_word + (size_t)(b / 33) * word_stride] >> (b % 32)) & 1u);", 0),
+    ("stream3_gemm_value_order", "(size_t)n, kk % 32);\n                const int z3", "(size_t)n, 31 - kk % 32);\n                const int z3", 0),
+    ("stream3_gemm_zero_column", "(size_t)(j / 32) * 3, 1, j % 32);\n                const float s3",
+     "(size_t)(j / 32) * 3, 1, (j + 1) % 32);\n                const float s3", 0),
+    ("stream3_zero_point_dropped", "const float w3 = (float)(q3 - z3) * s3;", "const float w3 = (float)(q3) * s3;", 0),
+    ("stream3_group_index", "const int group = kk / group_size;", "const int group = kk / 32 % (k / group_size);", 0),
+    ("stream3_unpack_qzeros_stream_base", "z[(size_t)gi * n + j] = (uint8_t)stream3_value(qzeros, (size_t)gi * row_words + (size_t)(j / 32) * 3, 1, j % 32);",
+     "z[(size_t)gi * n + j] = (uint8_t)stream3_value(qzeros, (size_t)gi * row_words + (size_t)(j / 32) * 3, 1, 31 - j % 32);", 0),
+    ("stream3_pack_clears_wrong_bit", "w &= ~(1u << (b % 32));", "w &= ~(1u << (t % 32));", 0),
     ("gidx_ignored", "const int row_group = g_idx[kk];", "const int row_group = kk / (k / groups);", 0),
     ("gidx_scale_from_row_position", "const float sf = w4a16_oracle_half_to_float(scales[(size_t)row_group * n + j]);",
      "const float sf = w4a16_oracle_half_to_float(scales[(size_t)(kk / (k / groups)) * n + j]);", 0),
