@@ -122,8 +122,8 @@ def make_call(w: Workload, kind: str, split_k=0, tile_cols=0, waves=0, reduce=0)
             if rc:
                 raise binding.W4A16Error(rc, "w4a16_gemm_ex")
     elif kind in ("splitk_bits", "dp_bits"):
-        gemm = {2: L.w2a16_gemm, 8: L.w8a16_gemm}[w.bits]
-        gemm_dp = {2: L.w2a16_gemm_dp, 8: L.w8a16_gemm_dp}[w.bits]
+        gemm = {2: L.w2a16_gemm, 3: L.w3a16_gemm, 8: L.w8a16_gemm}[w.bits]
+        gemm_dp = {2: L.w2a16_gemm_dp, 3: L.w3a16_gemm_dp, 8: L.w8a16_gemm_dp}[w.bits]
 
         def call(i):
             qw, s, qz = ptrs[i % nsets]
@@ -428,9 +428,9 @@ def main():
                 f"{2.0 * mm * 8192 * 8192 / e / 1e12:.0f} TFLOP/s")
         del wb
         extra["row_tiles_nk8192"] = rows
-        # 8-bit and 2-bit fields through the same kernels (twice / half the weight bytes per call)
+        # 8-bit, 3-bit and 2-bit fields through the same kernels (2, 3/4 and 1/2 of the weight bytes per call)
         rows = []
-        for bits in (8, 2):
+        for bits in (8, 3, 2):
             for nk in (4096, 8192):
                 wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk * bits // 8))), seed=args.seed, bits=bits)
                 for mm in (1, 16):

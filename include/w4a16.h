@@ -129,6 +129,21 @@ int w2a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size);
 
 /*
+ * 3-bit fields (Section 2's remark again; a width that does not divide 32).  32 consecutive
+ * values form a stream of 96 bits, value u at stream bits [3u, 3u + 2], low bit first; stream bit
+ * b is bit (b % 32) of word (b / 32) of three consecutive words (the layout of GPTQ's 3-bit
+ * checkpoints), so values 10 and 21 of a stream lie across two words:
+ *     qweight  int32  [3 k / 32, n]      word rows 3t, 3t+1, 3t+2 of column j: q[32t .. 32t+31][j], 0..7
+ *     qzeros   int32  [k / g, 3 n / 32]  words 3t, 3t+1, 3t+2 of row gi: z[gi][32t .. 32t+31]
+ * n must be a multiple of 32 (W4A16_ERR_SHAPE otherwise).  Otherwise as w8a16_gemm.
+ */
+int w3a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+               int m, int n, int k, int group_size, int split_k, void* stream);
+int w3a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                  int m, int n, int k, int group_size, void* stream);
+long long w3a16_algorithmic_bytes(int m, int n, int k, int group_size);
+
+/*
  * Activation ordering (GPTQ's act-order; outside the paper, whose groups are contiguous runs of
  * k): the group of row kk is g_idx[kk] instead of kk / g, W[kk, j] = (q[kk, j] - z[g_idx[kk], j])
  * * s[g_idx[kk], j], where g_idx (device, int32 [k]) gives every group exactly g rows.

@@ -25,7 +25,7 @@ EXPORTS = (
     "w4a16_check",
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
-    "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
+    "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w3a16_gemm", "w3a16_gemm_dp", "w3a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
     "w4a16_read_probe",
 )
 
@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
     L.w2a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
     L.w2a16_algorithmic_bytes.argtypes = [ci] * 4
     L.w2a16_algorithmic_bytes.restype = ctypes.c_longlong
+    L.w3a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
+    L.w3a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
+    L.w3a16_algorithmic_bytes.argtypes = [ci] * 4
+    L.w3a16_algorithmic_bytes.restype = ctypes.c_longlong
     L.w4a16_gemm_ex.argtypes = [vp] * 5 + [ci] * 8 + [vp]
     L.w4a16_gemm_dp_ex.argtypes = [vp] * 5 + [ci] * 6 + [vp]
     L.w4a16_plan.argtypes = [ci] * 5 + [ip] * 4
@@ -88,8 +92,8 @@ def lib() -> ctypes.CDLL:
     L.w4a16_phase_timeouts.argtypes = []
     L.w4a16_phase_timeouts.restype = ctypes.c_longlong
     for name in EXPORTS:
-        if name not in ("w4a16_algorithmic_bytes", "w8a16_algorithmic_bytes", "w2a16_algorithmic_bytes", "w4a16_strerror",
-                        "w4a16_last_hip_error",
+        if name not in ("w4a16_algorithmic_bytes", "w8a16_algorithmic_bytes", "w2a16_algorithmic_bytes",
+                        "w3a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
                         "w4a16_phase_timeouts"):
             getattr(L, name).restype = ci
     _lib = L
@@ -159,6 +163,20 @@ def w2a16_gemm_dp(A, qweight, scales, qzeros, C, m, n, k, group_size, stream=Non
 
 def w2a16_algorithmic_bytes(m, n, k, group_size) -> int:
     return int(lib().w2a16_algorithmic_bytes(m, n, k, group_size))
+
+
+def w3a16_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k=0, stream=None) -> None:
+    _check(lib().w3a16_gemm(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size, split_k,
+                            _stream(stream)), "w3a16_gemm")
+
+
+def w3a16_gemm_dp(A, qweight, scales, qzeros, C, m, n, k, group_size, stream=None) -> None:
+    _check(lib().w3a16_gemm_dp(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size,
+                               _stream(stream)), "w3a16_gemm_dp")
+
+
+def w3a16_algorithmic_bytes(m, n, k, group_size) -> int:
+    return int(lib().w3a16_algorithmic_bytes(m, n, k, group_size))
 
 
 def w4a16_actorder_prepare(qweight, g_idx, qweight_sorted, perm, status, n, k, group_size, stream=None) -> None:

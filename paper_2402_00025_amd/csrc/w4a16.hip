@@ -152,9 +152,9 @@ constexpr int kPhaseMaxSplit = 64;          // largest split_k of the phase prot
 constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers: n <= 65536
 
 // GC: 1 = every wave has exactly one compute group, 2 = at least two, 0 = decided at run time.
-// BITS: width of the packed fields, 4 (the paper's), 2 or 8 (Section 2: the method carries over
-// to other n-bit schemes; qweight is then int32 [k / f, n] and qzeros int32 [k / g, n / f] with
-// f = 32 / BITS fields per word).
+// BITS: width of the packed fields, 4 (the paper's), 2, 3 or 8 (Section 2: the method carries
+// over to other n-bit schemes; qweight is then int32 [k BITS / 32, n] and qzeros int32
+// [k / g, n BITS / 32]; 3-bit fields: 32 of them in a stream of three words).
 // NS: strips of 16 V columns per wave.  2 (only with GC = 1): the wave multiplies the same
 // activations with the weights of two adjacent strips, which halves the activation traffic per
 // weight byte and the number of waves.
@@ -162,7 +162,7 @@ template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
     static_assert(NS == 1 || (NS == 2 && GC == 1 && BITS == 4), "two strips per wave: one compute group per wave");
-    static_assert(BITS == 4 || V == 4, "2-bit and 8-bit fields: 64-column tiles");
+    static_assert(BITS == 4 || V == 4, "2-bit, 3-bit and 8-bit fields: 64-column tiles");
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V * NS;
     constexpr bool kService = MODE == kAtomicPkF16Service;
@@ -249,12 +249,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 
     const LaneMap lm = make_lane_map<V, BITS>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)(k / (32 * IPG)) >> p.param_shift;
-    constexpr int kFields = 32 / BITS;  // fields per packed word
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / kFields) * (uint32_t)n * 4u);
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 32 * BITS) * (uint32_t)n * 4u);  // k % 32 == 0
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / kFields) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n * BITS / 32) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;
@@ -1247,7 +1246,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
     const long long packed_bytes = (long long)k * n * bits / 8;
     if (bits != 4) {
-        // 2-bit and 8-bit fields: the per-wave kernel with 64-column tiles only
+        // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles only
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
         tile_cols = 64;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
@@ -1810,6 +1809,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         return W4A16_ERR_UNSUPPORTED;
     if ((unsigned long long)k * (unsigned long long)n * (unsigned)bits / 8 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
     if (bits == 2 && (n % 16) != 0) return W4A16_ERR_SHAPE;  // a zero word holds sixteen columns
+    if (bits == 3 && (n % 32) != 0) return W4A16_ERR_SHAPE;  // three zero words hold thirty-two columns
     // More than 16 rows (beyond the paper's regime): the streaming kernel takes up to 64 rows as
     // row tiles of one launch, so the weights stream once per 64 rows; whatever it does not
     // cover (data-parallel kernel, group sizes below 128, the other tile widths and reductions)
@@ -1897,6 +1897,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     }
     if (bits == 8) return launchn_ipg<8>(a, ipg, plan.waves, lds_bytes, mode, stream);
     if (bits == 2) return launchn_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (bits == 3) return launchn_ipg<3>(a, ipg, plan.waves, lds_bytes, mode, stream);
     if (two_strips) {
         if (ipg != 4 || mode != kAtomicPkF16Phase || a.groups_base != 1 || a.groups_rem != 0 || plan.waves > 4)
             return W4A16_ERR_UNSUPPORTED;
@@ -1973,6 +1974,27 @@ int w2a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
 {
     return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
                            true, stream, 2);
+}
+
+int w3a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+               int k, int group_size, int split_k, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
+                           W4A16_REDUCE_AUTO, true, stream, 3);
+}
+
+int w3a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
+                  int k, int group_size, void* stream)
+{
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, true, 1, 0, 0, W4A16_REDUCE_AUTO,
+                           true, stream, 3);
+}
+
+long long w3a16_algorithmic_bytes(int m, int n, int k, int group_size)
+{
+    if (m < 1 || n < 32 || group_size < 32 || k < group_size) return 0;
+    const long long g = k / group_size;
+    return (long long)k / 32 * 3 * n * 4 + g * n * 2 + g * (n / 32 * 3) * 4 + (long long)m * k * 2 + (long long)m * n * 2;
 }
 
 long long w2a16_algorithmic_bytes(int m, int n, int k, int group_size)

@@ -170,6 +170,49 @@ __device__ __forceinline__ half8_t unpack_shift2(uint32_t word, int half_shift, 
     return __builtin_bit_cast(half8_t, packed);
 }
 
+// 3-bit fields: 32 consecutive k of a column are a stream of 96 bits in three consecutive word
+// rows, value u at stream bits [3u, 3u + 2].  A lane's eight k are 24 consecutive stream bits that
+// start at a multiple of 24: inside one word or across two (`lo`, `hi`), brought down to bits
+// 0..23 by one funnel shift.  y keeps f0..f3 in its low half and f4..f7 in its high half at bits
+// 0, 3, 6, 9; fields at bits 0, 3, 6 lie inside the mantissa of fp16 1024.0, and f3 / f7 come from
+// y >> 6: a mask-or gives 1024 + q, 1024 + 8 q or 1024 + 64 q, and a packed add or fma (by 1/8 or
+// 1/64) leaves q - z exactly, in the slot order of unpack_shift.
+struct ZeroConst3 {
+    uint32_t c0;  // two copies of fp16 -(1024 + z)
+    uint32_t c3;  // two copies of fp16 -(128 + z)
+    uint32_t c6;  // two copies of fp16 -(16 + z)
+};
+
+__device__ __forceinline__ ZeroConst3 zero_const3(uint32_t z)
+{
+    ZeroConst3 c;
+    const uint32_t zz = z | (z << 16);
+    c.c0 = 0xE400E400u | zz;         // ulp 1
+    c.c3 = 0xD800D800u | (zz << 3);  // ulp 1/8
+    c.c6 = 0xCC00CC00u | (zz << 6);  // ulp 1/64
+    return c;
+}
+
+__device__ __forceinline__ half8_t unpack_shift3(uint32_t lo, uint32_t hi, int funnel, ZeroConst3 c, uint32_t magic)
+{
+    const half2_t k8 = {(_Float16)0.125f, (_Float16)0.125f};
+    const half2_t k64 = {(_Float16)0.015625f, (_Float16)0.015625f};
+    const uint32_t x = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)funnel);  // bits 0..23: f0..f7
+    const uint32_t y = (x & 0x00000FFFu) | ((x << 4) & 0x0FFF0000u);
+    const uint32_t y6 = y >> 6;
+    const uint32_t t0 = (y & 0x00070007u) | magic;   // 1024 + {f0, f4}
+    const uint32_t t1 = (y & 0x00380038u) | magic;   // 1024 + 8 {f1, f5}
+    const uint32_t t2 = (y & 0x01C001C0u) | magic;   // 1024 + 64 {f2, f6}
+    const uint32_t t3 = (y6 & 0x00380038u) | magic;  // 1024 + 8 {f3, f7}
+    const half2_t h0 = __builtin_bit_cast(half2_t, t0) + __builtin_bit_cast(half2_t, c.c0);
+    const half2_t h1 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t1), k8, __builtin_bit_cast(half2_t, c.c3));
+    const half2_t h2 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t2), k64, __builtin_bit_cast(half2_t, c.c6));
+    const half2_t h3 = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, t3), k8, __builtin_bit_cast(half2_t, c.c3));
+    u32x4_t packed = {__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                      __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
+    return __builtin_bit_cast(half8_t, packed);
+}
+
 // Eight consecutive activations {a0..a7} (four registers, two per register) reordered to the
 // slot order of unpack_shift: {a0,a4}, {a1,a5}, {a2,a6}, {a3,a7}.
 __device__ __forceinline__ half8_t permute_activations(u32x4_t d)
@@ -268,11 +311,23 @@ struct StepRegs<V, 8> {
     Words<V> w, w1;
     u32x4_t a;
 };
-
-// Per-group parameters of a lane: one qzeros word and V scales.
+// BITS = 3: the one or two word rows (of the step's three) that hold the lane's 24 stream bits
 template <int V>
+struct StepRegs<V, 3> {
+    Words<V> w, w1;
+    u32x4_t a;
+};
+
+// Per-group parameters of a lane: one qzeros word (3-bit fields: two, the lane's 3 V bits may lie
+// across them) and V scales.
+template <int V, int BITS = 4>
 struct ParamRegs {
     uint32_t zword;
+    ScaleBits<V> s;
+};
+template <int V>
+struct ParamRegs<V, 3> {
+    uint32_t zword, zword1;
     ScaleBits<V> s;
 };
 
@@ -282,11 +337,14 @@ struct ParamRegs {
 // in both cases what it computes lands in accumulator entries that are never stored.
 struct LaneMap {
     uint32_t off_w;   // ((lane / 16) * n + col0) * 4       into qweight (8-bit fields: twice the row)
+    uint32_t off_w1;  // 3-bit fields only: the word row that holds the upper part of the lane's 24 bits
     uint32_t off_z;   // (col0 / 8) * 4                     into a qzeros row
+    uint32_t off_z1;  // 3-bit fields only: the next word when the lane's 3 V bits go across, else off_z
     uint32_t off_s;   // col0 * 2                           into a scales row
     uint32_t off_a;   // (row * k + 8 * (lane / 16)) * 2    into A, row = min(lane % 16, m - 1)
     int zshift;       // 4 * (col0 % 8)
-    int half_shift;   // 2-bit fields only: which half of the word the lane's eight k are (0 or 16)
+    int half_shift;   // 2-bit fields: which half of the word the lane's eight k are (0 or 16);
+                      // 3-bit fields: the funnel shift that brings the lane's 24 bits down (0, 24, 16, 8)
 };
 
 // Scalar view of the problem.  A "compute group" is 32 * IPG consecutive k; a quantisation
@@ -309,17 +367,23 @@ __device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& 
     } else if constexpr (BITS == 2) {
         // two word rows per step, each shared by two lane groups
         r.w.load(t.qweight, lm.off_w, step * 8u * (uint32_t)t.n);
+    } else if constexpr (BITS == 3) {
+        // three word rows per step
+        r.w.load(t.qweight, lm.off_w, step * 12u * (uint32_t)t.n);
+        r.w1.load(t.qweight, lm.off_w1, step * 12u * (uint32_t)t.n);
     } else {
         r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
     }
 }
 
 template <int V, int BITS = 4>
-__device__ __forceinline__ void issue_params(ParamRegs<V>& r, const LaneMap& lm, const Tensors& t, int gi)
+__device__ __forceinline__ void issue_params(ParamRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, int gi)
 {
     const uint32_t gp = (uint32_t)gi >> t.param_shift;
-    // a qzeros row is n / (fields per word) words
-    r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, gp * (uint32_t)(t.n / (32 / BITS)) * 4u, 0);
+    // a qzeros row is n * BITS / 32 words
+    const uint32_t zrow = gp * (uint32_t)(t.n * BITS / 32) * 4u;
+    r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, zrow, 0);
+    if constexpr (BITS == 3) r.zword1 = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z1, zrow, 0);
     r.s.load(t.scales, lm.off_s, gp * (uint32_t)t.n * 2u);
 }
 
@@ -327,7 +391,7 @@ __device__ __forceinline__ void issue_params(ParamRegs<V>& r, const LaneMap& lm,
 template <int V, int IPG, int BITS = 4>
 struct Ring {
     StepRegs<V, BITS> step[2][IPG];
-    ParamRegs<V> par[2];
+    ParamRegs<V, BITS> par[2];
 };
 
 template <int V, int IPG, int H, int BITS = 4>
@@ -357,11 +421,16 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG, BITS>& ring, const La
     ZeroConst zc[V];
     ZeroConst8 zc8[V];
     ZeroConst2 zc2[V];
+    ZeroConst3 zc3[V];
     float sc[V];
+    uint32_t zbits3 = 0;
+    if constexpr (BITS == 3)
+        zbits3 = __builtin_amdgcn_alignbit(ring.par[H].zword1, ring.par[H].zword, (uint32_t)lm.zshift);
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         if constexpr (BITS == 8) zc8[j] = zero_const8((ring.par[H].zword >> (lm.zshift + 8 * j)) & 0xFFu);
         else if constexpr (BITS == 2) zc2[j] = zero_const2((ring.par[H].zword >> (lm.zshift + 2 * j)) & 0x3u);
+        else if constexpr (BITS == 3) zc3[j] = zero_const3((zbits3 >> (3 * j)) & 0x7u);
         else zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
         sc[j] = scale_of<V>(ring.par[H].s, j);
     }
@@ -388,6 +457,11 @@ __device__ __forceinline__ void compute_group(Ring<V, IPG, BITS>& ring, const La
             a8 = __builtin_bit_cast(half8_t, ring.step[H][it].a);
 #pragma unroll
             for (int j = 0; j < V; ++j) b8[j] = unpack_shift2(ring.step[H][it].w.v[j], lm.half_shift, zc2[j], magic);
+        } else if constexpr (BITS == 3) {
+            a8 = permute_activations(ring.step[H][it].a);
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                b8[j] = unpack_shift3(ring.step[H][it].w.v[j], ring.step[H][it].w1.v[j], lm.half_shift, zc3[j], magic);
         } else {
             a8 = permute_activations(ring.step[H][it].a);
 #pragma unroll
@@ -473,6 +547,8 @@ __device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n,
 {
     LaneMap lm;
     lm.half_shift = 0;
+    lm.off_w1 = 0;
+    lm.off_z1 = 0;
     const int col0 = n0 + V * (lane & 15);
     const int colc = col0 < n ? col0 : 0;  // an overhanging lane reads the first columns (n >= 8 >= V)
     if constexpr (BITS == 8) {
@@ -487,6 +563,19 @@ __device__ __forceinline__ LaneMap make_lane_map(int lane, int n0, int m, int n,
         lm.off_z = (uint32_t)(colc >> 4) * 4u;
         lm.zshift = 2 * (colc & 15);
         lm.half_shift = 16 * ((lane >> 4) & 1);
+    } else if constexpr (BITS == 3) {
+        // lane group kg takes stream bits [24 kg, 24 kg + 24) of the step's 96: word rows
+        // {0, 0}, {0, 1}, {1, 2}, {2, 2} and funnel shifts 0, 24, 16, 8; thirty-two columns per
+        // three zero words
+        const int kg = lane >> 4;
+        const int row_lo = kg == 0 ? 0 : kg - 1, row_hi = kg == 3 ? 2 : kg;
+        lm.off_w = ((uint32_t)row_lo * (uint32_t)n + (uint32_t)colc) * 4u;
+        lm.off_w1 = ((uint32_t)row_hi * (uint32_t)n + (uint32_t)colc) * 4u;
+        lm.half_shift = (32 - 8 * kg) & 31;
+        lm.off_z = (uint32_t)((3 * colc) >> 5) * 4u;
+        lm.zshift = (3 * colc) & 31;
+        // V divides 32, so the lane's columns stay inside one stream of three words
+        lm.off_z1 = lm.off_z + (lm.zshift + 3 * V > 32 ? 4u : 0u);
     } else {
         lm.off_w = ((uint32_t)(lane >> 4) * (uint32_t)n + (uint32_t)colc) * 4u;
         lm.off_z = (uint32_t)(colc >> 3) * 4u;

@@ -77,11 +77,13 @@ def random_words(rng: np.random.Generator, shape) -> np.ndarray:
 
 def make_weights(rng: np.random.Generator, n: int, k: int, group_size: int, bits: int = 4):
     """One (qweight, scales, qzeros) set drawn from `rng`, in that order.  `bits` is the field
-    width (32 // bits fields per word): uniform words are uniform independent fields at any width."""
-    fields = 32 // bits
-    qweight = random_words(rng, (k // fields, n))
+    width (k * bits / 32 word rows, n * bits / 32 zero words per group; 3-bit fields come 32 to
+    three words): uniform words are uniform independent fields at any width."""
+    if (k * bits) % 32 or (n * bits) % 32:
+        raise ValueError("k * bits and n * bits must be multiples of 32")
+    qweight = random_words(rng, (k * bits // 32, n))
     scales = rng.uniform(SCALE_LO, SCALE_HI, size=(k // group_size, n)).astype(np.float16)
-    qzeros = random_words(rng, (k // group_size, n // fields))
+    qzeros = random_words(rng, (k // group_size, n * bits // 32))
     return qweight, scales, qzeros
 
 
@@ -108,5 +110,4 @@ def make_weight_sets(count: int, n: int, k: int, group_size: int = 128, seed: in
 def algorithmic_bytes(m: int, n: int, k: int, group_size: int = 128, bits: int = 4) -> int:
     """Bytes every call must move at least once: packed weights + scales + zeros + A + C."""
     g = k // group_size
-    fields = 32 // bits
-    return (k // fields) * n * 4 + g * n * 2 + g * (n // fields) * 4 + m * k * 2 + m * n * 2
+    return (k * bits // 32) * n * 4 + g * n * 2 + g * (n * bits // 32) * 4 + m * k * 2 + m * n * 2

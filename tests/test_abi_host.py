@@ -15,7 +15,7 @@ HEADER = (ROOT / "include" / "w4a16.h").read_text()
 
 def declared_functions():
     body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
-    return sorted(set(re.findall(r"\b(w[248]a16_[a-z_0-9]+)\s*\(", body)))
+    return sorted(set(re.findall(r"\b(w[2348]a16_[a-z_0-9]+)\s*\(", body)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -86,6 +86,10 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w8a16_gemm_dp(p, p, p, p, odd, 1, 1024, 1024, 128, None) == b.ERR_UNSUPPORTED
     assert L.w2a16_gemm(p, p, p, p, p, 1, 1032, 1024, 128, 4, None) == b.ERR_SHAPE     # n % 16
     assert L.w2a16_gemm_dp(None, p, p, p, p, 1, 1024, 1024, 128, None) == b.ERR_NULL
+    assert L.w3a16_gemm(p, p, p, p, p, 1, 1040, 1024, 128, 4, None) == b.ERR_SHAPE     # n % 32
+    assert L.w3a16_gemm(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
+    assert L.w3a16_gemm(p, p, p, None, p, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
+    assert L.w3a16_gemm_dp(p, p, odd, p, p, 1, 1024, 1024, 128, None) == b.ERR_UNSUPPORTED
     q = ctypes.c_void_p(8192)
     assert L.w4a16_actorder_prepare(p, p, q, p, None, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_actorder_prepare(p, p, q, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
@@ -217,6 +221,12 @@ def test_8bit_algorithmic_bytes():
         expect = k * n // 4 + (k // 128) * n * 2 + (k // 128) * (n // 16) * 4 + m * k * 2 + m * n * 2
         assert b.w2a16_algorithmic_bytes(m, n, k, 128) == expect
         assert inputs.algorithmic_bytes(m, n, k, 128, bits=2) == expect
+    for (m, n, k) in ((1, 1024, 1024), (16, 4096, 4096), (8, 4096, 11008)):
+        expect = k * n * 3 // 8 + (k // 128) * n * 2 + (k // 128) * (n * 3 // 8) + m * k * 2 + m * n * 2
+        assert b.w3a16_algorithmic_bytes(m, n, k, 128) == expect
+        assert inputs.algorithmic_bytes(m, n, k, 128, bits=3) == expect
+    x = inputs.make_inputs(2, 64, 256, 128, seed=5, bits=3)
+    assert x.qweight.shape == (24, 64) and x.qzeros.shape == (2, 6) and x.scales.shape == (2, 64)
     x = inputs.make_inputs(2, 64, 256, 128, seed=5, bits=8)
     assert x.qweight.shape == (64, 64) and x.qzeros.shape == (2, 16) and x.scales.shape == (2, 64)
 

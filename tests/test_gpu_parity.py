@@ -8,7 +8,8 @@ import numpy as np
 import pytest
 
 from gpu_util import DeviceProblem, assert_parity, dev
-from oracle_pins import np_dense_weight, np_dense_weight_bits, random_act_order, random_case, random_case_bits
+from oracle_pins import (np_dense_weight, np_dense_weight_3bit, np_dense_weight_bits, random_act_order, random_case,
+                         random_case_3bit, random_case_bits)
 from paper_2402_00025_amd import binding as b
 from paper_2402_00025_amd.inputs import make_inputs
 
@@ -698,6 +699,71 @@ def test_2bit_one_hot_rows_bit_exact(split_k):
         b.w2a16_gemm(*p.args(), split_k)
         got = p.result()
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+# ------------------------------------------------------------------ 3-bit fields
+THREE_BIT = [
+    # m, n, k, g, split_k   (n a multiple of 32)
+    (1, 224, 512, 128, 1),
+    (16, 224, 1024, 128, 4),
+    (16, 352, 1024, 128, 8),      # one group per part, ragged last tile (352 = 5 * 64 + 32)
+    (5, 96, 1408, 128, 0),        # 11 groups, the library's split
+    (16, 288, 2048, 128, 2),      # eight groups per workgroup: steady loop
+    (3, 160, 1024, 256, 2),       # group_size 256
+    (16, 192, 512, 64, 2),        # group_size 64
+    (9, 192, 256, 32, 4),         # group_size 32: a group is one stream
+    (4, 64, 4096, 128, 0),        # few rows: fixed-point reduction
+    (40, 288, 1024, 128, 4),      # three launches of 16, 16, 8 rows
+    (16, 32, 256, 128, 2),        # half a tile
+]
+
+
+@pytest.mark.parametrize("m,n,k,g,split_k", THREE_BIT)
+def test_3bit_fields(oracle, m, n, k, g, split_k):
+    A, qw, s, qz = random_case_3bit(m, n, k, g, seed=970 + m + n)
+    Cref, _ = oracle.gemm_3bit(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w3a16_gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"3-bit splitk m={m} n={n} k={k} g={g} S={split_k} call {call}")
+    p.C.fill_(float("nan"))
+    b.w3a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"3-bit dp m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("split_k", [1, 4])
+def test_3bit_one_hot_rows_bit_exact(split_k):
+    """One non-zero term per row, swept over all k: pins the position of every value in its stream
+    (the two that lie across words among them), the word rows and funnel shifts of the lane
+    groups, the zero-point streams along n and the scale columns."""
+    m, n, k, g = 16, 224, 1024, 128
+    _, qw, s, qz = random_case_3bit(m, n, k, g, seed=61)
+    W = np_dense_weight_3bit(qw, s, qz, g)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        b.w3a16_gemm(*p.args(), split_k)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
+def test_3bit_full_size(oracle):
+    """The headline shape with 3-bit fields, SplitK (library's split) and data-parallel."""
+    x = make_inputs(16, 4096, 4096, 128, seed=0, bits=3)
+    Cref, _ = oracle.gemm_3bit(x.A, x.qweight, x.scales, x.qzeros, 128)
+    p = DeviceProblem(x.A, x.qweight, x.scales, x.qzeros, 128)
+    b.w3a16_gemm(*p.args(), 0)
+    assert_parity(p.result(), Cref, "3-bit splitk 4096^2")
+    p.C.fill_(float("nan"))
+    b.w3a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, "3-bit dp 4096^2")
 
 
 # ------------------------------------------------------------------ seeded random shapes
