@@ -754,6 +754,34 @@ def test_3bit_one_hot_rows_bit_exact(split_k):
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
 
 
+def _random_shapes_3bit(count, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = []
+    for _ in range(count):
+        g = int(rng.choice([32, 64, 128, 128, 128, 256]))
+        k = g * int(rng.integers(1, 41))
+        n = 32 * int(rng.integers(1, 60))
+        m = int(rng.choice([1, 2, 4, 5, 8, 13, 16, 17, 33]))
+        out.append((m, n, k, g))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k,g", _random_shapes_3bit(16, seed=2025))
+def test_3bit_random_shapes(oracle, m, n, k, g):
+    """The library's own split (uneven k shares among them) and the data-parallel kernel."""
+    A, qw, s, qz = random_case_3bit(m, n, k, g, seed=3000 + m + n + k)
+    Cref, _ = oracle.gemm_3bit(A, qw, s, qz, g)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w3a16_gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"3-bit auto m={m} n={n} k={k} g={g} call {call}")
+    p.C.fill_(float("nan"))
+    b.w3a16_gemm_dp(*p.args())
+    assert_parity(p.result(), Cref, f"3-bit dp m={m} n={n} k={k} g={g}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 def test_3bit_full_size(oracle):
     """The headline shape with 3-bit fields, SplitK (library's split) and data-parallel."""
     x = make_inputs(16, 4096, 4096, 128, seed=0, bits=3)
