@@ -196,6 +196,10 @@ int w4a16_gemm_dp_ex(const void* A, const void* qweight, const void* scales, con
  * `split_k` in: the requested value (0 = choose).
  */
 int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols, int* waves, int* reduce);
+/* The same for w8a16_gemm, w3a16_gemm, w2a16_gemm and their _dp forms (bits = 8, 3, 2; 4 = w4a16_plan):
+ * the values are outputs only, except `split_k` in.  W4A16_ERR_UNSUPPORTED for any other width. */
+int w4a16_plan_bits(int bits, int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols,
+                    int* waves, int* reduce);
 
 /* Argument check alone (host only, no HIP call): what w4a16_gemm would return before launching
  * (equal shares required of a requested split_k). */

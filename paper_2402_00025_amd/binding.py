@@ -21,7 +21,7 @@ REDUCE_ATOMIC_PK_F16_PHASE = 5
 
 #: every symbol include/w4a16.h declares
 EXPORTS = (
-    "w4a16_gemm", "w4a16_gemm_dp", "w4a16_gemm_streamk", "w4a16_gemm_ex", "w4a16_gemm_dp_ex", "w4a16_plan",
+    "w4a16_gemm", "w4a16_gemm_dp", "w4a16_gemm_streamk", "w4a16_gemm_ex", "w4a16_gemm_dp_ex", "w4a16_plan", "w4a16_plan_bits",
     "w4a16_check",
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
     L.w4a16_gemm_ex.argtypes = [vp] * 5 + [ci] * 8 + [vp]
     L.w4a16_gemm_dp_ex.argtypes = [vp] * 5 + [ci] * 6 + [vp]
     L.w4a16_plan.argtypes = [ci] * 5 + [ip] * 4
+    L.w4a16_plan_bits.argtypes = [ci] * 6 + [ip] * 4
     L.w4a16_check.argtypes = [ci] * 5
     L.w4a16_unpack.argtypes = [vp] * 4 + [ci] * 3 + [vp]
     L.w4a16_dequant.argtypes = [vp] * 4 + [ci] * 3 + [vp]
@@ -214,6 +215,13 @@ def w4a16_plan(m, n, k, group_size, dp=False, split_k=0, tile_cols=0, waves=0, r
     s, t, w, r = (ctypes.c_int(v) for v in (split_k, tile_cols, waves, reduce))
     _check(lib().w4a16_plan(m, n, k, group_size, int(bool(dp)), ctypes.byref(s), ctypes.byref(t), ctypes.byref(w),
                             ctypes.byref(r)), "w4a16_plan")
+    return dict(split_k=s.value, tile_cols=t.value, waves=w.value, reduce=r.value)
+
+
+def w4a16_plan_bits(bits, m, n, k, group_size, dp=False, split_k=0) -> dict:
+    s, t, w, r = (ctypes.c_int(v) for v in (split_k, 0, 0, 0))
+    _check(lib().w4a16_plan_bits(bits, m, n, k, group_size, int(bool(dp)), ctypes.byref(s), ctypes.byref(t),
+                                 ctypes.byref(w), ctypes.byref(r)), "w4a16_plan_bits")
     return dict(split_k=s.value, tile_cols=t.value, waves=w.value, reduce=r.value)
 
 

@@ -161,7 +161,7 @@ constexpr uint32_t kPhaseOrigins = 1u << 12;  // tile origins n0 / 16 it covers:
 template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
-    static_assert(NS == 1 || (NS == 2 && GC == 1 && BITS == 4), "two strips per wave: one compute group per wave");
+    static_assert(NS == 1 || (NS == 2 && GC == 1), "two strips per wave: one compute group per wave");
     static_assert(BITS == 4 || V == 4, "2-bit, 3-bit and 8-bit fields: 64-column tiles");
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V * NS;
@@ -303,14 +303,15 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
         issue_params<V, BITS>(ring1.par[0], lm1, tensors, g_begin);
 #pragma unroll
         for (int it = 0; it < IPG; ++it)
-            ring1.step[0][it].w.load(tensors.qweight, lm1.off_w, ((uint32_t)g_begin * IPG + it) * 16u * (uint32_t)n);
+            issue_step_weights<V, BITS>(ring1.step[0][it], lm1, tensors, (uint32_t)g_begin * IPG + it);
 #pragma unroll
         for (int j = 0; j < V; ++j) acc1[j] = float4_t{0.f, 0.f, 0.f, 0.f};
         wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
 #pragma unroll
         for (int it = 0; it < IPG; ++it) ring1.step[0][it].a = ring.step[0][it].a;
         FlagProbe none{nullptr, 0};
-        compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, magic_1024x2(), 0, acc1, none);
+        compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, BITS == 8 ? magic_64x4() : magic_1024x2(), 0,
+                                                     acc1, none);
     } else {
         wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
     }
@@ -1245,11 +1246,14 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
     const long long packed_bytes = (long long)k * n * bits / 8;
+    bool bits_choice = false;
     if (bits != 4) {
-        // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles only
+        // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles, or with two
+        // strips per wave where the rule below finds them
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
-        tile_cols = 64;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
+        bits_choice = !dp && tile_cols == 0 && waves == 0 && split_k == 0;
+        tile_cols = 64;
     }
     // The rules below come from a sweep of 246 shapes (n 2048..28672, k 1024..14336, m 1, 4, 16)
     // over every launch shape the kernels offer; the plan lands within 1 % (geometric mean, 9 %
@@ -1285,15 +1289,23 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Two strips per wave (128-column tiles, one compute group per wave, in-kernel zeroing by the
     // service wavefront): when k is short enough for that (k / 128 = 4 split_k with split_k up
     // to 16, i.e. k <= 8192), there is more than one row, at least 160 workgroups, and less
-    // than 32 MiB of packed weights (25 MiB beyond split_k = 8).  0-7 % faster than the
+    // than 32 MiB of packed 4-bit weights (25 MiB beyond split_k = 8).  The other field widths go
+    // by the number of weights too (what counts is the number of waves and of loads in flight),
+    // with their own bounds from a sweep of 11 shapes at m = 2..16: 2-bit fields as 4-bit ones but
+    // 24 MiB beyond split_k = 8 (n = k = 7168 loses 5 %), 3-bit and 8-bit fields, which issue two
+    // loads per step, 20 MiB (n = 11008 or 12288 with k = 4096 lose 3-9 %, n = k = 8192 8-30 %);
+    // inside the bounds two strips gain 5-30 % over the single-strip launch.  0-7 % faster than the
     // single-strip launch with fixed-point adds at m = 2..4, 1-4 % at m = 8..16, and up to 19 %
     // faster than the streaming kernel on matrices of 16-25 MiB.
     // (not where the 64-column tiles alone give 200-256 workgroups: one workgroup per tile over
     // all of k, stored without atomics, is 4-7 % faster there)
-    if (library_choice && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
+    const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20))
+                                      : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
+                                                  : (20ll << 20);
+    if ((library_choice || bits_choice) && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
         phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
-        packed_bytes < (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20)) && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
+        (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
         out->split_k = cgroups / 4;
         out->tile_cols = 128;
         out->waves = 4;
@@ -1397,7 +1409,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     }
     // 128 columns: two 64-column strips per wave, one compute group per wave, in-kernel zeroing
     const bool two_strips = tile_cols == 128;
-    if (two_strips && (dp || bits != 4 || group_size < 128)) return W4A16_ERR_UNSUPPORTED;
+    if (two_strips && (dp || group_size < 128)) return W4A16_ERR_UNSUPPORTED;
     if (tile_cols != 16 && tile_cols != 32 && tile_cols != 64 && !two_strips) return W4A16_ERR_UNSUPPORTED;
     const int tiles = (n + tile_cols - 1) / tile_cols;
     if (dp) {
@@ -1895,14 +1907,19 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
             if (!W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
         }
     }
-    if (bits == 8) return launchn_ipg<8>(a, ipg, plan.waves, lds_bytes, mode, stream);
-    if (bits == 2) return launchn_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
-    if (bits == 3) return launchn_ipg<3>(a, ipg, plan.waves, lds_bytes, mode, stream);
     if (two_strips) {
         if (ipg != 4 || mode != kAtomicPkF16Phase || a.groups_base != 1 || a.groups_rem != 0 || plan.waves > 4)
             return W4A16_ERR_UNSUPPORTED;
-        return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 4, 2>(a, plan.waves, lds_bytes, stream);
+        switch (bits) {
+        case 8: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 8, 2>(a, plan.waves, lds_bytes, stream);
+        case 3: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 3, 2>(a, plan.waves, lds_bytes, stream);
+        case 2: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 2, 2>(a, plan.waves, lds_bytes, stream);
+        default: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 4, 2>(a, plan.waves, lds_bytes, stream);
+        }
     }
+    if (bits == 8) return launchn_ipg<8>(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (bits == 2) return launchn_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
+    if (bits == 3) return launchn_ipg<3>(a, ipg, plan.waves, lds_bytes, mode, stream);
     switch (V) {
     case 1: return launch_ipg<1>(a, ipg, plan.waves, lds_bytes, mode, stream);
     case 2: return launch_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);
@@ -2019,7 +2036,9 @@ int w4a16_actorder_prepare(const void* qweight, const void* g_idx, void* qweight
     if (rc != W4A16_OK) return rc;
     if (qweight == qweight_sorted) return W4A16_ERR_UNSUPPORTED;  // not in place
     hipStream_t st = (hipStream_t)stream;
-    if (!w4a16::W4A16_HIP(hipMemsetAsync(status, 0, sizeof(int32_t), st))) return W4A16_ERR_HIP;
+    // a fill kernel rather than an asynchronous memset, so that the call can be captured into a graph
+    hipLaunchKernelGGL(w4a16::fill_zero_kernel, dim3(1), dim3(64), 0, st, (uint32_t*)status, (size_t)1);
+    if (!w4a16::W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
     hipLaunchKernelGGL(w4a16::actorder_perm_kernel, dim3((unsigned)(k / group_size)), dim3(256), 0, st,
                        (const int32_t*)g_idx, (int32_t*)perm, (int32_t*)status, k, group_size);
     if (!w4a16::W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
@@ -2074,6 +2093,26 @@ int w4a16_plan(int m, int n, int k, int group_size, int dp, int* split_k, int* t
                          : 16;
     rc = w4a16::make_plan(m < rows ? m : rows, n, k, group_size, dp != 0, req, tile_cols ? *tile_cols : 0,
                           waves ? *waves : 0, reduce ? *reduce : 0, &plan);
+    if (rc != W4A16_OK) return rc;
+    if (split_k) *split_k = plan.split_k;
+    if (tile_cols) *tile_cols = plan.tile_cols;
+    if (waves) *waves = plan.waves;
+    if (reduce) *reduce = plan.reduce;
+    return W4A16_OK;
+}
+
+int w4a16_plan_bits(int bits, int m, int n, int k, int group_size, int dp, int* split_k, int* tile_cols, int* waves,
+                    int* reduce)
+{
+    if (bits == 4) return w4a16_plan(m, n, k, group_size, dp, split_k, tile_cols, waves, reduce);
+    if (bits != 2 && bits != 3 && bits != 8) return W4A16_ERR_UNSUPPORTED;
+    const int req = split_k ? *split_k : 0;
+    int rc = w4a16::check_args(m, n, k, group_size, dp ? 1 : req, true);
+    if (rc != W4A16_OK) return rc;
+    if ((bits == 2 && n % 16 != 0) || (bits == 3 && n % 32 != 0)) return W4A16_ERR_SHAPE;
+    w4a16::Plan plan;
+    // more than 16 rows: the plan of each launch of 16
+    rc = w4a16::make_plan(m < 16 ? m : 16, n, k, group_size, dp != 0, dp ? 1 : req, 0, 0, W4A16_REDUCE_AUTO, &plan, bits);
     if (rc != W4A16_OK) return rc;
     if (split_k) *split_k = plan.split_k;
     if (tile_cols) *tile_cols = plan.tile_cols;

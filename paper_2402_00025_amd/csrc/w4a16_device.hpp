@@ -355,11 +355,10 @@ struct Tensors {
     int param_shift;
 };
 
-template <int V, int IPG, int BITS = 4>
-__device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, int gi, int it)
+// The weight words of MFMA step `step` along k (k = 32 * step) of a lane.
+template <int V, int BITS = 4>
+__device__ __forceinline__ void issue_step_weights(StepRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, uint32_t step)
 {
-    const uint32_t step = (uint32_t)gi * IPG + it;  // MFMA step index along k: k = 32 * step
-    r.a = __builtin_amdgcn_raw_buffer_load_b128(t.A, lm.off_a, step * 64u, 0);
     if constexpr (BITS == 8) {
         // eight word rows per step
         r.w.load(t.qweight, lm.off_w, step * 32u * (uint32_t)t.n);
@@ -374,6 +373,14 @@ __device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& 
     } else {
         r.w.load(t.qweight, lm.off_w, step * 16u * (uint32_t)t.n);
     }
+}
+
+template <int V, int IPG, int BITS = 4>
+__device__ __forceinline__ void issue_step(StepRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, int gi, int it)
+{
+    const uint32_t step = (uint32_t)gi * IPG + it;  // MFMA step index along k: k = 32 * step
+    r.a = __builtin_amdgcn_raw_buffer_load_b128(t.A, lm.off_a, step * 64u, 0);
+    issue_step_weights<V, BITS>(r, lm, t, step);
 }
 
 template <int V, int BITS = 4>

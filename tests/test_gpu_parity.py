@@ -794,6 +794,61 @@ def test_3bit_full_size(oracle):
     assert_parity(p.result(), Cref, "3-bit dp 4096^2")
 
 
+# ------------------------------------------------------------------ two strips per wave, other field widths
+@pytest.mark.parametrize("bits", [8, 3, 2])
+@pytest.mark.parametrize("m,n,k,g", [
+    (16, 5152, 2048, 128),     # 41 tiles of 128 columns (the last one a quarter full), split_k 4
+    (3, 2592, 4096, 128),      # few rows, split_k 8, last tile a quarter full
+    (9, 5120, 2048, 256),      # group_size 256: two compute groups per parameter row
+])
+def test_two_strips_other_field_widths(oracle, bits, m, n, k, g):
+    """The library's own launch for these shapes is the two-strip kernel (128-column tiles, one
+    compute group per wave, zeroing by the service wavefront) at every field width."""
+    plan = b.w4a16_plan_bits(bits, m, n, k, g)
+    assert plan["tile_cols"] == 128 and plan["split_k"] * 4 == k // 128, plan
+    if bits == 3:
+        A, qw, s, qz = random_case_3bit(m, n, k, g, seed=4000 + m)
+        Cref, _ = oracle.gemm_3bit(A, qw, s, qz, g)
+        gemm = b.w3a16_gemm
+    else:
+        A, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=4000 + m)
+        Cref, _ = oracle.gemm_bits(A, qw, s, qz, g, bits)
+        gemm = b.w8a16_gemm if bits == 8 else b.w2a16_gemm
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(3):
+        p.C.fill_(float("nan"))
+        gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"{bits}-bit two strips m={m} n={n} k={k} g={g} call {call}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("bits", [8, 3, 2])
+def test_two_strips_other_field_widths_one_hot_bit_exact(bits):
+    """One non-zero term per row over all k on a two-strip launch: both strips of every wave pick
+    the right fields, zero points and scales."""
+    m, n, k, g = 16, 5152, 2048, 128
+    assert b.w4a16_plan_bits(bits, m, n, k, g)["tile_cols"] == 128
+    if bits == 3:
+        _, qw, s, qz = random_case_3bit(m, n, k, g, seed=67)
+        W = np_dense_weight_3bit(qw, s, qz, g)
+        gemm = b.w3a16_gemm
+    else:
+        _, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=67)
+        W = np_dense_weight_bits(qw, s, qz, g, bits)
+        gemm = b.w8a16_gemm if bits == 8 else b.w2a16_gemm
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, m):
+        rows = [(base + 7 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        gemm(*p.args(), 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 # ------------------------------------------------------------------ seeded random shapes
 def _random_shapes(count, seed):
     rng = np.random.Generator(np.random.Philox(seed))
