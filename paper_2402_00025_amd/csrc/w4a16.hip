@@ -611,7 +611,8 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
 //                         the steady loop, when a load issued after the count has been consumed,
 //                         samples the flag before the last groups and does not join the last
 //                         barrier, behind which all waves add into C, before it has seen it.
-template <int D, int MODE, int MT>
+// BITS: width of the packed fields, as in gemm_body.
+template <int D, int MODE, int MT, int BITS = 4>
 __device__ __forceinline__ void stream_body(const StreamArgs& p)
 {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
@@ -641,13 +642,13 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     const float last_keep = G == G_real ? 1.f : 0.f;
     const int n0 = (tile * kStreamStrips + strip) * 64;
 
-    const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
+    const LaneMap lm = make_lane_map<4, BITS>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)(k / 128) >> p.param_shift;
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 8) * (uint32_t)n * 4u);
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 32 * BITS) * (uint32_t)n * 4u);
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / 8) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n * BITS / 32) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;
@@ -684,7 +685,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    WeightRing<D> ring;
+    WeightRing<D, BITS> ring;
     ring_prime<D, 0>(ring, lm, tensors, g_begin);
 
     // ---- phase protocol, first part (wave 0), behind the prologue's loads: zeros of slice 0 (the
@@ -713,7 +714,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
 
 #pragma unroll
     for (int rt = 0; rt < MT; ++rt)
-        *(half8_t*)(sl.ring + rt * kChunkBytes + sl.wslot) = permute_activations(a_in[0][rt]);
+        *(half8_t*)(sl.ring + rt * kChunkBytes + sl.wslot) = order_activations<BITS>(a_in[0][rt]);
     __syncthreads();
     u32x4_t a[MT][4];
 #pragma unroll
@@ -726,7 +727,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     for (int rt = 0; rt < MT; ++rt)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[rt][j] = float4_t{0.f, 0.f, 0.f, 0.f};
-    const uint32_t magic = magic_1024x2();
+    const uint32_t magic = unpack_magic<BITS>();
 
     uint32_t now = 0, sample = 0;
     bool published = !(kPhase && wave == 0);
@@ -839,7 +840,7 @@ struct StreamRest {
     int probe_delay;
 };
 
-template <int D, int MODE, int MT>
+template <int D, int MODE, int MT, int BITS = 4>
 __global__ void __launch_bounds__(kWave * (MT > 1 ? 4 : 8))
 gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
                    _Float16* C, int packed, int n, int k, int split_rem, const StreamRest rest)
@@ -864,7 +865,7 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.errors = rest.errors;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
-    stream_body<D, MODE, MT>(p);
+    stream_body<D, MODE, MT, BITS>(p);
 }
 
 // StreamK decomposition (the paper's Conclusion names it as the successor of SplitK to explore):
@@ -1246,6 +1247,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
     const long long packed_bytes = (long long)k * n * bits / 8;
+    const long long weights_half = (long long)k * n / 2;  // the packed bytes of 4-bit fields: size rules count weights
     bool bits_choice = false;
     if (bits != 4) {
         // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles, or with two
@@ -1315,9 +1317,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
     // tile_cols = 256, or chosen when the activation operand is large (m >= 5) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
-    if (!dp && bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) {
+    if (!dp && ((bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) || bits_choice)) {
         // more than 16 rows come here only when the streaming kernel can take them
-        const bool asked = tile_cols == kStreamTileCols || m > 16;
+        const bool asked = bits == 4 && (tile_cols == kStreamTileCols || m > 16);
         const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
         const bool shape_ok = group_size == 128 || group_size == 256;
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
@@ -1363,16 +1365,21 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                tiles64 * (pw_parts / 2) <= 256)
             pw_parts *= 2;
         const int pw_blocks = tiles64 * (pw_parts >= 4 ? pw_parts / 4 : 1);
-        const bool pw_one_group = m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20);
+        const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (128ll << 20);
         // (or stays under 160 while the streaming kernel's slices keep five groups or more)
         const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
         const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256)) &&
-                                 ((m >= 3 && packed_bytes >= (48ll << 20)) ||
-                                  (packed_bytes > (8ll << 20) && pw_bad &&
+                                 ((m >= 3 && weights_half >= (48ll << 20)) ||
+                                  (weights_half > (8ll << 20) && pw_bad &&
                                    (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
-        const bool worth = S <= cgroups && ((m >= 5 && packed_bytes > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
+        // (3-bit fields: a lane fetches two word rows per step of which it needs one and a half, so
+        // the address path is the bound sooner: the streaming kernel gains 4-10 % only from nine
+        // rows on, on 32 Mi x 2 weights or more with k >= 8192, and loses 4-14 % elsewhere)
+        const bool width_ok = bits != 3 || (m >= 9 && weights_half >= (32ll << 20) && cgroups >= 64);
+        const bool worth = S <= cgroups && width_ok &&
+                           ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
             waves = stream_waves;
@@ -1646,10 +1653,10 @@ static int launchn_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, 
 }
 
 // ---- launch of the streaming SplitK kernel
-template <int D, int MODE, int MT>
+template <int D, int MODE, int MT, int BITS = 4>
 static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = gemm_stream_kernel<D, MODE, MT>;
+    auto kern = gemm_stream_kernel<D, MODE, MT, BITS>;
     if (lds_bytes > 64 * 1024) {
         if (!W4A16_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes)))
@@ -1672,20 +1679,20 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
-template <int D, int MT>
+template <int D, int MT, int BITS = 4>
 static int launch_stream_mode(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
-    if (mode == kDirect) return launch_stream_one<D, kDirect, MT>(a, lds_bytes, stream);
-    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, MT>(a, lds_bytes, stream);
-    return launch_stream_one<D, kAtomicPkF16Phase, MT>(a, lds_bytes, stream);
+    if (mode == kDirect) return launch_stream_one<D, kDirect, MT, BITS>(a, lds_bytes, stream);
+    if (mode == kAtomicPkF16) return launch_stream_one<D, kAtomicPkF16, MT, BITS>(a, lds_bytes, stream);
+    return launch_stream_one<D, kAtomicPkF16Phase, MT, BITS>(a, lds_bytes, stream);
 }
 
-template <int MT>
+template <int MT, int BITS = 4>
 static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, hipStream_t stream)
 {
     // ring depth: two groups in flight per wave when every k part has at least two
-    if (a.groups_base >= 2 && g_stream_depth >= 2) return launch_stream_mode<2, MT>(a, lds_bytes, mode, stream);
-    return launch_stream_mode<1, MT>(a, lds_bytes, mode, stream);
+    if (a.groups_base >= 2 && g_stream_depth >= 2) return launch_stream_mode<2, MT, BITS>(a, lds_bytes, mode, stream);
+    return launch_stream_mode<1, MT, BITS>(a, lds_bytes, mode, stream);
 }
 
 static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
@@ -1695,9 +1702,10 @@ static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixe
 // tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
 // m <= 64; more than 16 rows need waves = 4.
 static int run_stream(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
-                      int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream)
+                      int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream, int bits = 4)
 {
     if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
+    if (bits != 4 && m > 16) return W4A16_ERR_UNSUPPORTED;  // the other field widths: one row tile
     if (waves == 0) waves = kStreamStrips;
     if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
     const int wk = waves / kStreamStrips;
@@ -1752,6 +1760,9 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
             mode = kAtomicPkF16;
         }
     }
+    if (bits == 8) return launch_stream_tiles<1, 8>(a, lds_bytes, mode, stream);
+    if (bits == 3) return launch_stream_tiles<1, 3>(a, lds_bytes, mode, stream);
+    if (bits == 2) return launch_stream_tiles<1, 2>(a, lds_bytes, mode, stream);
     switch (mt) {
     case 1: return launch_stream_tiles<1>(a, lds_bytes, mode, stream);
     case 2: return launch_stream_tiles<2>(a, lds_bytes, mode, stream);
@@ -1843,7 +1854,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (plan.tile_cols == kStreamTileCols) {
         if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
         return run_stream(A, qweight, scales, qzeros, C, m, n, k, group_size, plan.split_k, plan.waves, plan.reduce,
-                          (hipStream_t)stream_v);
+                          (hipStream_t)stream_v, bits);
     }
 
     hipStream_t stream = (hipStream_t)stream_v;

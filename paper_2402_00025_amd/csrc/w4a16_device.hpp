@@ -394,6 +394,54 @@ __device__ __forceinline__ void issue_params(ParamRegs<V, BITS>& r, const LaneMa
     r.s.load(t.scales, lm.off_s, gp * (uint32_t)t.n * 2u);
 }
 
+// The unpack stage as functions of the field width, for kernels that keep rings of their own:
+// the zero-point constant of the lane's column j, the B operand of that column for one step,
+// the constant register the unpack needs, and the activations in the order of the fields.
+template <int BITS> struct ZeroOf { using type = ZeroConst; };
+template <> struct ZeroOf<8> { using type = ZeroConst8; };
+template <> struct ZeroOf<3> { using type = ZeroConst3; };
+template <> struct ZeroOf<2> { using type = ZeroConst2; };
+
+template <int V, int BITS>
+__device__ __forceinline__ typename ZeroOf<BITS>::type zero_of_column(const ParamRegs<V, BITS>& par, const LaneMap& lm, int j)
+{
+    if constexpr (BITS == 8) {
+        return zero_const8((par.zword >> (lm.zshift + 8 * j)) & 0xFFu);
+    } else if constexpr (BITS == 2) {
+        return zero_const2((par.zword >> (lm.zshift + 2 * j)) & 0x3u);
+    } else if constexpr (BITS == 3) {
+        const uint32_t zbits = __builtin_amdgcn_alignbit(par.zword1, par.zword, (uint32_t)lm.zshift);
+        return zero_const3((zbits >> (3 * j)) & 0x7u);
+    } else {
+        return zero_const((par.zword >> (lm.zshift + 4 * j)) & 0xFu);
+    }
+}
+
+template <int V, int BITS>
+__device__ __forceinline__ half8_t unpack_column(const StepRegs<V, BITS>& r, int j, const LaneMap& lm,
+                                                 typename ZeroOf<BITS>::type zc, uint32_t magic)
+{
+    if constexpr (BITS == 8) return unpack_shift8(r.w.v[j], r.w1.v[j], zc, magic);
+    else if constexpr (BITS == 2) return unpack_shift2(r.w.v[j], lm.half_shift, zc, magic);
+    else if constexpr (BITS == 3) return unpack_shift3(r.w.v[j], r.w1.v[j], lm.half_shift, zc, magic);
+    else return unpack_shift(r.w.v[j], zc, magic);
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t unpack_magic()
+{
+    if constexpr (BITS == 8) return magic_64x4();
+    else return magic_1024x2();
+}
+
+// 4-bit and 3-bit fields come out in the slot order of unpack_shift, 8-bit and 2-bit ones in the order of k
+template <int BITS>
+__device__ __forceinline__ half8_t order_activations(u32x4_t d)
+{
+    if constexpr (BITS == 4 || BITS == 3) return permute_activations(d);
+    else return __builtin_bit_cast(half8_t, d);
+}
+
 // Ring of two compute groups: half h holds the IPG steps and the parameters of one group.
 template <int V, int IPG, int BITS = 4>
 struct Ring {

@@ -61,27 +61,28 @@ constexpr int kStreamMaxRowTiles = 4;      // row tiles of 16 activation rows pe
 // row and kc = 0..15; a reading wave has one kc and rows 0..15.
 __device__ __forceinline__ int chunk_slot_bytes(int kc, int row) { return (kc * 16 + (row ^ kc)) * 16; }
 
-template <int D>
+// BITS: width of the packed fields (4, or 8, 3, 2 as in the per-wave kernel); the activation
+// slot of a step's registers is not used here (the activations come from LDS).
+template <int D, int BITS = 4>
 struct WeightRing {
-    Words<4> w[D][4];
-    ParamRegs<4> par[D];
+    StepRegs<4, BITS> w[D][4];
+    ParamRegs<4, BITS> par[D];
 };
 
-template <int D, int H>
-__device__ __forceinline__ void ring_issue_group(WeightRing<D>& ring, const LaneMap& lm, const Tensors& t, int gi)
+template <int D, int H, int BITS>
+__device__ __forceinline__ void ring_issue_group(WeightRing<D, BITS>& ring, const LaneMap& lm, const Tensors& t, int gi)
 {
-    issue_params<4>(ring.par[H], lm, t, gi);
+    issue_params<4, BITS>(ring.par[H], lm, t, gi);
 #pragma unroll
-    for (int it = 0; it < 4; ++it)
-        ring.w[H][it].load(t.qweight, lm.off_w, ((uint32_t)gi * 4u + it) * 16u * (uint32_t)t.n);
+    for (int it = 0; it < 4; ++it) issue_step_weights<4, BITS>(ring.w[H][it], lm, t, (uint32_t)gi * 4u + it);
 }
 
-template <int D, int H>
-__device__ __forceinline__ void ring_prime(WeightRing<D>& ring, const LaneMap& lm, const Tensors& t, int g_begin)
+template <int D, int H, int BITS>
+__device__ __forceinline__ void ring_prime(WeightRing<D, BITS>& ring, const LaneMap& lm, const Tensors& t, int g_begin)
 {
     if constexpr (H < D) {
-        ring_issue_group<D, H>(ring, lm, t, g_begin + H);
-        ring_prime<D, H + 1>(ring, lm, t, g_begin);
+        ring_issue_group<D, H, BITS>(ring, lm, t, g_begin + H);
+        ring_prime<D, H + 1, BITS>(ring, lm, t, g_begin);
     }
 }
 
@@ -105,22 +106,22 @@ struct StreamLane {
 // `last_keep` says whether the contribution of a wave's last group (the one without NEXT) counts:
 // 1, or 0 when that group is a phantom that only evens out an odd count (its loads read the
 // next part's data or, behind the end of k, zeros; its product is dropped).
-template <int D, int H, bool REFILL, bool NEXT, int MT>
-__device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
+template <int D, int H, bool REFILL, bool NEXT, int MT, int BITS>
+__device__ __forceinline__ void stream_group(WeightRing<D, BITS>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
                                              const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
                                              uint32_t magic, int cc, int g_begin, float4_t (&acc)[MT][4],
                                              float last_keep)
 {
-    ZeroConst zc[4];
+    typename ZeroOf<BITS>::type zc[4];
     float sc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        zc[j] = zero_const((ring.par[H].zword >> (lm.zshift + 4 * j)) & 0xFu);
+        zc[j] = zero_of_column<4, BITS>(ring.par[H], lm, j);
         sc[j] = scale_of<4>(ring.par[H].s, j);
     }
     if constexpr (REFILL) {
         __builtin_amdgcn_sched_barrier(0);
-        issue_params<4>(ring.par[H], lm, t, g_begin + cc + D);
+        issue_params<4, BITS>(ring.par[H], lm, t, g_begin + cc + D);
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt)
             a_in[H][rt] = __builtin_amdgcn_raw_buffer_load_b128(t.A, sl.a_voff[rt],
@@ -136,10 +137,10 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
     for (int it = 0; it < 4; ++it) {
         half8_t b8[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b8[j] = unpack_shift(ring.w[H][it].v[j], zc[j], magic);
+        for (int j = 0; j < 4; ++j) b8[j] = unpack_column<4, BITS>(ring.w[H][it], j, lm, zc[j], magic);
         if constexpr (REFILL) {
             __builtin_amdgcn_sched_barrier(0);
-            ring.w[H][it].load(t.qweight, lm.off_w, ((uint32_t)(g_begin + cc + D) * 4u + it) * 16u * (uint32_t)t.n);
+            issue_step_weights<4, BITS>(ring.w[H][it], lm, t, (uint32_t)(g_begin + cc + D) * 4u + it);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -168,7 +169,7 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
         char* buf = sl.ring + ((cc + 1) & 1) * (MT * kChunkBytes);
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt)
-            *(half8_t*)(buf + rt * kChunkBytes + sl.wslot) = permute_activations(a_in[(H + 1) % D][rt]);
+            *(half8_t*)(buf + rt * kChunkBytes + sl.wslot) = order_activations<BITS>(a_in[(H + 1) % D][rt]);
         __syncthreads();
 #pragma unroll
         for (int rt = 0; rt < MT; ++rt)
@@ -177,8 +178,8 @@ __device__ __forceinline__ void stream_group(WeightRing<D>& ring, u32x4_t (&a_in
     }
 }
 
-template <int D, int H, bool REFILL, int MT>
-__device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
+template <int D, int H, bool REFILL, int MT, int BITS>
+__device__ __forceinline__ void stream_groups(WeightRing<D, BITS>& ring, u32x4_t (&a_in)[D][MT], u32x4_t (&a)[MT][4],
                                               const StreamLane<MT>& sl, const LaneMap& lm, const Tensors& t,
                                               uint32_t magic, int c0, int g_begin, float4_t (&acc)[MT][4],
                                               float last_keep)
@@ -186,8 +187,8 @@ __device__ __forceinline__ void stream_groups(WeightRing<D>& ring, u32x4_t (&a_i
     if constexpr (H < D) {
         // the last group of the wave has no successor
         constexpr bool kNext = REFILL || (H + 1 < D);
-        stream_group<D, H, REFILL, kNext, MT>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc, last_keep);
-        stream_groups<D, H + 1, REFILL, MT>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc, last_keep);
+        stream_group<D, H, REFILL, kNext, MT, BITS>(ring, a_in, a, sl, lm, t, magic, c0 + H, g_begin, acc, last_keep);
+        stream_groups<D, H + 1, REFILL, MT, BITS>(ring, a_in, a, sl, lm, t, magic, c0, g_begin, acc, last_keep);
     }
 }
 

@@ -216,12 +216,15 @@ def test_plan_of_the_other_field_widths():
     # two strips per wave where the 4-bit rule has them, by the number of weights
     for bits in (8, 3, 2):
         assert b.w4a16_plan_bits(bits, 16, 4096, 4096, 128) == dict(split_k=8, tile_cols=128, waves=4, reduce=5)
-        assert b.w4a16_plan_bits(bits, 16, 8192, 8192, 128)["tile_cols"] == 64
+        assert b.w4a16_plan_bits(bits, 16, 8192, 8192, 128)["tile_cols"] == 256      # streaming kernel
         assert b.w4a16_plan_bits(bits, 1, 4096, 4096, 128)["tile_cols"] == 64        # one row: no two strips
         assert b.w4a16_plan_bits(bits, 16, 4096, 4096, 128, split_k=4)["tile_cols"] == 64   # a requested split
         assert b.w4a16_plan_bits(bits, 16, 4096, 4096, 128, dp=True)["split_k"] == 1
     assert b.w4a16_plan_bits(2, 16, 11008, 4096, 128)["tile_cols"] == 128
     assert b.w4a16_plan_bits(3, 16, 11008, 4096, 128)["tile_cols"] == 64
+    assert b.w4a16_plan_bits(8, 16, 11008, 4096, 128)["tile_cols"] == 256
+    assert b.w4a16_plan_bits(3, 8, 8192, 8192, 128)["tile_cols"] == 64       # 3-bit streaming from nine rows on
+    assert b.w4a16_plan_bits(8, 3, 16384, 16384, 128)["tile_cols"] == 256    # few rows on a large matrix
     assert b.w4a16_plan_bits(4, 16, 4096, 4096, 128) == b.w4a16_plan(16, 4096, 4096, 128)
     L = b.lib()
     assert L.w4a16_plan_bits(5, 16, 4096, 4096, 128, 0, None, None, None, None) == b.ERR_UNSUPPORTED

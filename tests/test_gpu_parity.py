@@ -849,6 +849,66 @@ def test_two_strips_other_field_widths_one_hot_bit_exact(bits):
         assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
 
 
+# ------------------------------------------------------------------ streaming kernel, other field widths
+@pytest.mark.parametrize("bits,m,n,k,g", [
+    (8, 7, 5152, 3328, 128),      # 26 groups over 8 slices: uneven shares, odd counts (phantom group)
+    (2, 7, 5152, 3328, 128),
+    (8, 16, 5152, 3328, 256),     # group_size 256
+    (2, 12, 2592, 16384, 128),    # 23 slices (a split that fills the machine), last tile an eighth full
+    (8, 12, 2592, 16384, 128),
+    (3, 9, 8224, 8320, 128),      # 65 groups over 7 slices
+    (3, 16, 8192, 8192, 128),
+    (8, 16, 8192, 8192, 128),
+    (2, 16, 8192, 8192, 128),
+])
+def test_streaming_kernel_other_field_widths(oracle, bits, m, n, k, g):
+    """The library's own launch for these shapes is the streaming kernel (256-column tiles,
+    activations shared through LDS) at the other field widths."""
+    plan = b.w4a16_plan_bits(bits, m, n, k, g)
+    assert plan["tile_cols"] == 256, plan
+    if bits == 3:
+        A, qw, s, qz = random_case_3bit(m, n, k, g, seed=5000 + m)
+        Cref, _ = oracle.gemm_3bit(A, qw, s, qz, g)
+        gemm = b.w3a16_gemm
+    else:
+        A, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=5000 + m)
+        Cref, _ = oracle.gemm_bits(A, qw, s, qz, g, bits)
+        gemm = b.w8a16_gemm if bits == 8 else b.w2a16_gemm
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(3):
+        p.C.fill_(float("nan"))
+        gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"{bits}-bit streaming m={m} n={n} k={k} g={g} call {call} plan {plan}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("bits,m,n,k", [(8, 7, 5152, 3328), (2, 7, 5152, 3328), (3, 9, 8224, 8320)])
+def test_streaming_kernel_other_field_widths_one_hot_bit_exact(bits, m, n, k):
+    """One non-zero term per row on a streaming launch with uneven shares: sampled k (every
+    position of a 32-value stream and of a group, first and last groups of the slices)."""
+    g = 128
+    assert b.w4a16_plan_bits(bits, m, n, k, g)["tile_cols"] == 256
+    if bits == 3:
+        _, qw, s, qz = random_case_3bit(m, n, k, g, seed=71)
+        W = np_dense_weight_3bit(qw, s, qz, g)
+        gemm = b.w3a16_gemm
+    else:
+        _, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=71)
+        W = np_dense_weight_bits(qw, s, qz, g, bits)
+        gemm = b.w8a16_gemm if bits == 8 else b.w2a16_gemm
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    import torch
+    for base in range(0, k, 97):
+        rows = [(base + 131 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        gemm(*p.args(), 0)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), base
+
+
 # ------------------------------------------------------------------ seeded random shapes
 def _random_shapes(count, seed):
     rng = np.random.Generator(np.random.Philox(seed))
