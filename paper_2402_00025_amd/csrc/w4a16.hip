@@ -1304,7 +1304,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20))
                                       : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
                                                   : (20ll << 20);
-    if ((library_choice || bits_choice) && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
+    // (the other widths: from split_k = 4 on; with 2 or 3 slices of a short k the tiles alone fill
+    // the machine and the unsplit launch is 5-25 % faster, n = 26656, k = 1536 and n = 21952, k = 1024)
+    if ((library_choice || (bits_choice && cgroups / 4 >= 4)) && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
         (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
         phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
         (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
@@ -1374,10 +1376,25 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                    (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
-        // (3-bit fields: a lane fetches two word rows per step of which it needs one and a half, so
-        // the address path is the bound sooner: the streaming kernel gains 4-10 % only from nine
-        // rows on, on 32 Mi x 2 weights or more with k >= 8192, and loses 4-14 % elsewhere)
-        const bool width_ok = bits != 3 || (m >= 9 && weights_half >= (32ll << 20) && cgroups >= 64);
+        // The other field widths, from same-box sweeps against their per-wave launches (11 chosen
+        // and 2 x 36 random shapes at m = 2..16): not where the 4-bit plan does not split (one
+        // workgroup per 64-column tile over all of k fills the machine; n = 15392, k = 2048 at 8
+        // bits: +25 %; n = 13280, k = 3584, m = 16 at 2 bits: +12 %), not below k = 2560 (n = 28768,
+        // k = 1408 at 8 bits: +14-18 %), and from
+        // 12 Mi x 2 weights on (below, many short slices lose 6-15 %).  3-bit fields: a lane fetches two word rows
+        // per step of which it needs one and a half, so the address path binds sooner; the
+        // streaming kernel gains 4-10 % only from nine rows on, on 32 Mi x 2 weights or more with
+        // k >= 8192 and three slices or more, and loses 4-14 % elsewhere.  2-bit fields: not with two slices (+9-20 % at
+        // n >= 23520), and with few rows only below 64 Mi x 2 weights (+4-10 % above).  8-bit fields
+        // with few rows: from 24 Mi x 2 weights on (+4-5 % below).
+        bool width_ok = true;
+        if (bits != 4) {
+            width_ok = !no_split && !(fills_once && cgroups <= 50) && cgroups >= 20 && weights_half > (12ll << 20);
+            if (bits == 3)
+                width_ok = width_ok && m >= 9 && weights_half >= (32ll << 20) && cgroups >= 64 && S >= 3;
+            if (bits == 2) width_ok = width_ok && S >= 3 && (m >= 5 || weights_half < (64ll << 20));
+            if (bits == 8 && m < 5) width_ok = width_ok && weights_half >= (24ll << 20);
+        }
         const bool worth = S <= cgroups && width_ok &&
                            ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {

@@ -851,9 +851,9 @@ def test_two_strips_other_field_widths_one_hot_bit_exact(bits):
 
 # ------------------------------------------------------------------ streaming kernel, other field widths
 @pytest.mark.parametrize("bits,m,n,k,g", [
-    (8, 7, 5152, 3328, 128),      # 26 groups over 8 slices: uneven shares, odd counts (phantom group)
-    (2, 7, 5152, 3328, 128),
-    (8, 16, 5152, 3328, 256),     # group_size 256
+    (8, 7, 5152, 5248, 128),      # 41 groups over 8 slices: uneven shares, odd counts (phantom group)
+    (2, 7, 5152, 5248, 128),
+    (8, 16, 5152, 5376, 256),     # group_size 256
     (2, 12, 2592, 16384, 128),    # 23 slices (a split that fills the machine), last tile an eighth full
     (8, 12, 2592, 16384, 128),
     (3, 9, 8224, 8320, 128),      # 65 groups over 7 slices
@@ -882,7 +882,7 @@ def test_streaming_kernel_other_field_widths(oracle, bits, m, n, k, g):
     assert b.w4a16_phase_timeouts() == 0
 
 
-@pytest.mark.parametrize("bits,m,n,k", [(8, 7, 5152, 3328), (2, 7, 5152, 3328), (3, 9, 8224, 8320)])
+@pytest.mark.parametrize("bits,m,n,k", [(8, 7, 5152, 5248), (2, 7, 5152, 5248), (3, 9, 8224, 8320)])
 def test_streaming_kernel_other_field_widths_one_hot_bit_exact(bits, m, n, k):
     """One non-zero term per row on a streaming launch with uneven shares: sampled k (every
     position of a 32-value stream and of a group, first and last groups of the slices)."""
