@@ -1275,9 +1275,36 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         dp_cols /= 2;
     const int dp_tiles = (n + dp_cols - 1) / dp_cols;
     const bool fills_once = tiles64 >= 190 && tiles64 <= 256;
-    const bool no_split = cgroups <= 8 || (cgroups <= 12 && dp_tiles >= 130 && dp_tiles <= 256) ||
+    // Whether the two-strip launch further down is to be had for this shape (its conditions
+    // other than who is asking).
+    const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20))
+                                      : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
+                                                  : (20ll << 20);
+    const bool two_strip_ok = m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
+                              (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) &&
+                              cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 &&
+                              (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
+                              (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins;
+    // A fourth audit (40 random shapes, then grids around its misses) added two more cases of no
+    // split.  130-256 tiles of 64 columns up to k = 3584: one workgroup per tile over all of k
+    // beats the streaming kernel by 13-35 % (n = 10048 or 11520, k = 2304 or 2816, m = 8, 16) and
+    // is level with or ahead of everything else, except two strips per wave where they are to be
+    // had and the tiles are few (under 170, under 140 up to eight rows: 2-15 % for two strips at
+    // 130 tiles, 2-10 % against them at 180).  And 130-256 tiles of 16 columns (n up to 4096) up
+    // to k = 3328 where two strips are not to be had: eight waves per 16-column tile beat the
+    // split launches by 4-46 % (most at five to twelve rows).
+    const bool short_k_tiles_fill = cgroups <= 28 && tiles64 >= 130 && tiles64 <= 256;
+    const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 140));
+    const bool narrow_tiles_fill = cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
+    // (the first of them up to k = 2176 from two rows on: a grid of n = 4608..8000, k = 1792 and 2176,
+    // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
+    // from k = 2560 on two strips per wave win where they are to be had)
+    const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
                           (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
-                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 12 && cgroups <= 50 && fills_once)));
+                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 12 && cgroups <= 50 && fills_once))) ||
+                          (short_k_tiles_fill && !two_strips_there) || narrow_tiles_fill ||
+                          // (more than 256 tiles up to k = 1664: level or up to 25 % ahead on n = 17280..28672)
+                          (cgroups <= 13 && tiles64 > 256);
     if (library_choice && group_size >= 128 && no_split) {
         // the launch of the data-parallel kernel
         const int tc = dp_cols;
@@ -1301,15 +1328,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // faster than the streaming kernel on matrices of 16-25 MiB.
     // (not where the 64-column tiles alone give 200-256 workgroups: one workgroup per tile over
     // all of k, stored without atomics, is 4-7 % faster there)
-    const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20))
-                                      : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
-                                                  : (20ll << 20);
     // (the other widths: from split_k = 4 on; with 2 or 3 slices of a short k the tiles alone fill
     // the machine and the unsplit launch is 5-25 % faster, n = 26656, k = 1536 and n = 21952, k = 1024)
-    if ((library_choice || (bits_choice && cgroups / 4 >= 4)) && m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
-        (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) && cgroups % 4 == 0 &&
-        phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 && (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
-        (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins) {
+    if ((library_choice || (bits_choice && cgroups / 4 >= 4)) && two_strip_ok) {
         out->split_k = cgroups / 4;
         out->tile_cols = 128;
         out->waves = 4;
@@ -1367,11 +1388,16 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                tiles64 * (pw_parts / 2) <= 256)
             pw_parts *= 2;
         const int pw_blocks = tiles64 * (pw_parts >= 4 ? pw_parts / 4 : 1);
-        const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (128ll << 20);
+        // (one group per wave: below 96 MiB; n = 21192, k = 11264, 113 MiB, m = 1, 2: 7300 workgroups
+        // of it take 28-29 us, 249 of the streaming kernel 23.6)
+        const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (96ll << 20);
         // (or stays under 160 while the streaming kernel's slices keep five groups or more)
         const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
         const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256)) &&
                                  ((m >= 3 && weights_half >= (48ll << 20)) ||
+                                  // (any row count from 40 MiB on when 224-256 workgroups are to be had: 6-13 %
+                                  // ahead of one group per wave on six shapes of 44-73 MiB at m = 1, 2, 4)
+                                  (weights_half >= (40ll << 20) && stream_waves != 2 * kStreamStrips && stiles * S >= 224) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
                                    (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
@@ -1469,7 +1495,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
             if (group_size < 128) {
                 // as chosen above
-            } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (128ll << 20) &&
+            } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (96ll << 20) &&
                        (blocks < 200 || blocks > 256)) {
                 parts = cgroups;
             } else if (blocks > 256) {
