@@ -1348,6 +1348,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
                                reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
         int S = split_k;
+        const int S0 = split_k;  // 0: the split is the library's
         int stream_waves = waves;
         if (S == 0) {
             // about one workgroup per compute unit (160 to 319 of them), at least two groups each
@@ -1377,6 +1378,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                     stream_waves = 2 * kStreamStrips;
                 }
             }
+        }
+        // Eight waves with the split as chosen, where that leaves compute units idle: a grid of 105
+        // launches (43-125 column tiles, 150-256 workgroups, 8-16 groups per k part, m = 1, 6, 16) has
+        // eight waves 7-17 % ahead of four at 156-180 workgroups, 4-13 % at 196-198, 0-7 % at 208,
+        // 4-5 % at 219-220 with twelve groups or more per part (level with eight), and 1-6 % behind
+        // from 240 on.
+        if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && S >= 1 &&
+            cgroups % (2 * S) == 0) {
+            const int part_groups = cgroups / (2 * S);
+            if (part_groups >= 8 && (stiles * S <= 208 || (stiles * S <= 220 && part_groups >= 12)))
+                stream_waves = 2 * kStreamStrips;
         }
         const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
         // Fewer rows: only with a count that sits well, and only on large matrices or where the

@@ -949,7 +949,8 @@ def test_random_shapes_library_plan(oracle, m, n, k, g):
     (8, 16400, 1024, 0, 0, 0),       # two strips, split_k 2, ragged last tile
     (3, 8192, 2048, 0, 0, 0),        # two strips at few rows (in-kernel zeroing instead of fixed-point adds)
     (16, 5632, 8192, 4, 256, 8),     # eight-wave streaming workgroups, two k parts of eight groups
-    (9, 5632, 16384, 0, 0, 0),       # the plan's own eight-wave choice
+    (9, 5632, 16384, 0, 0, 0),       # a split that is no power of two (11 slices)
+    (16, 16896, 9216, 0, 0, 0),      # the plan's own eight-wave choice: three slices, two k parts of twelve groups
     (16, 2304, 4096, 0, 0, 0),       # under-filled launch
 ])
 def test_medium_shapes_plan_variants(oracle, m, n, k, split_k, tile_cols, waves):
