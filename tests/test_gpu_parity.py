@@ -794,6 +794,73 @@ def test_3bit_full_size(oracle):
     assert_parity(p.result(), Cref, "3-bit dp 4096^2")
 
 
+def test_hip_graph_replays_other_field_widths_and_activation_ordering(oracle):
+    """The 8-, 3- and 2-bit entry points (per-wave, two-strip and streaming launches) and the
+    activation-ordering pair (prepare + product) captured in one HIP graph and replayed, with
+    eager calls between the replays."""
+    import torch
+    cases = [
+        # bits, m, n, k
+        (8, 16, 512, 1024), (3, 5, 512, 1024), (2, 3, 512, 2048),      # per-wave
+        (8, 16, 5152, 2048), (3, 9, 5152, 2048), (2, 2, 5152, 2048),   # two strips per wave
+        (8, 7, 5152, 5248), (2, 12, 5152, 5248),                       # streaming kernel, uneven shares
+    ]
+    probs = []
+    for (bits, m, n, k) in cases:
+        if bits == 3:
+            A, qw, s, qz = random_case_3bit(m, n, k, 128, seed=6000 + m + k)
+            Cref, _ = oracle.gemm_3bit(A, qw, s, qz, 128)
+            gemm = b.w3a16_gemm
+        else:
+            A, qw, s, qz = random_case_bits(m, n, k, 128, bits, seed=6000 + m + k)
+            Cref, _ = oracle.gemm_bits(A, qw, s, qz, 128, bits)
+            gemm = b.w8a16_gemm if bits == 8 else b.w2a16_gemm
+        probs.append((DeviceProblem(A, qw, s, qz, 128), Cref, gemm, f"{bits}-bit m={m} n={n} k={k}"))
+    # activation ordering: the group map is sorted and the rows repacked inside the graph as well
+    m, n, k, g = 16, 520, 1024, 128
+    A, qw, s, qz = random_case(m, n, k, g, seed=6100)
+    g_idx = random_act_order(k, g, seed=6101)
+    Cref_ao, _ = oracle.gemm_gidx(A, qw, s, qz, g_idx)
+    pa = DeviceProblem(A, qw, s, qz, g)
+    d_gidx = dev(g_idx)
+    qw_sorted = torch.empty_like(pa.qweight)
+    perm = torch.full((k,), -1, dtype=torch.int32, device="cuda")
+    status = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    A_work = torch.empty_like(pa.A)
+
+    def run_all(stream=None):
+        for (p, _, gemm, _) in probs:
+            gemm(*p.args(), 0, stream=stream)
+        b.w4a16_actorder_prepare(pa.qweight, d_gidx, qw_sorted, perm, status, n, k, g, stream=stream)
+        b.w4a16_gemm_actorder(pa.A, qw_sorted, pa.scales, pa.qzeros, perm, A_work, pa.C, m, n, k, g, 0, stream=stream)
+
+    run_all()                                  # eager warm-up: scratch allocation happens outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_all(stream=torch.cuda.current_stream())
+    for rep in range(3):
+        for (p, *_rest) in probs:
+            p.C.fill_(float("nan"))
+        pa.C.fill_(float("nan"))
+        status.fill_(7)
+        perm.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (p, Cref, _, what) in probs:
+            assert_parity(p.C.cpu().numpy(), Cref, f"replay {rep}: {what}")
+        assert int(status.item()) == 0
+        assert_parity(pa.C.cpu().numpy(), Cref_ao, f"replay {rep}: activation ordering")
+        # eager work between the replays on the same tiles
+        probs[3][2](*probs[3][0].args(), 4)
+        probs[6][2](*probs[6][0].args(), 0)
+        torch.cuda.synchronize()
+    assert b.w4a16_phase_timeouts() == 0
+
+
 # ------------------------------------------------------------------ two strips per wave, other field widths
 @pytest.mark.parametrize("bits", [8, 3, 2])
 @pytest.mark.parametrize("m,n,k,g", [
