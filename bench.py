@@ -431,7 +431,8 @@ def main():
         # 8-bit, 3-bit and 2-bit fields through the same kernels (2, 3/4 and 1/2 of the weight bytes per call)
         rows = []
         for bits in (8, 3, 2):
-            for nk in (4096, 8192):
+            # (8-bit fields also at 16384: 256 MiB of weights, the largest stream any of the kernels sees)
+            for nk in (4096, 8192) + ((16384,) if bits == 8 else ()):
                 wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk * bits // 8))), seed=args.seed, bits=bits)
                 for mm in (1, 16):
                     wm = wb.with_m(mm)
