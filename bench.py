@@ -29,10 +29,11 @@ ROTATE_BYTES = 512 << 20
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 
-def measured_traffic(m, n, k):
+def measured_traffic(m, n, k, bits=4):
     """HBM bytes per launch of the headline kernel from the committed rocprofv3 counter
     summary (profiles/), or None when there is none for this shape."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_splitk_m{m}_n{n}_k{k}.txt")
+    tag = "splitk" if bits == 4 else f"splitk_w{bits}"
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}_m{m}_n{n}_k{k}.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch="):
@@ -272,6 +273,9 @@ def main():
     ap.add_argument("--shape", default="16,4096,4096",
                     help="m,n,k of the timed workload (default: the headline workload; another shape runs "
                          "without the tables, e.g. for a profile of the streaming kernel)")
+    ap.add_argument("--bits", type=int, default=4, choices=(2, 3, 4, 8),
+                    help="field width of the timed workload (default 4, the paper's; another width runs "
+                         "without the tables and without the CPU leg, e.g. for a profile)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 256 MiB device copies (reference traffic for rocprofv3 counter runs)")
     args = ap.parse_args()
@@ -290,28 +294,40 @@ def main():
     dev_name = torch.cuda.get_device_name(0)
     g = 128
     m, n, k = (int(x) for x in args.shape.split(","))
-    if (m, n, k) != (16, 4096, 4096):
+    bits = args.bits
+    if (m, n, k) != (16, 4096, 4096) or bits != 4:
         args.no_sweep = True   # the tables belong to the headline run
+    if bits != 4:
+        args.no_cpu = True     # the CPU leg is the headline's
 
     def nsets(n_, k_):
-        per = n_ * k_ // 2
+        per = n_ * k_ * bits // 8
         return max(2, -(-ROTATE_BYTES // per))
 
     log(f"[bench] device {dev_name}; building workload m={m} n={n} k={k} ({nsets(n, k)} weight sets)")
-    w = Workload(m, n, k, g, nsets(n, k), seed=args.seed)
-    plan = binding.w4a16_plan(m, n, k, g, split_k=args.split_k)
+    w = Workload(m, n, k, g, nsets(n, k), seed=args.seed, bits=bits)
+    plan = (binding.w4a16_plan(m, n, k, g, split_k=args.split_k) if bits == 4
+            else binding.w4a16_plan_bits(bits, m, n, k, g, split_k=args.split_k))
 
     # oracle: reference for the correctness gate and the CPU baseline
     if args.no_cpu:
         from oracle import w4a16_oracle
-        Cref, _ = w4a16_oracle.gemm(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g)
+        if bits == 4:
+            Cref, _ = w4a16_oracle.gemm(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g)
+        elif bits == 3:
+            Cref, _ = w4a16_oracle.gemm_3bit(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g)
+        else:
+            Cref, _ = w4a16_oracle.gemm_bits(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g, bits)
         cpu = None
     else:
         Cref, cpu = cpu_baseline(w)
         log(f"[bench] oracle on {cpu['cores']} host threads: {cpu['ms_per_call']:.1f} ms/call = {cpu['value']:.2f} GB/s")
 
-    head = make_call(w, "splitk", split_k=plan["split_k"], tile_cols=plan["tile_cols"], waves=plan["waves"],
-                     reduce=plan["reduce"])
+    if bits == 4:
+        head = make_call(w, "splitk", split_k=plan["split_k"], tile_cols=plan["tile_cols"], waves=plan["waves"],
+                         reduce=plan["reduce"])
+    else:
+        head = make_call(w, "splitk_bits", split_k=args.split_k)
     ok, rel, emax = verify(w, head, Cref)
     log(f"[bench] parity of the timed configuration: ok={ok} rel_fro={rel:.2e} max_err={emax:.2e}")
     if not ok:
@@ -483,11 +499,11 @@ def main():
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 x int4 -> f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"m={m}, n={n}, k={k}, group_size={g}, split_k={plan['split_k']}, "
+        "dtype": f"f16 x int{bits} -> f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"m={m}, n={n}, k={k}, group_size={g}, {bits}-bit fields, split_k={plan['split_k']}, "
                                f"tile_cols={plan['tile_cols']}, weights rotated over {len(w.sets)} sets (cold HBM)", "seed": args.seed},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k, bits),
                      "kernel": "w4a16::gemm_stream_kernel (SplitK)" if plan["tile_cols"] == 256 else "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
         "cpu_baseline": cpu,
         "extra": extra,
