@@ -294,36 +294,36 @@ def main():
     dev_name = torch.cuda.get_device_name(0)
     g = 128
     m, n, k = (int(x) for x in args.shape.split(","))
-    bits = args.bits
-    if (m, n, k) != (16, 4096, 4096) or bits != 4:
+    width = args.bits   # field width of the timed workload
+    if (m, n, k) != (16, 4096, 4096) or width != 4:
         args.no_sweep = True   # the tables belong to the headline run
-    if bits != 4:
+    if width != 4:
         args.no_cpu = True     # the CPU leg is the headline's
 
     def nsets(n_, k_):
-        per = n_ * k_ * bits // 8
+        per = n_ * k_ * width // 8
         return max(2, -(-ROTATE_BYTES // per))
 
     log(f"[bench] device {dev_name}; building workload m={m} n={n} k={k} ({nsets(n, k)} weight sets)")
-    w = Workload(m, n, k, g, nsets(n, k), seed=args.seed, bits=bits)
-    plan = (binding.w4a16_plan(m, n, k, g, split_k=args.split_k) if bits == 4
-            else binding.w4a16_plan_bits(bits, m, n, k, g, split_k=args.split_k))
+    w = Workload(m, n, k, g, nsets(n, k), seed=args.seed, bits=width)
+    plan = (binding.w4a16_plan(m, n, k, g, split_k=args.split_k) if width == 4
+            else binding.w4a16_plan_bits(width, m, n, k, g, split_k=args.split_k))
 
     # oracle: reference for the correctness gate and the CPU baseline
     if args.no_cpu:
         from oracle import w4a16_oracle
-        if bits == 4:
+        if width == 4:
             Cref, _ = w4a16_oracle.gemm(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g)
-        elif bits == 3:
+        elif width == 3:
             Cref, _ = w4a16_oracle.gemm_3bit(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g)
         else:
-            Cref, _ = w4a16_oracle.gemm_bits(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g, bits)
+            Cref, _ = w4a16_oracle.gemm_bits(w.host.A, w.host.qweight, w.host.scales, w.host.qzeros, g, width)
         cpu = None
     else:
         Cref, cpu = cpu_baseline(w)
         log(f"[bench] oracle on {cpu['cores']} host threads: {cpu['ms_per_call']:.1f} ms/call = {cpu['value']:.2f} GB/s")
 
-    if bits == 4:
+    if width == 4:
         head = make_call(w, "splitk", split_k=plan["split_k"], tile_cols=plan["tile_cols"], waves=plan["waves"],
                          reduce=plan["reduce"])
     else:
@@ -499,11 +499,11 @@ def main():
         "metric": "effective HBM bandwidth of the fused W4A16 SplitK GEMM call (algorithmic bytes / time per call)",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": f"f16 x int{bits} -> f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"m={m}, n={n}, k={k}, group_size={g}, {bits}-bit fields, split_k={plan['split_k']}, "
+        "dtype": f"f16 x int{width} -> f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"m={m}, n={n}, k={k}, group_size={g}, {width}-bit fields, split_k={plan['split_k']}, "
                                f"tile_cols={plan['tile_cols']}, weights rotated over {len(w.sets)} sets (cold HBM)", "seed": args.seed},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k, bits),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k, width),
                      "kernel": "w4a16::gemm_stream_kernel (SplitK)" if plan["tile_cols"] == 256 else "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
         "cpu_baseline": cpu,
         "extra": extra,
