@@ -212,6 +212,39 @@ def test_algorithmic_bytes():
     assert int(gold["splitk_grid"]) == 4 * int(gold["dp_grid"])
 
 
+def test_plan_invariants_of_the_other_field_widths():
+    """The same for the 8-, 3- and 2-bit entry points: 64-column tiles, two strips or the streaming
+    kernel with one row tile, and launches the kernels accept."""
+    ns = (32, 96, 1024, 2304, 4096, 5152, 6144, 9216, 11008, 14336, 22016, 28672)
+    ks = (256, 1024, 1408, 2048, 4096, 5120, 7168, 8192, 11008, 13824, 28672)
+    count = 0
+    for bits in (8, 3, 2):
+        for g in (32, 128, 256):
+            for m in (1, 2, 4, 5, 9, 16, 40):
+                for n in ns:
+                    for k in ks:
+                        if k % g or n * k * bits // 8 >= 1 << 31:
+                            continue
+                        for dp in (False, True):
+                            pl = b.w4a16_plan_bits(bits, m, n, k, g, dp=dp)
+                            S, tc, wv, red = pl["split_k"], pl["tile_cols"], pl["waves"], pl["reduce"]
+                            cg = k // min(g, 128)
+                            assert tc in (64, 128, 256) and 1 <= wv <= 8 and S >= 1, (bits, m, n, k, g, dp, pl)
+                            kparts = wv // 4 if tc == 256 else wv
+                            assert S * kparts <= cg, (bits, m, n, k, g, dp, pl)
+                            if dp:
+                                assert S == 1 and tc == 64
+                                continue
+                            if tc == 128:
+                                assert S * wv == cg and g >= 128 and 4 <= S <= 16 and m >= 2
+                            if tc == 256:
+                                assert g >= 128 and wv in (4, 8) and (wv == 4 or cg % (2 * S) == 0)
+                            if S > 1 and red in (2, 5):
+                                assert S <= 32
+                            count += 1
+    assert count > 4000
+
+
 def test_plan_of_the_other_field_widths():
     # two strips per wave where the 4-bit rule has them, by the number of weights
     for bits in (8, 3, 2):
