@@ -1384,7 +1384,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // eight waves 7-17 % ahead of four at 156-180 workgroups, 4-13 % at 196-198, 0-7 % at 208,
         // 4-5 % at 219-220 with twelve groups or more per part (level with eight), and 1-6 % behind
         // from 240 on.
-        if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && S >= 1 &&
+        // (2-bit and 3-bit fields gain the same way, 7-17 % on eight launches; 8-bit fields, whose waves
+        // have twice the bytes in flight already, lose 2-5 %)
+        if (bits != 8 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && S >= 1 &&
             cgroups % (2 * S) == 0) {
             const int part_groups = cgroups / (2 * S);
             if (part_groups >= 8 && (stiles * S <= 208 || (stiles * S <= 220 && part_groups >= 12)))

@@ -927,12 +927,15 @@ def test_two_strips_other_field_widths_one_hot_bit_exact(bits):
     (3, 16, 8192, 8192, 128),
     (8, 16, 8192, 8192, 128),
     (2, 16, 8192, 8192, 128),
+    (2, 6, 13312, 8192, 128),     # eight waves: two k parts of eight groups in each of four slices
+    (3, 16, 16896, 9216, 128),    # eight waves, three slices
 ])
 def test_streaming_kernel_other_field_widths(oracle, bits, m, n, k, g):
     """The library's own launch for these shapes is the streaming kernel (256-column tiles,
     activations shared through LDS) at the other field widths."""
     plan = b.w4a16_plan_bits(bits, m, n, k, g)
     assert plan["tile_cols"] == 256, plan
+    assert plan["waves"] == (8 if n > 13000 else 4), plan
     if bits == 3:
         A, qw, s, qz = random_case_3bit(m, n, k, g, seed=5000 + m)
         Cref, _ = oracle.gemm_3bit(A, qw, s, qz, g)
