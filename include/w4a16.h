@@ -107,8 +107,10 @@ int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, c
  * fields per word:
  *     qweight  int32  [k / 4, n]         field i (bits 8i..8i+7) of word (r, j) is q[4r + i][j], 0..255
  *     qzeros   int32  [k / g, n / 4]     field i of word (gi, c) is z[gi][4c + i]
- * SplitK and data-parallel kernels with 64-column tiles; more than 16 rows run one launch per
- * 16.  w8a16_algorithmic_bytes: qweight + scales + qzeros + A + C for this layout.
+ * The launch is the library's (per-wave kernel, two strips per wave or streaming kernel for SplitK;
+ * 16- to 64-column tiles for the data-parallel kernel; w4a16_plan_bits reports it); more than 16
+ * rows run one launch per 16.  w8a16_algorithmic_bytes: qweight + scales + qzeros + A + C for
+ * this layout.
  */
 int w8a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                int m, int n, int k, int group_size, int split_k, void* stream);

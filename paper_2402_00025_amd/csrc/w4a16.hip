@@ -162,7 +162,6 @@ template <int V, int IPG, int MODE, int WMAX, int GC, int BITS = 4, int NS = 1>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 {
     static_assert(NS == 1 || (NS == 2 && GC == 1), "two strips per wave: one compute group per wave");
-    static_assert(BITS == 4 || V == 4, "2-bit, 3-bit and 8-bit fields: 64-column tiles");
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     constexpr int BN = 16 * V * NS;
     constexpr bool kService = MODE == kAtomicPkF16Service;
@@ -1255,7 +1254,14 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
         bits_choice = !dp && tile_cols == 0 && waves == 0 && split_k == 0;
+        const bool narrow = dp && tile_cols == 0;
         tile_cols = 64;
+        if (narrow) {
+            // the data-parallel launch narrows its tiles as the 4-bit one does (further down)
+            while (tile_cols > 16 && (n + tile_cols - 1) / tile_cols < g_stream_min_blocks &&
+                   (n + tile_cols / 2 - 1) / (tile_cols / 2) <= 256)
+                tile_cols /= 2;
+        }
     }
     // The rules below come from a sweep of 246 shapes (n 2048..28672, k 1024..14336, m 1, 4, 16)
     // over every launch shape the kernels offer; the plan lands within 1 % (geometric mean, 9 %
@@ -1709,6 +1715,31 @@ static int launchn_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, 
     }
 }
 
+// ---- the other field widths, data-parallel launch with narrow tiles (16 or 32 columns, up to 16 waves)
+template <int V, int BITS>
+static int launchn_direct_narrow(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, hipStream_t stream)
+{
+    if (waves <= 4) {
+        switch (ipg) {
+        case 1: return launch_bound<V, 1, kDirect, 4, 0, BITS>(a, waves, lds_bytes, stream);
+        case 2: return launch_bound<V, 2, kDirect, 4, 0, BITS>(a, waves, lds_bytes, stream);
+        default: return launch_bound<V, 4, kDirect, 4, 0, BITS>(a, waves, lds_bytes, stream);
+        }
+    }
+    switch (ipg) {
+    case 1: return launch_bound<V, 1, kDirect, 16, 0, BITS>(a, waves, lds_bytes, stream);
+    case 2: return launch_bound<V, 2, kDirect, 16, 0, BITS>(a, waves, lds_bytes, stream);
+    default: return launch_bound<V, 4, kDirect, 16, 0, BITS>(a, waves, lds_bytes, stream);
+    }
+}
+
+template <int BITS>
+static int launchn_direct_narrow_v(const GemmArgs& a, int V, int ipg, int waves, size_t lds_bytes, hipStream_t stream)
+{
+    if (V == 1) return launchn_direct_narrow<1, BITS>(a, ipg, waves, lds_bytes, stream);
+    return launchn_direct_narrow<2, BITS>(a, ipg, waves, lds_bytes, stream);
+}
+
 // ---- launch of the streaming SplitK kernel
 template <int D, int MODE, int MT, int BITS = 4>
 static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t stream)
@@ -1984,6 +2015,13 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         case 2: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 2, 2>(a, plan.waves, lds_bytes, stream);
         default: return launch_bound<4, 4, kAtomicPkF16Service, 4, 1, 4, 2>(a, plan.waves, lds_bytes, stream);
         }
+    }
+    if (bits != 4 && V < 4) {
+        // narrow tiles: the data-parallel launch only
+        if (mode != kDirect) return W4A16_ERR_UNSUPPORTED;
+        if (bits == 8) return launchn_direct_narrow_v<8>(a, V, ipg, plan.waves, lds_bytes, stream);
+        if (bits == 3) return launchn_direct_narrow_v<3>(a, V, ipg, plan.waves, lds_bytes, stream);
+        return launchn_direct_narrow_v<2>(a, V, ipg, plan.waves, lds_bytes, stream);
     }
     if (bits == 8) return launchn_ipg<8>(a, ipg, plan.waves, lds_bytes, mode, stream);
     if (bits == 2) return launchn_ipg<2>(a, ipg, plan.waves, lds_bytes, mode, stream);

@@ -229,11 +229,11 @@ def test_plan_invariants_of_the_other_field_widths():
                             pl = b.w4a16_plan_bits(bits, m, n, k, g, dp=dp)
                             S, tc, wv, red = pl["split_k"], pl["tile_cols"], pl["waves"], pl["reduce"]
                             cg = k // min(g, 128)
-                            assert tc in (64, 128, 256) and 1 <= wv <= 8 and S >= 1, (bits, m, n, k, g, dp, pl)
+                            assert tc in (16, 32, 64, 128, 256) and 1 <= wv <= 8 and S >= 1, (bits, m, n, k, g, dp, pl)
                             kparts = wv // 4 if tc == 256 else wv
                             assert S * kparts <= cg, (bits, m, n, k, g, dp, pl)
                             if dp:
-                                assert S == 1 and tc == 64
+                                assert S == 1 and tc in (16, 32, 64) and wv <= 8
                                 continue
                             if tc == 128:
                                 assert S * wv == cg and g >= 128 and 4 <= S <= 16 and m >= 2
