@@ -1301,18 +1301,22 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // split launches by 4-46 % (most at five to twelve rows).
     const bool short_k_tiles_fill = cgroups <= 28 && tiles64 >= 130 && tiles64 <= 256;
     const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 140));
-    const bool narrow_tiles_fill = cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
+    // (4-bit fields only: n = 2880, k = 2944 is 5-7 % slower that way at the other widths)
+    const bool narrow_tiles_fill =
+        bits == 4 && cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
     // (the first of them up to k = 2176 from two rows on: a grid of n = 4608..8000, k = 1792 and 2176,
     // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
     // from k = 2560 on two strips per wave win where they are to be had)
-    const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
+    // (the other field widths: k = 2176 on 249 tiles of 32 columns is 15-42 % slower unsplit at 3 and 8 bits)
+    const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
                           (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
                           (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 12 && cgroups <= 50 && fills_once))) ||
                           (short_k_tiles_fill && !two_strips_there) || narrow_tiles_fill ||
                           // (more than 256 tiles up to k = 1664: level or up to 25 % ahead on n = 17280..28672)
                           (cgroups <= 13 && tiles64 > 256);
-    if (library_choice && group_size >= 128 && no_split) {
-        // the launch of the data-parallel kernel
+    if ((library_choice || bits_choice) && group_size >= 128 && no_split) {
+        // the launch of the data-parallel kernel (the other field widths as well: on 36 random shapes
+        // with k up to 3712 their launches became 3-5 % faster on average, up to 35 % on narrow tiles)
         const int tc = dp_cols;
         const int wv = tc < 64 && m <= 12 ? 8 : 4;
         out->split_k = 1;
