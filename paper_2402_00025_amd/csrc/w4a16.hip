@@ -1249,8 +1249,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const long long weights_half = (long long)k * n / 2;  // the packed bytes of 4-bit fields: size rules count weights
     bool bits_choice = false;
     if (bits != 4) {
-        // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles, or with two
-        // strips per wave where the rule below finds them
+        // 2-bit, 3-bit and 8-bit fields: the per-wave kernel with 64-column tiles, with two strips per
+        // wave or the streaming kernel where the rules below find them, and narrow tiles for the
+        // launches that do not split k
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
         if (m > 16) return W4A16_ERR_UNSUPPORTED;
         bits_choice = !dp && tile_cols == 0 && waves == 0 && split_k == 0;
@@ -1687,7 +1688,7 @@ static int launch_ipg(const GemmArgs& a, int ipg, int waves, size_t lds_bytes, i
     }
 }
 
-// ---- 2-bit and 8-bit fields: 64-column tiles, at most four waves per workgroup
+// ---- 2-bit, 3-bit and 8-bit fields, per-wave kernel with a split: 64-column tiles, at most four waves per workgroup
 template <int IPG, int MODE, int BITS>
 static int launchn_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
