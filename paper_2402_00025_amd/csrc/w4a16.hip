@@ -250,9 +250,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
     const uint32_t qgroups = (uint32_t)(k / (32 * IPG)) >> p.param_shift;
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 32 * BITS) * (uint32_t)n * 4u);  // k % 32 == 0
+    // (k and n times BITS / 32, written per width so that each keeps its shortest form; 3-bit: k, n % 32 == 0)
+    constexpr int kFields = BITS == 3 ? 1 : 32 / BITS;
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(BITS == 3 ? k / 32 * 3 : k / kFields) * (uint32_t)n * 4u);
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n * BITS / 32) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(BITS == 3 ? n / 32 * 3 : n / kFields) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;
@@ -302,15 +304,22 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
         issue_params<V, BITS>(ring1.par[0], lm1, tensors, g_begin);
 #pragma unroll
         for (int it = 0; it < IPG; ++it)
-            issue_step_weights<V, BITS>(ring1.step[0][it], lm1, tensors, (uint32_t)g_begin * IPG + it);
+        {
+            if constexpr (BITS == 4)
+                ring1.step[0][it].w.load(tensors.qweight, lm1.off_w, ((uint32_t)g_begin * IPG + it) * 16u * (uint32_t)n);
+            else
+                issue_step_weights<V, BITS>(ring1.step[0][it], lm1, tensors, (uint32_t)g_begin * IPG + it);
+        }
 #pragma unroll
         for (int j = 0; j < V; ++j) acc1[j] = float4_t{0.f, 0.f, 0.f, 0.f};
         wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
 #pragma unroll
         for (int it = 0; it < IPG; ++it) ring1.step[0][it].a = ring.step[0][it].a;
         FlagProbe none{nullptr, 0};
-        compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, BITS == 8 ? magic_64x4() : magic_1024x2(), 0,
-                                                     acc1, none);
+        if constexpr (BITS == 8)
+            compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, magic_64x4(), 0, acc1, none);
+        else
+            compute_group<V, IPG, 0, false, false, BITS>(ring1, lm1, tensors, magic_1024x2(), 0, acc1, none);
     } else {
         wave_run<V, IPG, MODE == kAtomicPkF16Phase, GC, BITS>(ring, tensors, lm, g_begin, g_count, acc, probe);
     }
@@ -645,9 +654,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     const uint32_t qgroups = (uint32_t)(k / 128) >> p.param_shift;
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 32 * BITS) * (uint32_t)n * 4u);
+    constexpr int kFields = BITS == 3 ? 1 : 32 / BITS;  // sizes written per width, as in gemm_body
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(BITS == 3 ? k / 32 * 3 : k / kFields) * (uint32_t)n * 4u);
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n * BITS / 32) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(BITS == 3 ? n / 32 * 3 : n / kFields) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;

@@ -387,10 +387,14 @@ template <int V, int BITS = 4>
 __device__ __forceinline__ void issue_params(ParamRegs<V, BITS>& r, const LaneMap& lm, const Tensors& t, int gi)
 {
     const uint32_t gp = (uint32_t)gi >> t.param_shift;
-    // a qzeros row is n * BITS / 32 words
-    const uint32_t zrow = gp * (uint32_t)(t.n * BITS / 32) * 4u;
-    r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, zrow, 0);
-    if constexpr (BITS == 3) r.zword1 = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z1, zrow, 0);
+    // a qzeros row is n * BITS / 32 words (written per width so that each keeps its shortest form)
+    if constexpr (BITS == 3) {
+        const uint32_t zrow = gp * (uint32_t)(t.n / 32 * 3) * 4u;
+        r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, zrow, 0);
+        r.zword1 = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z1, zrow, 0);
+    } else {
+        r.zword = __builtin_amdgcn_raw_buffer_load_b32(t.qzeros, lm.off_z, gp * (uint32_t)(t.n / (32 / BITS)) * 4u, 0);
+    }
     r.s.load(t.scales, lm.off_s, gp * (uint32_t)t.n * 2u);
 }
 
