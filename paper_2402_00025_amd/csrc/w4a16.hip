@@ -1306,12 +1306,12 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // split.  130-256 tiles of 64 columns up to k = 3584: one workgroup per tile over all of k
     // beats the streaming kernel by 13-35 % (n = 10048 or 11520, k = 2304 or 2816, m = 8, 16) and
     // is level with or ahead of everything else, except two strips per wave where they are to be
-    // had and the tiles are few (under 170, under 140 up to eight rows: 2-15 % for two strips at
-    // 130 tiles, 2-10 % against them at 180).  And 130-256 tiles of 16 columns (n up to 4096) up
+    // had and the tiles are few (under 170, under 150 up to eight rows: 2-15 % for two strips at
+    // 130 tiles, 7 % at 147 with four rows, 2-10 % against them at 157-180).  And 130-256 tiles of 16 columns (n up to 4096) up
     // to k = 3328 where two strips are not to be had: eight waves per 16-column tile beat the
     // split launches by 4-46 % (most at five to twelve rows).
     const bool short_k_tiles_fill = cgroups <= 28 && tiles64 >= 130 && tiles64 <= 256;
-    const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 140));
+    const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 150));
     // (4-bit fields only: n = 2880, k = 2944 is 5-7 % slower that way at the other widths)
     const bool narrow_tiles_fill =
         bits == 4 && cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
