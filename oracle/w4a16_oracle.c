@@ -22,6 +22,11 @@
  *   - groups are contiguous runs of g rows along k;
  *   - fp32 -> fp16 conversion rounds to nearest, ties to even.
  *
+ * w4a16_oracle_gemm, the function every parity test calls, is the definition one output element
+ * at a time: three nested loops (column, row, k), nothing cached, nothing blocked.
+ * w4a16_oracle_gemm_blocked is the same arithmetic arranged in column blocks for the timed CPU
+ * baseline only, held to the definition bit for bit by a test.
+ *
  * Accumulation modes: 0 = fp64 accumulator (every product a*w is exact in fp64, so this is
  * the definition up to one rounding per addition at 2^-53), 1 = fp32 accumulator with fp32
  * products, the precision Algorithm 1 names.  Summation order is ascending k inside each
@@ -29,6 +34,7 @@
  *
  * Parity status: all functions below are pinned by tests/test_oracle_*.py against closed
  * forms, exact-rational brute force, numpy's float16 and matmul, and pack/unpack bijection;
+ * which k index enters which partial sum by a hand-worked cancellation case in fp32;
  * the functions for other field widths (end of the file) by hand-written words, numpy byte
  * views, exact rationals, closed forms, numpy's matmul and, at 4 bits, the 4-bit functions;
  * the product with a group index per row by the contiguous case, numpy's matmul over a
@@ -181,18 +187,82 @@ static inline int partition_of(int kk, int k, int split_k, int block_k)
 }
 
 /*
- * Cref (fp64 [m,n], required) and C16 (fp16 [m,n], may be NULL) <- A . dequant(Wq).
- * acc_mode 0: fp64 accumulators; 1: fp32 products and accumulators.
- * split_k >= 1 partial sums are formed separately from zero and then added in ascending
- * partition order, as the final additions into C of Algorithm 1 do in some order.
- * threads: OpenMP threads over blocks of output columns (each output element is still
- * computed by one thread with the same operation order); <= 0 means the runtime default.
+ * Cref (fp64 [m,n], required) and C16 (fp16 [m,n], may be NULL) <- A . dequant(Wq): the
+ * definition, one output element at a time.
+ * acc_mode 0: fp64 accumulators; 1: fp32 products and accumulators (Algorithm 1's accumulator).
+ * split_k >= 1 partial sums are formed separately, each from zero over its own k indices in
+ * ascending order, and then added in ascending partition order, as the final additions into C
+ * of Algorithm 1 do in some order.
+ * threads: OpenMP threads over output columns (every output element is computed by one thread,
+ * by the loops below and nothing else); <= 0 means the runtime default.
  * Returns the number of threads used, or a negative number on bad arguments.
  */
 int w4a16_oracle_gemm(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
                       const int32_t* qzeros, double* Cref, uint16_t* C16,
                       int m, int n, int k, int group_size,
                       int split_k, int block_k, int acc_mode, int threads)
+{
+    if (!A || !qweight || !scales || !qzeros || !Cref) return -1;
+    if (m < 1 || n < 8 || n % 8 || group_size < 8 || group_size % 8 || k < group_size || k % group_size) return -2;
+    if (split_k < 1 || (block_k == 0 && k % split_k) || block_k < 0) return -3;
+    if (acc_mode != 0 && acc_mode != 1) return -4;
+
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#endif
+
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < n; ++j) {
+        for (int i = 0; i < m; ++i) {
+            double total64 = 0.0;
+            float total32 = 0.0f;
+            for (int p = 0; p < split_k; ++p) {
+                double part64 = 0.0;
+                float part32 = 0.0f;
+                for (int kk = 0; kk < k; ++kk) {
+                    if (partition_of(kk, k, split_k, block_k) != p) continue;
+                    const int grp = kk / group_size;
+                    const int qd = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);
+                    const int zd = field_of(qzeros, (size_t)grp * (n / 8) + j / 8, j % 8);
+                    const float sd = w4a16_oracle_half_to_float(scales[(size_t)grp * n + j]);
+                    const float wd = (float)(qd - zd) * sd; /* exact */
+                    const float ad = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);
+                    if (acc_mode == 0) {
+                        part64 += (double)ad * (double)wd;
+                    } else {
+                        const float prod = ad * wd;
+                        part32 += prod;
+                    }
+                }
+                total64 += part64;
+                total32 += part32;
+            }
+            const double total = acc_mode == 0 ? total64 : (double)total32;
+            Cref[(size_t)i * n + j] = total;
+            if (C16) C16[(size_t)i * n + j] = w4a16_oracle_double_to_half(total);
+        }
+    }
+    return used;
+}
+
+/*
+ * The same product arranged for speed, for the timed CPU baseline only: blocks of 128 output
+ * columns, one dequantised weight row kept per k index and used by all m activation rows, one
+ * array of partial sums per block.  Per output element the operations and their order are those
+ * of w4a16_oracle_gemm (ascending k inside a partial sum, ascending partition order), so the
+ * results are the same bit for bit; a test holds it to that on several blocks and a ragged last
+ * one.  No parity test uses this function.
+ */
+int w4a16_oracle_gemm_blocked(const uint16_t* A, const int32_t* qweight, const uint16_t* scales,
+                              const int32_t* qzeros, double* Cref, uint16_t* C16,
+                              int m, int n, int k, int group_size,
+                              int split_k, int block_k, int acc_mode, int threads)
 {
     if (!A || !qweight || !scales || !qzeros || !Cref) return -1;
     if (m < 1 || n < 8 || n % 8 || group_size < 8 || group_size % 8 || k < group_size || k % group_size) return -2;

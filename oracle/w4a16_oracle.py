@@ -60,6 +60,8 @@ class Oracle:
         lib.w4a16_oracle_dequant.restype = None
         lib.w4a16_oracle_gemm.argtypes = [_u16p, _i32p, _u16p, _i32p, _f64p, _u16p] + [ctypes.c_int] * 8
         lib.w4a16_oracle_gemm.restype = ctypes.c_int
+        lib.w4a16_oracle_gemm_blocked.argtypes = lib.w4a16_oracle_gemm.argtypes
+        lib.w4a16_oracle_gemm_blocked.restype = ctypes.c_int
         for name in ("unpack_qweight_bits", "unpack_qzeros_bits"):
             fn = getattr(lib, "w4a16_oracle_" + name)
             fn.argtypes = [_i32p, _u8p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
@@ -144,8 +146,11 @@ class Oracle:
 
     # ---- the product (paper Algorithm 1; Section 3 first paragraph for the DP variant)
     def gemm(self, A, qweight, scales, qzeros, group_size: int, split_k: int = 1, block_k: int = 0,
-             acc: str = "f64", threads: int = 0, return_threads: bool = False):
-        """Cref (float64 [m, n]) and its fp16 rounding C16 (float16 [m, n]).
+             acc: str = "f64", threads: int = 0, return_threads: bool = False, blocked: bool = False):
+        """Cref (float64 [m, n]) and its fp16 rounding C16 (float16 [m, n]): the definition, one
+        output element at a time.  blocked=True calls the arrangement kept for the timed CPU
+        baseline instead (same operations per element, bit-identical results; no parity test
+        uses it).
 
         acc = "f64": fp64 accumulators (the definition); "f32": Algorithm 1's fp32 accumulator.
         split_k partial sums: contiguous chunks of k (block_k = 0) or Algorithm 1's strided
@@ -164,7 +169,8 @@ class Oracle:
             raise OracleError("scales / qzeros shapes do not match k, n, group_size")
         Cref = np.empty((m, n), np.float64)
         C16 = np.empty((m, n), np.float16)
-        rc = self.lib.w4a16_oracle_gemm(
+        fn = self.lib.w4a16_oracle_gemm_blocked if blocked else self.lib.w4a16_oracle_gemm
+        rc = fn(
             _ptr(A.view(np.uint16), ctypes.c_uint16), _ptr(qweight, ctypes.c_int32),
             _ptr(scales.view(np.uint16), ctypes.c_uint16), _ptr(qzeros, ctypes.c_int32),
             _ptr(Cref, ctypes.c_double), _ptr(C16.view(np.uint16), ctypes.c_uint16),
@@ -390,3 +396,7 @@ def gemm_3bit(A, qweight, scales, qzeros, group_size, **kw):
 
 def gemm(A, qweight, scales, qzeros, group_size, **kw):
     return default().gemm(A, qweight, scales, qzeros, group_size, **kw)
+
+
+def gemm_blocked(A, qweight, scales, qzeros, group_size, **kw):
+    return default().gemm(A, qweight, scales, qzeros, group_size, blocked=True, **kw)

@@ -287,6 +287,50 @@ def pin_splitk_invariance(o):
         assert np.abs(Cs32 - C1).max() <= 1e-5 * scale
 
 
+def pin_partition_order_by_cancellation(o):
+    """Which k index goes into which partial sum, made visible through fp32 rounding, with the
+    expected values worked out by hand.  All weights are 256 (q = 1, z = 0, s = 256); k = 32;
+    the terms are +2^23 at k = 0, 1/4 at k = 8..15, -2^23 at k = 16.  An fp32 sum that holds 2^23
+    loses every 1/4 added to it (the unit in the last place there is 1).
+      Algorithm 1's walk with split_k = 2 over k-blocks of 8: program 0 takes blocks 0 and 2
+      (2^23 - 2^23 = 0), program 1 takes blocks 1 and 3 (8 * 1/4 = 2): total 2.
+      Two contiguous halves: 2^23 + 8 lost quarters = 2^23, then -2^23: total 0.
+      No split: the quarters are lost as well: 0.  fp64 accumulators: always exactly 2."""
+    n, k, g = 8, 32, 32
+    A = np.zeros((1, k), np.float16)
+    A[0, 0] = 32768.0
+    A[0, 8:16] = 2.0 ** -10
+    A[0, 16] = -32768.0
+    qw = np.full((k // 8, n), 0x11111111, dtype=np.uint32).view(np.int32)
+    qz = np.zeros((k // g, n // 8), np.int32)
+    s = np.full((k // g, n), 256.0, np.float16)
+    for blocked in (False, True):
+        for kw, expect in ((dict(split_k=2, block_k=8, acc="f32"), 2.0), (dict(split_k=2, acc="f32"), 0.0),
+                           (dict(acc="f32"), 0.0), (dict(split_k=2, block_k=8), 2.0), (dict(split_k=2), 2.0),
+                           (dict(), 2.0), (dict(split_k=4, block_k=8, acc="f32"), 2.0),
+                           (dict(split_k=4, acc="f32"), 2.0)):
+            Cref, _ = o.gemm(A, qw, s, qz, g, blocked=blocked, **kw)
+            assert np.array_equal(Cref, np.full((1, n), expect)), (blocked, kw, Cref)
+
+
+def pin_blocked_arrangement_is_the_definition(o):
+    """The arrangement kept for the timed CPU baseline (column blocks of 128, a cached weight
+    row) against the definition, bit for bit: three and more blocks, a ragged last block, one
+    block, both accumulators, both kinds of partition; and on its own against numpy's matmul."""
+    for (m, n, k, g, seed) in ((5, 392, 512, 128, 31), (16, 520, 256, 64, 32), (3, 384, 384, 128, 33), (2, 72, 256, 32, 34)):
+        A, qw, s, qz = random_case(m, n, k, g, seed)
+        for kw in (dict(), dict(acc="f32"), dict(split_k=2), dict(split_k=4, block_k=32, acc="f32"), dict(split_k=2, block_k=64)):
+            Cp, Cp16 = o.gemm(A, qw, s, qz, g, **kw)
+            Cb, Cb16 = o.gemm(A, qw, s, qz, g, blocked=True, **kw)
+            assert np.array_equal(Cb.view(np.uint64), Cp.view(np.uint64)), (n, kw)
+            assert np.array_equal(Cb16.view(np.uint16), Cp16.view(np.uint16)), (n, kw)
+        W = np_dense_weight(qw, s, qz, g)
+        ref = A.astype(np.float64) @ W
+        absdot = np.abs(A.astype(np.float64)) @ np.abs(W)
+        Cb, _ = o.gemm(A, qw, s, qz, g, blocked=True)
+        assert np.all(np.abs(Cb - ref) <= 2 * k * 2.0 ** -53 * absdot + 1e-300)
+
+
 def pin_distribution(o):
     """Output statistics of the synthetic workload: Var(C) = k * Var(q - z) * E[s^2] * E[a^2]
     with Var(q - z) = 2 * (16^2 - 1) / 12 = 42.5 and E[s^2] = (a^2 + ab + b^2) / 3."""
@@ -658,6 +702,8 @@ ALL_PINS = [
     pin_group_boundary,
     pin_linearity_and_permutation,
     pin_splitk_invariance,
+    pin_partition_order_by_cancellation,
+    pin_blocked_arrangement_is_the_definition,
     pin_distribution,
     pin_bits_known_words,
     pin_bits_unpack_library_and_bijection,

@@ -76,6 +76,7 @@ def test_cfg1(oracle):
     p.C.fill_(float("nan"))
     b.w4a16_gemm_dp(*p.args())
     assert_parity(p.result(), Cref, "cfg1 dp")
+    assert b.w4a16_phase_timeouts() == 0
 
 
 # ------------------------------------------------------------------ small shapes: tiles, ragged tail, every knob
@@ -1231,6 +1232,7 @@ def test_cfg2_split_sweep(oracle):
     p.C.fill_(float("nan"))
     b.w4a16_gemm_dp(*p.args())
     assert_parity(p.result(), Cref, "cfg2 dp")
+    assert b.w4a16_phase_timeouts() == 0
 
 
 @pytest.mark.parametrize("nk", [4096, 8192])
@@ -1246,6 +1248,7 @@ def test_cfg3_m_sweep(oracle, nk):
         p.C.fill_(float("nan"))
         b.w4a16_gemm_dp(*p.args())
         assert_parity(p.result(), Cref, f"cfg3 dp m={m} nk={nk}")
+    assert b.w4a16_phase_timeouts() == 0
 
 
 def test_cfg4_split_sweep(oracle):
@@ -1254,6 +1257,7 @@ def test_cfg4_split_sweep(oracle):
         p.C.fill_(float("nan"))
         b.w4a16_gemm(*p.args(), split_k)
         assert_parity(p.result(), Cref, f"cfg4 S={split_k}")
+    assert b.w4a16_phase_timeouts() == 0
 
 
 def test_cfg5_split_sweep(oracle):
@@ -1265,3 +1269,4 @@ def test_cfg5_split_sweep(oracle):
     p.C.fill_(float("nan"))
     b.w4a16_gemm_dp(*p.args())
     assert_parity(p.result(), Cref, "cfg5 dp")
+    assert b.w4a16_phase_timeouts() == 0

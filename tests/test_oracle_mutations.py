@@ -14,26 +14,41 @@ SRC = pathlib.Path(__file__).resolve().parent.parent / "oracle" / "w4a16_oracle.
 
 # (name, text to find, replacement, which occurrence: index or "all")
 MUTATIONS = [
-    ("qweight_field_order_in_gemm",
-     "int q = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);\n                int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
-     "int q = field_of(qweight, (size_t)(kk / 8) * n + j, 7 - kk % 8);\n                int z = field_of(qzeros, (size_t)gi * (n / 8) + j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow", 0),
-    ("qzeros_field_order_in_gemm", "j / 8, j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
-     "j / 8, 7 - j % 8);\n                float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow", 0),
-    ("zero_point_plus_one", "wrow[jj] = (float)(q - z) * s;", "wrow[jj] = (float)(q - z - 1) * s;", 0),
-    ("sign_flipped", "wrow[jj] = (float)(q - z) * s;", "wrow[jj] = (float)(z - q) * s;", 0),
-    ("group_boundary_off_by_one", "const int gi = kk / group_size;\n            const int p",
+    # the definition (w4a16_oracle_gemm)
+    ("qweight_field_order_in_gemm", "const int qd = field_of(qweight, (size_t)(kk / 8) * n + j, kk % 8);",
+     "const int qd = field_of(qweight, (size_t)(kk / 8) * n + j, 7 - kk % 8);", 0),
+    ("qzeros_field_order_in_gemm", "const int zd = field_of(qzeros, (size_t)grp * (n / 8) + j / 8, j % 8);",
+     "const int zd = field_of(qzeros, (size_t)grp * (n / 8) + j / 8, 7 - j % 8);", 0),
+    ("qzeros_word_column_in_gemm", "const int zd = field_of(qzeros, (size_t)grp * (n / 8) + j / 8, j % 8);",
+     "const int zd = field_of(qzeros, (size_t)grp * (n / 8) + j % (n / 8), j % 8);", 0),
+    ("zero_point_plus_one", "const float wd = (float)(qd - zd) * sd;", "const float wd = (float)(qd - zd - 1) * sd;", 0),
+    ("sign_flipped", "const float wd = (float)(qd - zd) * sd;", "const float wd = (float)(zd - qd) * sd;", 0),
+    ("group_boundary_off_by_one", "const int grp = kk / group_size;",
+     "const int grp = (kk == k - 1 ? kk : kk + 1) / group_size;", 0),
+    ("A_transposed", "const float ad = w4a16_oracle_half_to_float(A[(size_t)i * k + kk]);",
+     "const float ad = w4a16_oracle_half_to_float(A[(size_t)kk * m + i]);", 0),
+    ("last_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n                    if (partition_of",
+     "for (int kk = 0; kk < k - 1; ++kk) {\n                    if (partition_of", 0),
+    ("first_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n                    if (partition_of",
+     "for (int kk = 1; kk < k; ++kk) {\n                    if (partition_of", 0),
+    ("last_partial_sum_dropped", "for (int p = 0; p < split_k; ++p) {\n                double part64",
+     "for (int p = 0; p < split_k - (split_k > 1); ++p) {\n                double part64", 0),
+    ("partial_sums_not_added_f32", "total32 += part32;", "total32 = part32;", 0),
+    ("partial_sums_not_added_f64", "total64 += part64;", "total64 = part64;", 0),
+    ("strided_partition_ignores_block", "return (kk / block_k) % split_k;", "return kk % split_k < 0 ? 0 : (kk / (k / split_k)) % split_k;", 0),
+    ("scale_column_swapped", "const float sd = w4a16_oracle_half_to_float(scales[(size_t)grp * n + j]);",
+     "const float sd = w4a16_oracle_half_to_float(scales[(size_t)grp * n + (j ^ 1)]);", 0),
+    ("fp32_mode_accumulates_in_fp64", "const float prod = ad * wd;\n                        part32 += prod;",
+     "part64 += (double)ad * (double)wd;\n                        part32 = (float)part64;", 0),
+    # the arrangement for the timed baseline (w4a16_oracle_gemm_blocked): held to the definition
+    ("blocked_zero_point_plus_one", "wrow[jj] = (float)(q - z) * s;", "wrow[jj] = (float)(q - z - 1) * s;", 0),
+    ("blocked_group_boundary_off_by_one", "const int gi = kk / group_size;\n            const int p",
      "const int gi = (kk == k - 1 ? kk : kk + 1) / group_size;\n            const int p", 0),
-    ("A_transposed", "A[(size_t)i * k + kk]", "A[(size_t)kk * m + i]", 0),
-    ("last_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n            const int gi",
-     "for (int kk = 0; kk < k - 1; ++kk) {\n            const int gi", 0),
-    ("first_k_term_dropped", "for (int kk = 0; kk < k; ++kk) {\n            const int gi",
-     "for (int kk = 1; kk < k; ++kk) {\n            const int gi", 0),
-    ("last_partial_sum_dropped_f64", "for (int p = 0; p < split_k; ++p) t += part64",
+    ("blocked_last_block_dropped", "const int n_blocks = (n + col_block - 1) / col_block;", "const int n_blocks = n / col_block > 0 ? n / col_block : 1;", 0),
+    ("blocked_last_partial_sum_dropped_f64", "for (int p = 0; p < split_k; ++p) t += part64",
      "for (int p = 0; p < split_k - (split_k > 1); ++p) t += part64", 0),
-    ("last_partial_sum_dropped_f32", "for (int p = 0; p < split_k; ++p) t += part32",
+    ("blocked_last_partial_sum_dropped_f32", "for (int p = 0; p < split_k; ++p) t += part32",
      "for (int p = 0; p < split_k - (split_k > 1); ++p) t += part32", 0),
-    ("scale_column_swapped", "float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + j]);\n                wrow",
-     "float s = w4a16_oracle_half_to_float(scales[(size_t)gi * n + (j ^ 1)]);\n                wrow", 0),
     ("ties_away_from_zero", "(rem == halfway && (q & 1))", "(rem == halfway)", 0),
     ("truncating_conversion", "if (rem > halfway || (rem == halfway && (q & 1))) ++q;", "", 0),
     ("subnormal_exponent", "127 - 15 + 1 - shift", "127 - 15 - shift", 0),
