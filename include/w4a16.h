@@ -36,13 +36,24 @@
  * aborts.
  *
  * Split-k scratch: depending on the reduction flavour (W4A16_REDUCE_*) the split-k entry points
- * keep partial sums, arrival counters or per-tile flags in library-owned per-device scratch
- * buffers (at most 16 * n 64-bit words, split_k * m * n floats for the workspace flavour, and,
- * for the in-kernel zeroing, 16 KiB * (1 + split_k) per distinct split_k used), allocated on the
- * first call that needs them and left consistent
- * for the next call by the kernel itself.  Two split-k calls that overlap in time on the same
- * device (different streams) would share that scratch and must not be issued; calls on one
- * stream are safe.
+ * keep partial sums, arrival counters or per-tile flags in scratch memory that every call leaves
+ * as it found it (sums back at zero, counters one call further).  By default that memory is the
+ * library's, one set of buffers per device (at most 16 * n 64-bit words, split_k * m * n floats
+ * for the workspace flavour, and, for the in-kernel zeroing, 16 KiB * (1 + split_k) per distinct
+ * split_k used), allocated by the first call that needs it (hipMalloc + a synchronous clear; use
+ * w4a16_reserve_scratch to do that ahead of time) and never moved or freed before
+ * w4a16_release_scratch: a buffer that is outgrown stays alive, so a HIP graph captured earlier
+ * keeps working.  A call that would have to allocate while its stream is being captured returns
+ * W4A16_ERR_STATE instead.  Split-k calls that overlap in time on one device share the library's
+ * buffers and must not be issued on different streams; a caller with several streams gives each
+ * its own memory with w4a16_set_workspace, and calls on different streams are then independent.
+ *
+ * Failure of the in-kernel zeroing (W4A16_REDUCE_ATOMIC_PK_F16_PHASE): its waits are bounded, so
+ * a kernel always ends.  A wait that runs out (only possible when the per-tile words were
+ * corrupted: overlapping calls on shared scratch, an aborted kernel) is counted, adds NaN to the
+ * tile's first output pair, and raises a sticky per-device word in pinned host memory that every
+ * later split-k call on the library's or a bound scratch checks first, without synchronising:
+ * such calls return W4A16_ERR_STATE until w4a16_release_scratch.
  */
 #ifndef W4A16_H
 #define W4A16_H
@@ -58,6 +69,9 @@ extern "C" {
                                       k parts than compute groups, uneven parts where they must be equal */
 #define W4A16_ERR_UNSUPPORTED (-4) /* group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
 #define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
+#define W4A16_ERR_STATE (-6)       /* an earlier wait of the in-kernel zeroing ran out on this device (see above), or
+                                      scratch would have to be allocated during a stream capture */
+#define W4A16_ERR_LIMIT (-7)       /* beyond a fixed capacity: a bound workspace's n_max, the table of bound workspaces */
 
 /* How split-k partial sums reach C (Section 2.1 of the paper discusses the atomic form). */
 #define W4A16_REDUCE_AUTO 0
@@ -69,7 +83,8 @@ extern "C" {
 #define W4A16_REDUCE_WORKSPACE 3    /* plain fp32 partial tiles in scratch; last block sums them in fixed order */
 #define W4A16_REDUCE_ATOMIC_FIXED 4 /* 64-bit fixed-point atomic adds that also count arrivals: one round trip,
                                        order-independent (bit-reproducible) sum; split_k <= 64; partial sums
-                                       are clamped to +-131071 */
+                                       are clamped to +-131071 (an fp16 infinity in C either way) and a NaN
+                                       partial sum makes the element NaN */
 #define W4A16_REDUCE_ATOMIC_PK_F16_PHASE 5 /* packed-fp16 atomic adds straight into C with no launch before the
                                        GEMM kernel: the first k slice's workgroup zeroes its tile of C inside
                                        the kernel and the others wait for that through a per-tile flag;
@@ -155,7 +170,7 @@ long long w3a16_algorithmic_bytes(int m, int n, int k, int group_size);
  * qweight itself) <- the rows of qweight in that order; *status (device, int32) <- 0, or 1 when
  * some group does not have exactly g rows (then perm and qweight_sorted are unusable; no access
  * leaves the buffers whatever g_idx holds).  Asynchronous on `stream` like everything else; it
- * clears *status with a memset node, so it is not meant to be captured in a HIP graph.
+ * clears *status with a small kernel, so it can be captured in a HIP graph.
  *
  * w4a16_gemm_actorder, per call: A_work (device, fp16 [m, k], 16-byte aligned, caller's scratch,
  * not A) <- A[:, perm], then the SplitK GEMM of A_work with qweight_sorted, scales and qzeros as
@@ -238,13 +253,42 @@ const char* w4a16_last_hip_error(void);
 
 /*
  * W4A16_REDUCE_ATOMIC_PK_F16_PHASE only: how many wavefronts on the current device have so far
- * given up waiting for a tile's zeroing (they then add into whatever C held).  0 unless the
- * per-tile words were corrupted, e.g. by two overlapping calls or an aborted kernel; releasing
- * the scratch resets them.  Synchronises the device.  Negative: a W4A16_ERR_* code.
+ * given up waiting for a tile's zeroing (library scratch and bound workspaces together).  0 unless the per-tile words were corrupted, e.g. by two overlapping calls or an
+ * aborted kernel; releasing the scratch resets them.  Synchronises the device.  Negative: a
+ * W4A16_ERR_* code.
  */
 long long w4a16_phase_timeouts(void);
 
-/* Release the per-device scratch of the current device (synchronises the device). */
+/*
+ * Test hook for the failure path above: the number of polls after which a wait gives up
+ * (0 = the library's default, 131072).  A kernel ends normally whatever the value.
+ */
+int w4a16_set_phase_spin_limit(int polls);
+
+/*
+ * A caller-owned workspace for the split-k state of the calls issued on `stream` (current device):
+ * `workspace` is device memory, 256-byte aligned, of at least w4a16_workspace_bytes(n_max) bytes
+ * (about 34 MiB + 192 bytes per column; 0 for a bad n_max: a multiple of 8 up to 65536), which
+ * the caller keeps alive and untouched while bound.  The call clears it on `stream` (a kernel, so
+ * it may be captured) and binds it: from then on calls on that stream with n <= n_max use it and
+ * are independent of calls on other streams; n > n_max returns W4A16_ERR_LIMIT.  Only the partial
+ * tiles of W4A16_REDUCE_WORKSPACE, which have no bound, stay in the library's own buffer.
+ * workspace == NULL unbinds the stream.  Up to 64 bindings per process.
+ */
+long long w4a16_workspace_bytes(int n_max);
+int w4a16_set_workspace(void* workspace, long long bytes, int n_max, void* stream);
+
+/*
+ * Allocate, now, everything the library's own scratch can need for calls with up to n_max columns
+ * (about 36 MiB at n_max = 16384), so that no later call allocates, e.g. before capturing graphs.
+ */
+int w4a16_reserve_scratch(int n_max);
+
+/*
+ * Release the library's scratch of the current device, retired buffers included (synchronises the
+ * device), forget its bound workspaces and clear the sticky error.  Graphs
+ * captured before this call must not be replayed after it.
+ */
 int w4a16_release_scratch(void);
 
 #ifdef __cplusplus

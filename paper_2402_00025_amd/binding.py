@@ -15,7 +15,7 @@ _HERE = pathlib.Path(__file__).resolve().parent
 LIB_PATH = _HERE / "libw4a16.so"
 
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_SPLIT, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
+ERR_NULL, ERR_SHAPE, ERR_SPLIT, ERR_UNSUPPORTED, ERR_HIP, ERR_STATE, ERR_LIMIT = -1, -2, -3, -4, -5, -6, -7
 REDUCE_AUTO, REDUCE_ATOMIC_F32, REDUCE_ATOMIC_PK_F16, REDUCE_WORKSPACE, REDUCE_ATOMIC_FIXED = 0, 1, 2, 3, 4
 REDUCE_ATOMIC_PK_F16_PHASE = 5
 
@@ -26,7 +26,8 @@ EXPORTS = (
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
     "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w3a16_gemm", "w3a16_gemm_dp", "w3a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
-    "w4a16_read_probe",
+    "w4a16_read_probe", "w4a16_set_phase_spin_limit", "w4a16_workspace_bytes",
+    "w4a16_set_workspace", "w4a16_reserve_scratch",
 )
 
 _lib = None
@@ -36,7 +37,7 @@ class W4A16Error(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
         detail = ""
-        if code == ERR_HIP:
+        if code in (ERR_HIP, ERR_STATE):
             detail = " [" + lib().w4a16_last_hip_error().decode() + "]"
         super().__init__(f"{where} failed with code {code}: {strerror(code)}{detail}")
 
@@ -60,6 +61,11 @@ def lib() -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     L.w4a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w4a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
+    L.w4a16_set_phase_spin_limit.argtypes = [ci]
+    L.w4a16_workspace_bytes.argtypes = [ci]
+    L.w4a16_workspace_bytes.restype = ctypes.c_longlong
+    L.w4a16_set_workspace.argtypes = [vp, ctypes.c_longlong, ci, vp]
+    L.w4a16_reserve_scratch.argtypes = [ci]
     L.w4a16_gemm_streamk.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w8a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w8a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
@@ -95,7 +101,7 @@ def lib() -> ctypes.CDLL:
     for name in EXPORTS:
         if name not in ("w4a16_algorithmic_bytes", "w8a16_algorithmic_bytes", "w2a16_algorithmic_bytes",
                         "w3a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
-                        "w4a16_phase_timeouts"):
+                        "w4a16_phase_timeouts", "w4a16_workspace_bytes"):
             getattr(L, name).restype = ci
     _lib = L
     return L
@@ -253,3 +259,19 @@ def w4a16_phase_timeouts() -> int:
 
 def w4a16_release_scratch() -> None:
     _check(lib().w4a16_release_scratch(), "w4a16_release_scratch")
+
+
+def w4a16_set_phase_spin_limit(polls: int) -> None:
+    _check(lib().w4a16_set_phase_spin_limit(polls), "w4a16_set_phase_spin_limit")
+
+
+def w4a16_workspace_bytes(n_max: int) -> int:
+    return int(lib().w4a16_workspace_bytes(n_max))
+
+
+def w4a16_set_workspace(workspace, nbytes: int, n_max: int, stream=None) -> None:
+    _check(lib().w4a16_set_workspace(_p(workspace), nbytes, n_max, _stream(stream)), "w4a16_set_workspace")
+
+
+def w4a16_reserve_scratch(n_max: int) -> None:
+    _check(lib().w4a16_reserve_scratch(n_max), "w4a16_reserve_scratch")

@@ -42,6 +42,7 @@ struct GemmArgs {
     uint32_t* flags;    // phase mode: zeroings so far, per tile origin
     uint32_t* counts;   // phase mode: calls so far, per (tile origin, slice)
     uint32_t* errors;   // phase mode: count of waits that ran out
+    uint32_t* err_host; // phase mode: word in pinned host memory set to 1 by a wait that ran out (may be null)
 };
 
 enum : int {
@@ -50,31 +51,44 @@ enum : int {
 };
 
 // kAtomicFixed: one 64-bit integer atomic add per output element and workgroup.
-//   bits 57..63  arrivals so far (split_k <= 64)
-//   bits  0..56  sum of (partial * 2^33 + 2^50): fixed point, biased so it never goes negative;
-//                every term is below 2^51 (|partial| is clamped below 2^17), so 64 of them stay
-//                below 2^57 and never reach the arrival count
+//   bits 58..63  arrivals before this one (0..63: split_k <= 64; the last add may carry out of
+//                the word, which is then reset anyway)
+//   bits 52..57  how many of the contributions so far were NaN (they add nothing to the sum)
+//   bits  0..51  sum of (partial * 2^28 + 2^45): fixed point, biased so it never goes negative;
+//                every term is below 2^46 (|partial| is clamped below 2^17, beyond fp16's range),
+//                so 64 of them stay below 2^52.  2^-28 resolves every product of an fp16 value
+//                with a small integer exactly and is finer than the fp32 partial sums' own
+//                last place from 1/16 on.
 // The add returns the previous word, so the workgroup that sees split_k - 1 earlier arrivals
 // holds the complete sum (previous + its own) and finishes the element: one memory round trip,
-// no separate ticket, and a sum that does not depend on arrival order (integer addition).
-constexpr int kFixedFracBits = 33;
-constexpr uint64_t kFixedBias = 1ull << 50;
-constexpr int kFixedArrivalShift = 57;
+// no separate ticket, and a sum that does not depend on arrival order (integer addition).  A NaN
+// among the partial sums makes the result NaN, as with every other reduction; an infinite or
+// huge one is clamped and comes out as an fp16 infinity.
+constexpr int kFixedFracBits = 28;
+constexpr uint64_t kFixedBias = 1ull << 45;
+constexpr int kFixedNanShift = 52;
+constexpr int kFixedArrivalShift = 58;
 constexpr uint64_t kFixedArrival = 1ull << kFixedArrivalShift;
-constexpr uint64_t kFixedSumMask = kFixedArrival - 1;
-constexpr float kFixedClamp = 131071.0f;  // |partial| < 2^17 keeps partial * 2^33 inside the bias
+constexpr uint64_t kFixedSumMask = (1ull << kFixedNanShift) - 1;
+constexpr uint64_t kFixedNanMask = (kFixedArrival - 1) & ~kFixedSumMask;
+constexpr float kFixedClamp = 131071.0f;  // |partial| < 2^17 keeps partial * 2^28 inside the bias
 
 __device__ __forceinline__ uint64_t fixed_contribution(float v)
 {
-    v = fminf(fmaxf(v, -kFixedClamp), kFixedClamp);
+    const bool nan = v != v;
+    v = nan ? 0.f : fminf(fmaxf(v, -kFixedClamp), kFixedClamp);
     const long long q = __double2ll_rn((double)v * (double)(1ull << kFixedFracBits));
-    return (uint64_t)(q + (long long)kFixedBias) + kFixedArrival;
+    return (uint64_t)(q + (long long)kFixedBias) + kFixedArrival + (nan ? 1ull << kFixedNanShift : 0ull);
 }
 
-__device__ __forceinline__ float fixed_total(uint64_t word, int split_k)
+// The total of the word before the last add (`old`) and the last contribution (`mine`); the
+// fields are read from each on its own, so a NaN count of 64 cannot wrap to "none".
+__device__ __forceinline__ float fixed_total(uint64_t old, uint64_t mine, int split_k)
 {
-    const long long q = (long long)(word & kFixedSumMask) - (long long)split_k * (long long)kFixedBias;
-    return (float)((double)q * (1.0 / (double)(1ull << kFixedFracBits)));
+    const long long q =
+        (long long)((old & kFixedSumMask) + (mine & kFixedSumMask)) - (long long)split_k * (long long)kFixedBias;
+    const float sum = (float)((double)q * (1.0 / (double)(1ull << kFixedFracBits)));
+    return ((old | mine) & kFixedNanMask) ? __builtin_nanf("") : sum;
 }
 
 // After `old = fetch_add(word, mine)`: if this was the last of split_k arrivals, returns true
@@ -82,7 +96,7 @@ __device__ __forceinline__ float fixed_total(uint64_t word, int split_k)
 __device__ __forceinline__ bool fixed_finish(uint64_t* word, uint64_t old, uint64_t mine, int split_k, float* total)
 {
     if ((int)(old >> kFixedArrivalShift) != split_k - 1) return false;
-    *total = fixed_total(old + mine, split_k);
+    *total = fixed_total(old, mine, split_k);
     __hip_atomic_store(word, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return true;
 }
@@ -97,6 +111,17 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi)
 // before it goes on.  On gfx9-family hardware the vector memory counter also covers stores and
 // atomics without return.  The "memory" clobber keeps the compiler from moving accesses across.
 __device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// A wait of the phase protocol ran out (one lane calls this): count it, raise the sticky word the
+// host looks at before its next call, and add NaN to the first column pair of the tile, so that
+// the output cannot pass for a result.  `c_off` is a byte offset inside C.
+__device__ __forceinline__ void phase_wait_failed(uint32_t* errors, uint32_t* err_host, rsrc_t rs_c, uint32_t c_off)
+{
+    __hip_atomic_fetch_add(errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (err_host) __hip_atomic_store(err_host, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const half2_t poison = {(_Float16)__builtin_nanf(""), (_Float16)__builtin_nanf("")};
+    __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(poison, rs_c, c_off, 0, 0);
+}
 
 // One workgroup = WAVES wavefronts that share one output tile [m, 16 V] and divide the
 // workgroup's k range between them; blockIdx.x = slice * tiles + tile.
@@ -209,8 +234,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
                     __hip_atomic_load(p.flags + origin_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 ++polls;
             } while (seen != now && polls < p.spin_limit);
-            if (seen != now && lane == 0)
-                __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (seen != now && lane == 0) phase_wait_failed(p.errors, p.err_host, rs_c, (uint32_t)n0 * 2u);
             __syncthreads();  // the working waves' one barrier
             return;
         }
@@ -478,8 +502,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
                 __hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             ++polls;
         }
-        if (seen != expect && lane == 0)
-            __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen != expect && lane == 0) phase_wait_failed(p.errors, p.err_host, rs_out, (uint32_t)n0 * 2u);
     }
 
     if (has_units) {
@@ -567,6 +590,7 @@ struct GemmRest {
     uint32_t* flags;
     uint32_t* counts;
     uint32_t* errors;
+    uint32_t* err_host;
     int split_k;
     int lds_wave_bytes;
     int spin_limit;
@@ -597,6 +621,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
     p.flags = rest.flags;
     p.counts = rest.counts;
     p.errors = rest.errors;
+    p.err_host = rest.err_host;
     p.split_k = rest.split_k;
     p.lds_wave_bytes = rest.lds_wave_bytes;
     p.spin_limit = rest.spin_limit;
@@ -791,7 +816,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
                 ++polls;
             }
             if (!seen && lane == 0)
-                __hip_atomic_fetch_add(p.errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                phase_wait_failed(p.errors, p.err_host, rs_c, (uint32_t)tile * (uint32_t)kStreamTileCols * 2u);
         }
     }
     __syncthreads();
@@ -845,6 +870,7 @@ struct StreamRest {
     uint32_t* flags;
     uint32_t* counts;
     uint32_t* errors;
+    uint32_t* err_host;
     int spin_limit;
     int probe_delay;
 };
@@ -872,6 +898,7 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
     p.flags = rest.flags;
     p.counts = rest.counts;
     p.errors = rest.errors;
+    p.err_host = rest.err_host;
     p.spin_limit = rest.spin_limit;
     p.probe_delay = rest.probe_delay;
     stream_body<D, MODE, MT, BITS>(p);
@@ -1164,6 +1191,9 @@ struct Buffer {
     void* ptr = nullptr;
     size_t bytes = 0;
 };
+// Split-k state of one device, owned by the library.  Buffers only ever grow, and a buffer that
+// is outgrown is kept until w4a16_release_scratch: a HIP graph captured earlier still holds its
+// address and must find it alive (and consistent: every call leaves its words as it found them).
 struct DeviceScratch {
     Buffer sums;      // atomic mode: fp32 [16, n]; all zero whenever no call is running
     Buffer partials;  // workspace mode: fp32 [split_k, m, n]; no invariant
@@ -1173,10 +1203,32 @@ struct DeviceScratch {
     // call with that split_k: flags [kPhaseOrigins], then counts [kPhaseOrigins][split_k]
     Buffer phase_level[kPhaseMaxSplit + 1];
     Buffer phase_err;  // the error count [1]
+    uint32_t* err_host = nullptr;  // pinned host word that a wait which ran out sets to 1
+    void* retired[64] = {};        // outgrown buffers, freed by w4a16_release_scratch
+    int retired_count = 0;
 };
+// Where one call's split-k state lives: the library's own buffers or a workspace the caller bound
+// to the stream.
+struct ScratchView {
+    float* sums = nullptr;
+    float* partials = nullptr;
+    uint64_t* fixed = nullptr;
+    uint32_t* tickets = nullptr;
+    uint32_t* flags = nullptr;
+    uint32_t* counts = nullptr;
+    uint32_t* errors = nullptr;
+    uint32_t* err_host = nullptr;
+};
+struct ScratchNeed {
+    size_t sums_floats = 0, partial_floats = 0, fixed_words = 0, ticket_count = 0;
+    int phase_split = 0;  // 0, or the split_k whose flags and counts the call needs
+    int n = 0;            // columns of the call (the phase words cover tile origins n0 / 16)
+};
+enum : int { kScratchLibrary = 0 };
 // Word offset of the counts inside a level's buffer, and the buffer's size in words.
 static size_t phase_counts_offset() { return kPhaseOrigins; }
 static size_t phase_level_words(int split_k) { return (size_t)kPhaseOrigins * (1 + (size_t)split_k); }
+
 // Text of the last failed HIP call on this host thread (for W4A16_ERR_HIP diagnostics).
 static thread_local char g_hip_detail[256] = "";
 
@@ -1193,6 +1245,7 @@ constexpr int kMaxDevices = 64;
 // microsecond): far longer than any call takes, short enough that a broken state cannot hang
 // the device.
 constexpr int kSpinLimit = 1 << 17;
+static int g_spin_limit = kSpinLimit;  // w4a16_set_phase_spin_limit (tests of the failure path)
 // 64-cycle sleeps before a sample of the tile flag (service wave: before every sample; in-wave
 // protocol: between learning the call count and the early sample).  Measured flat from 0 to 16
 // with a slight optimum at 8-16 (fewer polls on the way to memory), worse from 32 on.
@@ -1204,7 +1257,28 @@ static int g_streamk_blocks = 256;
 // Fewest workgroups that the plan accepts for a launch whose waves each take a long run of groups.
 static int g_stream_min_blocks = 160;
 static DeviceScratch g_scratch[kMaxDevices];
+// A workspace that the caller bound to a stream (w4a16_set_workspace): calls on that stream keep
+// their split-k state there, so calls on different streams no longer share anything.
+struct Binding {
+    int dev = -1;
+    hipStream_t stream = nullptr;
+    uint32_t* base = nullptr;
+    int n_max = 0;
+};
+constexpr int kMaxBindings = 64;
+static Binding g_bindings[kMaxBindings];
 static std::mutex g_mutex;
+
+// Layout of a caller's workspace, in 32-bit words: 64 words head ([0] = waits that ran out), one
+// ticket per 16 columns, the phase levels of split_k 2..64, fp32 sums [16, n_max], fixed-point
+// words [16, n_max].
+static size_t workspace_level_offset(int n_max, int split_k)
+{
+    return 64 + (size_t)n_max / 16 + (size_t)kPhaseOrigins * ((size_t)(split_k - 2) + ((size_t)(split_k - 1) * split_k / 2 - 1));
+}
+static size_t workspace_sums_offset(int n_max) { return (workspace_level_offset(n_max, kPhaseMaxSplit + 1) + 63) & ~(size_t)63; }
+static size_t workspace_fixed_offset(int n_max) { return workspace_sums_offset(n_max) + (size_t)16 * n_max; }
+static size_t workspace_words(int n_max) { return workspace_fixed_offset(n_max) + (size_t)32 * n_max; }
 
 // `even_split`: a requested split_k must cut k into equal shares of whole quantisation groups
 // (Algorithm 1 as printed); otherwise it only has to be positive, and the shares are whole
@@ -1253,6 +1327,7 @@ static bool phase_split_ok(int split_k) { return split_k >= 2 && split_k <= kPha
 static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves,
                      int reduce, Plan* out, int bits = 4)
 {
+    const int reduce_asked = reduce;
     // compute groups: the units (32, 64 or 128 consecutive k) that the k parts are made of
     const int cgroups = k / (group_size >= 128 ? 128 : group_size);
     const long long packed_bytes = (long long)k * n * bits / 8;
@@ -1561,7 +1636,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     }
     if (two_strips) {
         if (split_k * waves != cgroups || waves > 4 || split_k < 2) return W4A16_ERR_UNSUPPORTED;
-        if (reduce == W4A16_REDUCE_ATOMIC_FIXED && m <= 4) reduce = W4A16_REDUCE_ATOMIC_PK_F16_PHASE;  // the auto choice
+        // the only reduction of this launch; an explicit request for another one is refused, not rewritten
+        if (reduce_asked == W4A16_REDUCE_AUTO) reduce = W4A16_REDUCE_ATOMIC_PK_F16_PHASE;
         if (reduce != W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
     }
     if (reduce < W4A16_REDUCE_ATOMIC_F32 || reduce > W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
@@ -1574,12 +1650,26 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     return W4A16_OK;
 }
 
-// Grow-only device buffer.  Growth happens on the first call for a shape, outside any timed
-// region; it frees (which waits for the device), allocates, clears and synchronises.
-static int grow(Buffer& b, size_t bytes, bool* grew)
+// Grow-only device buffer.  Growth happens on the first call that needs the size, outside any
+// timed region (allocation and a synchronous clear), never while `stream` is being captured into
+// a graph, and never frees: the outgrown buffer is retired (see DeviceScratch).
+static int grow(DeviceScratch& s, Buffer& b, size_t bytes, size_t floor_bytes, hipStream_t stream, bool* grew)
 {
     if (b.bytes >= bytes) return W4A16_OK;
-    if (b.ptr) (void)hipFree(b.ptr);
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (!W4A16_HIP(hipStreamIsCapturing(stream, &capturing))) return W4A16_ERR_HIP;
+    if (capturing != hipStreamCaptureStatusNone) {
+        snprintf(g_hip_detail, sizeof(g_hip_detail),
+                 "split-k scratch has to be allocated before a capture: run the call once eagerly, or use "
+                 "w4a16_reserve_scratch or w4a16_set_workspace");
+        return W4A16_ERR_STATE;
+    }
+    if (b.ptr) {
+        if (s.retired_count >= (int)(sizeof(s.retired) / sizeof(s.retired[0]))) return W4A16_ERR_UNSUPPORTED;
+        s.retired[s.retired_count++] = b.ptr;
+    }
+    if (bytes < floor_bytes) bytes = floor_bytes;
+    if (bytes < 2 * b.bytes) bytes = 2 * b.bytes;  // few retirements
     b.ptr = nullptr;
     b.bytes = 0;
     if (!W4A16_HIP(hipMalloc(&b.ptr, bytes))) return W4A16_ERR_HIP;
@@ -1589,35 +1679,80 @@ static int grow(Buffer& b, size_t bytes, bool* grew)
     return W4A16_OK;
 }
 
-// phase_split: 0, or the split_k whose flags and counts the call needs (*phase <- that level's
-// buffer, *phase_err <- the error word).
-static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
-                          int phase_split, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
-                          uint32_t** phase, uint32_t** phase_err)
+// Has a wait of the phase protocol run out on this device since the scratch was last released?
+// (a read of pinned host memory: no synchronisation)
+static bool sticky_error(const DeviceScratch& s) { return s.err_host && *(volatile uint32_t*)s.err_host != 0u; }
+
+static Binding* find_binding(int dev, hipStream_t stream)
 {
-    if (phase_split < 0 || phase_split > kPhaseMaxSplit) return W4A16_ERR_UNSUPPORTED;
+    for (Binding& b : g_bindings)
+        if (b.base && b.dev == dev && b.stream == stream) return &b;
+    return nullptr;
+}
+
+// The pointers a call needs, from the source `kind` names.  kScratchLibrary: the workspace bound
+// to `stream` if there is one, else the library's own buffers (allocated here on first need).
+static int resolve_scratch(int kind, hipStream_t stream, const ScratchNeed& need, ScratchView* out)
+{
+    if (need.phase_split < 0 || need.phase_split > kPhaseMaxSplit) return W4A16_ERR_UNSUPPORTED;
     int dev = 0;
     if (!W4A16_HIP(hipGetDevice(&dev))) return W4A16_ERR_HIP;
     if (dev < 0 || dev >= kMaxDevices) return W4A16_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
+    *out = ScratchView{};
     DeviceScratch& s = g_scratch[dev];
+    if (sticky_error(s)) return W4A16_ERR_STATE;
+    if (const Binding* b = find_binding(dev, stream)) {
+        if (need.n > b->n_max) return W4A16_ERR_LIMIT;
+        out->errors = b->base;
+        out->err_host = s.err_host;
+        out->tickets = b->base + 64;
+        if (need.phase_split) {
+            out->flags = b->base + workspace_level_offset(b->n_max, need.phase_split);
+            out->counts = out->flags + phase_counts_offset();
+        }
+        out->sums = (float*)(b->base + workspace_sums_offset(b->n_max));
+        out->fixed = (uint64_t*)(b->base + workspace_fixed_offset(b->n_max));
+        if (need.partial_floats) {
+            // the partial tiles of the workspace flavour have no bound: they stay in the library's buffer
+            bool grew_partials = false;
+            const int rcp = grow(s, s.partials, need.partial_floats * sizeof(float), 0, stream, &grew_partials);
+            if (rcp != W4A16_OK) return rcp;
+            if (grew_partials && !W4A16_HIP(hipDeviceSynchronize())) return W4A16_ERR_HIP;
+            out->partials = (float*)s.partials.ptr;
+        }
+        return W4A16_OK;
+    }
     bool grew = false;
-    int rc = grow(s.sums, sums_floats * sizeof(float), &grew);
-    if (rc == W4A16_OK) rc = grow(s.partials, partial_floats * sizeof(float), &grew);
-    if (rc == W4A16_OK) rc = grow(s.fixed, fixed_words * sizeof(uint64_t), &grew);
-    if (rc == W4A16_OK) rc = grow(s.tickets, ticket_count * sizeof(uint32_t), &grew);
-    if (rc == W4A16_OK && phase_split) {
-        rc = grow(s.phase_level[phase_split], phase_level_words(phase_split) * sizeof(uint32_t), &grew);
-        if (rc == W4A16_OK) rc = grow(s.phase_err, sizeof(uint32_t), &grew);
+    // sized for sixteen rows whatever m is, and at first for n = 16384, so that the usual shapes
+    // never grow a buffer twice
+    const size_t rows16 = (size_t)16 * (size_t)need.n;
+    const size_t sums_floats = need.sums_floats ? (need.sums_floats > rows16 ? need.sums_floats : rows16) : 0;
+    const size_t fixed_words = need.fixed_words ? (need.fixed_words > rows16 ? need.fixed_words : rows16) : 0;
+    int rc = grow(s, s.sums, sums_floats * sizeof(float), (size_t)16 * 16384 * sizeof(float), stream, &grew);
+    if (rc == W4A16_OK) rc = grow(s, s.partials, need.partial_floats * sizeof(float), 0, stream, &grew);
+    if (rc == W4A16_OK) rc = grow(s, s.fixed, fixed_words * sizeof(uint64_t), (size_t)16 * 16384 * sizeof(uint64_t), stream, &grew);
+    if (rc == W4A16_OK) rc = grow(s, s.tickets, need.ticket_count * sizeof(uint32_t), 4096 * sizeof(uint32_t), stream, &grew);
+    if (rc == W4A16_OK && need.phase_split) {
+        rc = grow(s, s.phase_level[need.phase_split], phase_level_words(need.phase_split) * sizeof(uint32_t), 0, stream, &grew);
+        if (rc == W4A16_OK) rc = grow(s, s.phase_err, sizeof(uint32_t), 256, stream, &grew);
+        if (rc == W4A16_OK && !s.err_host) {
+            if (!W4A16_HIP(hipHostMalloc((void**)&s.err_host, 256, hipHostMallocMapped))) return W4A16_ERR_HIP;
+            *s.err_host = 0u;
+        }
     }
     if (rc != W4A16_OK) return rc;
     if (grew && !W4A16_HIP(hipDeviceSynchronize())) return W4A16_ERR_HIP;
-    *sums = (float*)s.sums.ptr;
-    *partials = (float*)s.partials.ptr;
-    *fixed = (uint64_t*)s.fixed.ptr;
-    *tickets = (uint32_t*)s.tickets.ptr;
-    *phase = phase_split ? (uint32_t*)s.phase_level[phase_split].ptr : nullptr;
-    *phase_err = (uint32_t*)s.phase_err.ptr;
+    out->sums = (float*)s.sums.ptr;
+    out->partials = (float*)s.partials.ptr;
+    out->fixed = (uint64_t*)s.fixed.ptr;
+    out->tickets = (uint32_t*)s.tickets.ptr;
+    if (need.phase_split) {
+        out->flags = (uint32_t*)s.phase_level[need.phase_split].ptr;
+        out->counts = out->flags + phase_counts_offset();
+    }
+    out->errors = (uint32_t*)s.phase_err.ptr;
+    out->err_host = s.err_host;
     return W4A16_OK;
 }
 
@@ -1643,6 +1778,7 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
     rest.flags = a.flags;
     rest.counts = a.counts;
     rest.errors = a.errors;
+    rest.err_host = a.err_host;
     rest.split_k = a.split_k;
     rest.lds_wave_bytes = a.lds_wave_bytes;
     rest.spin_limit = a.spin_limit;
@@ -1775,6 +1911,7 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     rest.flags = a.flags;
     rest.counts = a.counts;
     rest.errors = a.errors;
+    rest.err_host = a.err_host;
     rest.spin_limit = a.spin_limit;
     rest.probe_delay = a.probe_delay;
     hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a.A,
@@ -1798,14 +1935,11 @@ static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, 
     return launch_stream_mode<1, MT, BITS>(a, lds_bytes, mode, stream);
 }
 
-static int ensure_scratch(size_t sums_floats, size_t partial_floats, size_t fixed_words, size_t ticket_count,
-                          int phase_split, float** sums, float** partials, uint64_t** fixed, uint32_t** tickets,
-                          uint32_t** phase, uint32_t** phase_err);
-
 // tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
 // m <= 64; more than 16 rows need waves = 4.
 static int run_stream(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
-                      int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream, int bits = 4)
+                      int n, int k, int group_size, int split_k, int waves, int reduce, hipStream_t stream, int bits = 4,
+                      int scratch_kind = kScratchLibrary)
 {
     if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
     if (bits != 4 && m > 16) return W4A16_ERR_UNSUPPORTED;  // the other field widths: one row tile
@@ -1829,7 +1963,7 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     a.scales = (const _Float16*)scales;
     a.qzeros = (const uint32_t*)qzeros;
     a.C = (_Float16*)C;
-    a.flags = a.counts = a.errors = nullptr;
+    a.flags = a.counts = a.errors = a.err_host = nullptr;
     a.m = m;
     a.n = n;
     a.k = k;
@@ -1839,21 +1973,23 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     a.groups_base = groups / (split_k * wk);
     a.groups_rem = groups % (split_k * wk);
     a.param_shift = group_size == 256 ? 1 : 0;
-    a.spin_limit = kSpinLimit;
+    a.spin_limit = g_spin_limit;
     a.probe_delay = g_probe_delay;
     const size_t lds_bytes = (size_t)wk * 2 * mt * kChunkBytes + (size_t)waves * m * 64 * 4;
     int mode = kDirect;
     if (split_k > 1) {
         if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) {
             if (!phase_split_ok(split_k) || (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
-            float *sums = nullptr, *partials = nullptr;
-            uint64_t* fixed = nullptr;
-            uint32_t *tickets = nullptr, *phase = nullptr, *phase_err = nullptr;
-            const int rc = ensure_scratch(0, 0, 0, 0, split_k, &sums, &partials, &fixed, &tickets, &phase, &phase_err);
+            ScratchNeed need;
+            need.phase_split = split_k;
+            need.n = n;
+            ScratchView view;
+            const int rc = resolve_scratch(scratch_kind, stream, need, &view);
             if (rc != W4A16_OK) return rc;
-            a.flags = phase;
-            a.counts = phase + phase_counts_offset();
-            a.errors = phase_err;
+            a.flags = view.flags;
+            a.counts = view.counts;
+            a.errors = view.errors;
+            a.err_host = view.err_host;
             mode = kAtomicPkF16Phase;
         } else {
             const size_t words = (size_t)m * n / 2;
@@ -1917,15 +2053,23 @@ static void read_tuning_env()
     static bool done = false;
     if (done) return;
     done = true;
-    if (const char* e = getenv("W4A16_PROBE_DELAY")) g_probe_delay = atoi(e);
-    if (const char* e = getenv("W4A16_STREAM_DEPTH")) g_stream_depth = atoi(e);
-    if (const char* e = getenv("W4A16_STREAM_MIN_BLOCKS")) g_stream_min_blocks = atoi(e);
-    if (const char* e = getenv("W4A16_STREAMK_BLOCKS")) g_streamk_blocks = atoi(e) > 0 ? atoi(e) : g_streamk_blocks;
+    // a value outside its range is ignored (the default stays)
+    auto read = [](const char* name, int lo, int hi, int* value) {
+        const char* e = getenv(name);
+        if (!e || !*e) return;
+        char* end = nullptr;
+        const long v = strtol(e, &end, 10);
+        if (end && *end == '\0' && v >= lo && v <= hi) *value = (int)v;
+    };
+    read("W4A16_PROBE_DELAY", 0, 64, &g_probe_delay);
+    read("W4A16_STREAM_DEPTH", 1, 2, &g_stream_depth);
+    read("W4A16_STREAM_MIN_BLOCKS", 1, 1024, &g_stream_min_blocks);
+    read("W4A16_STREAMK_BLOCKS", 1, 65535, &g_streamk_blocks);
 }
 
 static int run_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
                     int n, int k, int group_size, bool dp, int split_k, int tile_cols, int waves, int reduce,
-                    bool even_split, void* stream_v, int bits = 4)
+                    bool even_split, void* stream_v, int bits = 4, int scratch_kind = kScratchLibrary)
 {
     if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
     read_tuning_env();
@@ -1946,7 +2090,8 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
         for (int r = 0; r < m; r += rows_per_launch) {
             const int mm = m - r < rows_per_launch ? m - r : rows_per_launch;
             rc = run_gemm((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros, (_Float16*)C + (size_t)r * n, mm,
-                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v, bits);
+                          n, k, group_size, dp, split_k, tile_cols, waves, reduce, even_split, stream_v, bits,
+                          scratch_kind);
             if (rc != W4A16_OK) return rc;
         }
         return W4A16_OK;
@@ -1957,7 +2102,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (plan.tile_cols == kStreamTileCols) {
         if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
         return run_stream(A, qweight, scales, qzeros, C, m, n, k, group_size, plan.split_k, plan.waves, plan.reduce,
-                          (hipStream_t)stream_v, bits);
+                          (hipStream_t)stream_v, bits, scratch_kind);
     }
 
     hipStream_t stream = (hipStream_t)stream_v;
@@ -1990,7 +2135,8 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     a.flags = nullptr;
     a.counts = nullptr;
     a.errors = nullptr;
-    a.spin_limit = kSpinLimit;
+    a.err_host = nullptr;
+    a.spin_limit = g_spin_limit;
     a.probe_delay = g_probe_delay;
     if (lds_bytes > 160 * 1024) return W4A16_ERR_UNSUPPORTED;
 
@@ -1998,21 +2144,24 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     if (plan.split_k > 1) {
         mode = plan.reduce;  // W4A16_REDUCE_* values equal the kernel modes
         if (mode != kAtomicPkF16) {
-            float *sums = nullptr, *partials = nullptr;
-            uint64_t* fixed = nullptr;
-            uint32_t *phase = nullptr, *phase_err = nullptr;
             if (mode == kAtomicPkF16Phase && (size_t)n > 16 * (size_t)kPhaseOrigins) return W4A16_ERR_UNSUPPORTED;
-            rc = ensure_scratch(mode == kAtomicF32 ? (size_t)16 * n : 0,
-                                mode == kWorkspace ? (size_t)plan.split_k * m * n : 0,
-                                mode == kAtomicFixed ? (size_t)16 * n : 0, (size_t)a.tiles,
-                                mode == kAtomicPkF16Phase ? plan.split_k : 0, &sums, &partials, &fixed, &a.tickets,
-                                &phase, &phase_err);
+            ScratchNeed need;
+            need.n = n;
+            need.sums_floats = mode == kAtomicF32 ? (size_t)m * n : 0;
+            need.partial_floats = mode == kWorkspace ? (size_t)plan.split_k * m * n : 0;
+            need.fixed_words = mode == kAtomicFixed ? (size_t)m * n : 0;
+            need.ticket_count = mode == kAtomicF32 || mode == kWorkspace ? (size_t)a.tiles : 0;
+            need.phase_split = mode == kAtomicPkF16Phase ? plan.split_k : 0;
+            ScratchView view;
+            rc = resolve_scratch(scratch_kind, stream, need, &view);
             if (rc != W4A16_OK) return rc;
-            a.scratch = mode == kAtomicF32 ? sums : mode == kWorkspace ? partials : (float*)fixed;
+            a.scratch = mode == kAtomicF32 ? view.sums : mode == kWorkspace ? view.partials : (float*)view.fixed;
+            a.tickets = view.tickets;
             if (mode == kAtomicPkF16Phase) {
-                a.flags = phase;
-                a.counts = phase + phase_counts_offset();
-                a.errors = phase_err;
+                a.flags = view.flags;
+                a.counts = view.counts;
+                a.errors = view.errors;
+                a.err_host = view.err_host;
             }
         } else {
             const size_t words = (size_t)m * n / 2;
@@ -2316,6 +2465,11 @@ const char* w4a16_strerror(int code)
     case W4A16_ERR_UNSUPPORTED:
         return "unsupported: group_size not in {32,64,128,256}, pointer not 16-byte aligned, or bad tuning value";
     case W4A16_ERR_HIP: return "a HIP runtime call failed";
+    case W4A16_ERR_STATE:
+        return "split-k scratch unusable: a wait of the in-kernel zeroing ran out earlier on this device (release "
+               "the scratch to go on), or scratch would have to be allocated while the stream is being captured";
+    case W4A16_ERR_LIMIT:
+        return "beyond a fixed capacity: a bound workspace takes n up to the n_max it was sized for";
     default: return "unknown w4a16 error code";
     }
 }
@@ -2329,13 +2483,92 @@ long long w4a16_phase_timeouts(void)
     if (dev < 0 || dev >= w4a16::kMaxDevices) return W4A16_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(w4a16::g_mutex);
     const w4a16::DeviceScratch& s = w4a16::g_scratch[dev];
-    if (!s.phase_err.ptr) return 0;
-    uint32_t count = 0;
+    // the counters of the library's own scratch and of every bound workspace
+    const uint32_t* words[2 + w4a16::kMaxBindings];
+    int count = 0;
+    if (s.phase_err.ptr) words[count++] = (const uint32_t*)s.phase_err.ptr;
+    for (const w4a16::Binding& b : w4a16::g_bindings)
+        if (b.base && b.dev == dev) words[count++] = b.base;
+    if (count == 0) return 0;
     if (hipDeviceSynchronize() != hipSuccess) return W4A16_ERR_HIP;
-    if (hipMemcpy(&count, (const uint32_t*)s.phase_err.ptr, sizeof(count),
-                  hipMemcpyDeviceToHost) != hipSuccess)
-        return W4A16_ERR_HIP;
-    return (long long)count;
+    long long total = 0;
+    for (int i = 0; i < count; ++i) {
+        uint32_t v = 0;
+        if (hipMemcpy(&v, words[i], sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return W4A16_ERR_HIP;
+        total += v;
+    }
+    return total;
+}
+
+int w4a16_set_phase_spin_limit(int polls)
+{
+    if (polls < 0) return W4A16_ERR_UNSUPPORTED;
+    w4a16::g_spin_limit = polls == 0 ? w4a16::kSpinLimit : polls;
+    return W4A16_OK;
+}
+
+long long w4a16_workspace_bytes(int n_max)
+{
+    if (n_max < 8 || (n_max % 8) != 0 || (size_t)n_max > 16 * (size_t)w4a16::kPhaseOrigins) return 0;
+    return (long long)(w4a16::workspace_words(n_max) * sizeof(uint32_t));
+}
+
+int w4a16_set_workspace(void* workspace, long long bytes, int n_max, void* stream_v)
+{
+    int dev = 0;
+    if (!w4a16::W4A16_HIP(hipGetDevice(&dev))) return W4A16_ERR_HIP;
+    if (dev < 0 || dev >= w4a16::kMaxDevices) return W4A16_ERR_UNSUPPORTED;
+    hipStream_t stream = (hipStream_t)stream_v;
+    if (workspace) {
+        const long long want = w4a16_workspace_bytes(n_max);
+        if (want == 0) return W4A16_ERR_SHAPE;
+        if (bytes < want) return W4A16_ERR_LIMIT;
+        if (((uintptr_t)workspace & 255u) != 0) return W4A16_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(w4a16::g_mutex);
+    w4a16::DeviceScratch& s = w4a16::g_scratch[dev];
+    w4a16::Binding* slot = w4a16::find_binding(dev, stream);
+    if (!workspace) {  // unbind
+        if (slot) *slot = w4a16::Binding{};
+        return W4A16_OK;
+    }
+    if (!slot)
+        for (w4a16::Binding& b : w4a16::g_bindings)
+            if (!b.base) {
+                slot = &b;
+                break;
+            }
+    if (!slot) return W4A16_ERR_LIMIT;
+    if (!s.err_host) {
+        if (!w4a16::W4A16_HIP(hipHostMalloc((void**)&s.err_host, 256, hipHostMallocMapped))) return W4A16_ERR_HIP;
+        *s.err_host = 0u;
+    }
+    // every word starts at zero; cleared on the stream the workspace serves (a kernel, not a memset node)
+    const size_t words = w4a16::workspace_words(n_max);
+    hipLaunchKernelGGL(w4a16::fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                       (uint32_t*)workspace, words);
+    if (!w4a16::W4A16_HIP(hipGetLastError())) return W4A16_ERR_HIP;
+    slot->dev = dev;
+    slot->stream = stream;
+    slot->base = (uint32_t*)workspace;
+    slot->n_max = n_max;
+    return W4A16_OK;
+}
+
+int w4a16_reserve_scratch(int n_max)
+{
+    if (n_max < 8 || (n_max % 8) != 0) return W4A16_ERR_SHAPE;
+    // everything the library's own plan can ask for at this n: fixed-point words and every phase level
+    for (int split_k = 0; split_k <= w4a16::kPhaseMaxSplit; split_k = split_k == 0 ? 2 : split_k + 1) {
+        w4a16::ScratchNeed need;
+        need.n = n_max;
+        need.fixed_words = (size_t)16 * n_max;
+        need.phase_split = (size_t)n_max <= 16 * (size_t)w4a16::kPhaseOrigins ? split_k : 0;
+        w4a16::ScratchView view;
+        const int rc = w4a16::resolve_scratch(w4a16::kScratchLibrary, nullptr, need, &view);
+        if (rc != W4A16_OK) return rc;
+    }
+    return W4A16_OK;
 }
 
 int w4a16_release_scratch(void)
@@ -2353,7 +2586,12 @@ int w4a16_release_scratch(void)
     for (w4a16::Buffer& level : s.phase_level)
         if (level.ptr) (void)hipFree(level.ptr);
     if (s.phase_err.ptr) (void)hipFree(s.phase_err.ptr);
+    for (int i = 0; i < s.retired_count; ++i) (void)hipFree(s.retired[i]);
+    if (s.err_host) (void)hipHostFree(s.err_host);
     s = w4a16::DeviceScratch{};
+    // bound workspaces belong to their callers: forget them
+    for (w4a16::Binding& b : w4a16::g_bindings)
+        if (b.dev == dev) b = w4a16::Binding{};
     return W4A16_OK;
 }
 

@@ -37,6 +37,7 @@ struct StreamArgs {
     uint32_t* flags;      // phase protocol: zeroings so far, per tile origin (n0 / 16)
     uint32_t* counts;     // phase protocol: calls so far, per (tile origin, slice)
     uint32_t* errors;     // phase protocol: count of waits that ran out
+    uint32_t* err_host;   // phase protocol: word in pinned host memory set by a wait that ran out (may be null)
     int m, n, k;
     int tiles;            // 256-column workgroup tiles = ceil(n / 256)
     int split_k;

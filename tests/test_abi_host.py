@@ -29,14 +29,17 @@ def test_library_exports_every_declared_symbol():
 def test_error_codes_match_header():
     for name, val in (("W4A16_OK", b.OK), ("W4A16_ERR_NULL", b.ERR_NULL), ("W4A16_ERR_SHAPE", b.ERR_SHAPE),
                       ("W4A16_ERR_SPLIT", b.ERR_SPLIT), ("W4A16_ERR_UNSUPPORTED", b.ERR_UNSUPPORTED),
-                      ("W4A16_ERR_HIP", b.ERR_HIP), ("W4A16_REDUCE_ATOMIC_F32", b.REDUCE_ATOMIC_F32),
+                      ("W4A16_ERR_HIP", b.ERR_HIP), ("W4A16_ERR_STATE", b.ERR_STATE), ("W4A16_ERR_LIMIT", b.ERR_LIMIT),
+                      ("W4A16_REDUCE_ATOMIC_F32", b.REDUCE_ATOMIC_F32),
                       ("W4A16_REDUCE_ATOMIC_PK_F16", b.REDUCE_ATOMIC_PK_F16), ("W4A16_REDUCE_WORKSPACE", b.REDUCE_WORKSPACE),
                       ("W4A16_REDUCE_ATOMIC_FIXED", b.REDUCE_ATOMIC_FIXED),
                       ("W4A16_REDUCE_ATOMIC_PK_F16_PHASE", b.REDUCE_ATOMIC_PK_F16_PHASE)):
         mt = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", HEADER)
         assert mt and int(mt.group(1)) == val, name
-    for code in range(-6, 1):
+    for code in range(-8, 1):
         assert isinstance(b.strerror(code), str) and b.strerror(code)
+    texts = [b.strerror(code) for code in range(-7, 1)]
+    assert len(set(texts)) == len(texts) and b.strerror(-8) not in texts   # every code has a text of its own
 
 
 @pytest.mark.parametrize("args,code", [
@@ -104,6 +107,22 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL
+    assert L.w4a16_set_phase_spin_limit(-1) == b.ERR_UNSUPPORTED
+    assert L.w4a16_set_phase_spin_limit(0) == b.OK
+
+
+def test_workspace_size():
+    """w4a16_workspace_bytes: 0 for a bad n_max, otherwise the documented layout (head, tickets,
+    phase levels of split_k 2..64, fp32 sums and fixed-point words for sixteen rows)."""
+    assert b.w4a16_workspace_bytes(0) == 0 and b.w4a16_workspace_bytes(4100) == 0
+    assert b.w4a16_workspace_bytes(65544) == 0
+    levels = sum(4096 * (1 + s) for s in range(2, 65))
+    for n in (8, 4096, 16384, 65536):
+        words = 64 + n // 16 + levels
+        words = (words + 63) // 64 * 64
+        words += 16 * n + 32 * n
+        assert b.w4a16_workspace_bytes(n) == 4 * words, n
+    assert b.w4a16_workspace_bytes(16384) < 40 << 20
 
 
 def test_plan_is_consistent():
