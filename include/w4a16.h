@@ -71,7 +71,8 @@ extern "C" {
 #define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
 #define W4A16_ERR_STATE (-6)       /* an earlier wait of the in-kernel zeroing ran out on this device (see above), or
                                       scratch would have to be allocated during a stream capture */
-#define W4A16_ERR_LIMIT (-7)       /* beyond a fixed capacity: a bound workspace's n_max, the table of bound workspaces */
+#define W4A16_ERR_LIMIT (-7)       /* beyond a fixed capacity: w4a16_gemm_static's static array, a bound workspace's
+                                      n_max, the table of bound workspaces */
 
 /* How split-k partial sums reach C (Section 2.1 of the paper discusses the atomic form). */
 #define W4A16_REDUCE_AUTO 0
@@ -97,6 +98,20 @@ extern "C" {
  */
 int w4a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                int m, int n, int k, int group_size, int split_k, void* stream);
+
+/*
+ * w4a16_gemm for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same operation, same kernels and launch plan,
+ * but the split-k state lives in a static device array of the library (2.7 MiB per GPU, held
+ * until the process ends) instead of allocated buffers.  The call allocates nothing and frees
+ * nothing.  Limits: m <= 16, n <= 16384, and a split_k (given or chosen) of at most 32 when
+ * m > 4; beyond them W4A16_ERR_LIMIT.  All calls on one GPU share the array, which every call
+ * leaves as it found it; calls that overlap in time on one GPU (different streams) race on it
+ * and must not be issued.  A wait of the in-kernel zeroing that runs out is counted
+ * (w4a16_phase_timeouts) and poisons its tile with NaN, but raises no sticky error here.
+ */
+int w4a16_gemm_static(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
+                      int m, int n, int k, int group_size, int split_k, void* stream);
 
 /*
  * Data-parallel tiled kernel (Section 3, first paragraph: one workgroup alone computes a whole
@@ -253,7 +268,8 @@ const char* w4a16_last_hip_error(void);
 
 /*
  * W4A16_REDUCE_ATOMIC_PK_F16_PHASE only: how many wavefronts on the current device have so far
- * given up waiting for a tile's zeroing (library scratch and bound workspaces together).  0 unless the per-tile words were corrupted, e.g. by two overlapping calls or an
+ * given up waiting for a tile's zeroing (library scratch, bound workspaces and the static array
+ * together).  0 unless the per-tile words were corrupted, e.g. by two overlapping calls or an
  * aborted kernel; releasing the scratch resets them.  Synchronises the device.  Negative: a
  * W4A16_ERR_* code.
  */
@@ -286,7 +302,7 @@ int w4a16_reserve_scratch(int n_max);
 
 /*
  * Release the library's scratch of the current device, retired buffers included (synchronises the
- * device), forget its bound workspaces and clear the sticky error.  Graphs
+ * device), forget its bound workspaces, clear the static array and the sticky error.  Graphs
  * captured before this call must not be replayed after it.
  */
 int w4a16_release_scratch(void);

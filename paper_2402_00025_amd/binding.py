@@ -26,7 +26,7 @@ EXPORTS = (
     "w4a16_unpack", "w4a16_dequant", "w4a16_algorithmic_bytes", "w4a16_strerror", "w4a16_last_hip_error",
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
     "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w3a16_gemm", "w3a16_gemm_dp", "w3a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
-    "w4a16_read_probe", "w4a16_set_phase_spin_limit", "w4a16_workspace_bytes",
+    "w4a16_read_probe", "w4a16_gemm_static", "w4a16_set_phase_spin_limit", "w4a16_workspace_bytes",
     "w4a16_set_workspace", "w4a16_reserve_scratch",
 )
 
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
     ip = ctypes.POINTER(ctypes.c_int)
     L.w4a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w4a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
+    L.w4a16_gemm_static.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w4a16_set_phase_spin_limit.argtypes = [ci]
     L.w4a16_workspace_bytes.argtypes = [ci]
     L.w4a16_workspace_bytes.restype = ctypes.c_longlong
@@ -137,6 +138,11 @@ def strerror(code: int) -> str:
 def w4a16_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, stream=None) -> None:
     _check(lib().w4a16_gemm(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size, split_k,
                             _stream(stream)), "w4a16_gemm")
+
+
+def w4a16_gemm_static(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, stream=None) -> None:
+    _check(lib().w4a16_gemm_static(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size, split_k,
+                                   _stream(stream)), "w4a16_gemm_static")
 
 
 def w4a16_gemm_dp(A, qweight, scales, qzeros, C, m, n, k, group_size, stream=None) -> None:

@@ -1207,8 +1207,8 @@ struct DeviceScratch {
     void* retired[64] = {};        // outgrown buffers, freed by w4a16_release_scratch
     int retired_count = 0;
 };
-// Where one call's split-k state lives: the library's own buffers or a workspace the caller bound
-// to the stream.
+// Where one call's split-k state lives: the library's own buffers, a workspace the caller bound
+// to the stream, or the static array of the entry point that allocates nothing.
 struct ScratchView {
     float* sums = nullptr;
     float* partials = nullptr;
@@ -1224,11 +1224,30 @@ struct ScratchNeed {
     int phase_split = 0;  // 0, or the split_k whose flags and counts the call needs
     int n = 0;            // columns of the call (the phase words cover tile origins n0 / 16)
 };
-enum : int { kScratchLibrary = 0 };
+enum : int { kScratchLibrary = 0, kScratchStatic = 1 };
 // Word offset of the counts inside a level's buffer, and the buffer's size in words.
 static size_t phase_counts_offset() { return kPhaseOrigins; }
 static size_t phase_level_words(int split_k) { return (size_t)kPhaseOrigins * (1 + (size_t)split_k); }
 
+// ---- the static array of w4a16_gemm_static (callers that cannot allocate) --------------------
+// Limits of that entry point: n <= kStaticMaxN, m * n <= kStaticFixedWords for the fixed-point
+// adds (up to four rows at the largest n), split_k <= kStaticPhaseMaxSplit for the in-kernel
+// zeroing.  Layout, in 32-bit words: [0] the count of waits that ran out (64 words reserved);
+// the fixed-point words; then for every split_k from 2 on a level of flags [kStaticOrigins] and
+// counts [kStaticOrigins][split_k].  Zero at load time, and every call leaves it as it found it
+// (the fixed-point words return to zero, the phase words count calls).
+constexpr int kStaticMaxN = 16384;
+constexpr size_t kStaticFixedWords = (size_t)4 * kStaticMaxN;  // 64-bit words
+constexpr int kStaticPhaseMaxSplit = 32;
+constexpr uint32_t kStaticOrigins = kStaticMaxN / 16;
+constexpr size_t kStaticHeadWords = 64;
+constexpr size_t static_level_offset(int split_k)  // in 32-bit words; levels 2 .. split_k - 1 lie before it
+{
+    return kStaticHeadWords + 2 * kStaticFixedWords +
+           (size_t)kStaticOrigins * ((size_t)(split_k - 2) + ((size_t)(split_k - 1) * split_k / 2 - 1));
+}
+constexpr size_t kStaticWords = static_level_offset(kStaticPhaseMaxSplit + 1);
+static __device__ __align__(256) uint32_t scratch[kStaticWords];
 // Text of the last failed HIP call on this host thread (for W4A16_ERR_HIP diagnostics).
 static thread_local char g_hip_detail[256] = "";
 
@@ -1257,6 +1276,7 @@ static int g_streamk_blocks = 256;
 // Fewest workgroups that the plan accepts for a launch whose waves each take a long run of groups.
 static int g_stream_min_blocks = 160;
 static DeviceScratch g_scratch[kMaxDevices];
+static uint32_t* g_static_ptr[kMaxDevices];  // device address of `scratch` on each device (hipGetSymbolAddress)
 // A workspace that the caller bound to a stream (w4a16_set_workspace): calls on that stream keep
 // their split-k state there, so calls on different streams no longer share anything.
 struct Binding {
@@ -1692,6 +1712,7 @@ static Binding* find_binding(int dev, hipStream_t stream)
 
 // The pointers a call needs, from the source `kind` names.  kScratchLibrary: the workspace bound
 // to `stream` if there is one, else the library's own buffers (allocated here on first need).
+// kScratchStatic: the static array; nothing is allocated, sizes beyond it are W4A16_ERR_LIMIT.
 static int resolve_scratch(int kind, hipStream_t stream, const ScratchNeed& need, ScratchView* out)
 {
     if (need.phase_split < 0 || need.phase_split > kPhaseMaxSplit) return W4A16_ERR_UNSUPPORTED;
@@ -1700,6 +1721,27 @@ static int resolve_scratch(int kind, hipStream_t stream, const ScratchNeed& need
     if (dev < 0 || dev >= kMaxDevices) return W4A16_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(g_mutex);
     *out = ScratchView{};
+    if (kind == kScratchStatic) {
+        if (need.sums_floats || need.partial_floats || need.ticket_count) return W4A16_ERR_UNSUPPORTED;
+        if (need.n > kStaticMaxN || need.fixed_words > kStaticFixedWords || need.phase_split > kStaticPhaseMaxSplit)
+            return W4A16_ERR_LIMIT;
+        if (!g_static_ptr[dev]) {
+            // once per device, with that device current: the array's name is a host-side stand-in,
+            // its address on this device comes from the runtime
+            uint32_t* ptr = nullptr;
+            if (!W4A16_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)))) return W4A16_ERR_HIP;
+            if (!ptr) return W4A16_ERR_HIP;
+            g_static_ptr[dev] = ptr;
+        }
+        uint32_t* base = g_static_ptr[dev];
+        out->errors = base;
+        out->fixed = (uint64_t*)(base + kStaticHeadWords);
+        if (need.phase_split) {
+            out->flags = base + static_level_offset(need.phase_split);
+            out->counts = out->flags + kStaticOrigins;
+        }
+        return W4A16_OK;
+    }
     DeviceScratch& s = g_scratch[dev];
     if (sticky_error(s)) return W4A16_ERR_STATE;
     if (const Binding* b = find_binding(dev, stream)) {
@@ -2209,6 +2251,18 @@ int w4a16_gemm(const void* A, const void* qweight, const void* scales, const voi
                            W4A16_REDUCE_AUTO, true, stream);
 }
 
+int w4a16_gemm_static(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                      int n, int k, int group_size, int split_k, void* stream)
+{
+    // the limits that do not depend on the launch; resolve_scratch checks the rest against the plan
+    if (m > 16 || n > w4a16::kStaticMaxN) {
+        const int rc = w4a16::check_args(m, n, k, group_size, split_k, true);
+        return rc != W4A16_OK ? rc : W4A16_ERR_LIMIT;
+    }
+    return w4a16::run_gemm(A, qweight, scales, qzeros, C, m, n, k, group_size, false, split_k, 0, 0,
+                           W4A16_REDUCE_AUTO, true, stream, 4, w4a16::kScratchStatic);
+}
+
 int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
                   int k, int group_size, void* stream)
 {
@@ -2469,7 +2523,8 @@ const char* w4a16_strerror(int code)
         return "split-k scratch unusable: a wait of the in-kernel zeroing ran out earlier on this device (release "
                "the scratch to go on), or scratch would have to be allocated while the stream is being captured";
     case W4A16_ERR_LIMIT:
-        return "beyond a fixed capacity: a bound workspace takes n up to the n_max it was sized for";
+        return "beyond a fixed capacity: w4a16_gemm_static takes m <= 16, n <= 16384, m * n <= 65536 with up to "
+               "four rows and split_k <= 32 beyond; a bound workspace takes n up to the n_max it was sized for";
     default: return "unknown w4a16 error code";
     }
 }
@@ -2483,10 +2538,11 @@ long long w4a16_phase_timeouts(void)
     if (dev < 0 || dev >= w4a16::kMaxDevices) return W4A16_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(w4a16::g_mutex);
     const w4a16::DeviceScratch& s = w4a16::g_scratch[dev];
-    // the counters of the library's own scratch and of every bound workspace
+    // the counters of the library's own scratch, of the static array and of every bound workspace
     const uint32_t* words[2 + w4a16::kMaxBindings];
     int count = 0;
     if (s.phase_err.ptr) words[count++] = (const uint32_t*)s.phase_err.ptr;
+    if (w4a16::g_static_ptr[dev]) words[count++] = w4a16::g_static_ptr[dev];
     for (const w4a16::Binding& b : w4a16::g_bindings)
         if (b.base && b.dev == dev) words[count++] = b.base;
     if (count == 0) return 0;
@@ -2589,9 +2645,12 @@ int w4a16_release_scratch(void)
     for (int i = 0; i < s.retired_count; ++i) (void)hipFree(s.retired[i]);
     if (s.err_host) (void)hipHostFree(s.err_host);
     s = w4a16::DeviceScratch{};
-    // bound workspaces belong to their callers: forget them
+    // bound workspaces belong to their callers: forget them; the static array starts over at zero
     for (w4a16::Binding& b : w4a16::g_bindings)
         if (b.dev == dev) b = w4a16::Binding{};
+    if (w4a16::g_static_ptr[dev] &&
+        hipMemset(w4a16::g_static_ptr[dev], 0, w4a16::kStaticWords * sizeof(uint32_t)) != hipSuccess)
+        return W4A16_ERR_HIP;
     return W4A16_OK;
 }
 

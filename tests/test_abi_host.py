@@ -107,6 +107,13 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL
+    # the entry point that allocates nothing: its own limits on top of w4a16_gemm's checks
+    assert L.w4a16_gemm_static(None, p, p, p, p, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
+    assert L.w4a16_gemm_static(p, p, p, p, p, 1, 1020, 1024, 128, 4, None) == b.ERR_SHAPE
+    assert L.w4a16_gemm_static(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
+    assert L.w4a16_gemm_static(p, p, p, p, p, 17, 1024, 1024, 128, 4, None) == b.ERR_LIMIT    # m > 16
+    assert L.w4a16_gemm_static(p, p, p, p, p, 16, 16392, 1024, 128, 4, None) == b.ERR_LIMIT   # n > 16384
+    assert L.w4a16_gemm_static(p, p, p, p, p, 17, 1020, 1024, 128, 4, None) == b.ERR_SHAPE    # a bad shape stays one
     assert L.w4a16_set_phase_spin_limit(-1) == b.ERR_UNSUPPORTED
     assert L.w4a16_set_phase_spin_limit(0) == b.OK
 
