@@ -29,18 +29,36 @@ ROTATE_BYTES = 512 << 20
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 
+def kernel_source_id():
+    """What identifies the kernels that are being timed: a hash of the HIP sources and of the build
+    script (which holds the compiler flags).  A counter summary under profiles/ carries the value
+    it was taken with, so a number from it is only quoted while it still describes this build."""
+    import hashlib
+
+    h = hashlib.sha256()
+    pkg = os.path.join(ROOT, "paper_2402_00025_amd")
+    for rel in ("csrc/w4a16.hip", "csrc/w4a16_device.hpp", "csrc/w4a16_stream.hpp", "build.py"):
+        with open(os.path.join(pkg, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(m, n, k, bits=4):
-    """HBM bytes per launch of the headline kernel from the committed rocprofv3 counter
-    summary (profiles/), or None when there is none for this shape."""
+    """HBM bytes per launch of the timed kernel from the committed rocprofv3 counter summary
+    (profiles/), or None when there is none for this shape or when it was taken with other kernel
+    sources than the ones being timed (its `kernel_source_id=` line differs)."""
     tag = "splitk" if bits == 4 else f"splitk_w{bits}"
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}_m{m}_n{n}_k{k}.txt")
+    traffic, stamp = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch="):
-                return float(line.split("=", 1)[1])
+                traffic = float(line.split("=", 1)[1])
+            if line.startswith("kernel_source_id="):
+                stamp = line.split("=", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    return traffic if stamp == kernel_source_id() else None
 
 
 def calibrate_copy(reps=6, mib=256):
@@ -215,8 +233,17 @@ def time_calls(call, steps, warmup, prewarm_s=0.03):
     while time.perf_counter() < t_end:
         graphs[0].replay()
         torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # pass 1, wall clock: exactly `steps` calls between two synchronisations, nothing else enqueued
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for _ in range(reps):
+        graphs[0].replay()
+    if rem:
+        graphs[1].replay()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    # pass 2, HIP events on the launch stream around the same `steps` calls
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
         graphs[0].replay()
@@ -224,7 +251,6 @@ def time_calls(call, steps, warmup, prewarm_s=0.03):
         graphs[1].replay()
     e1.record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     return (t1 - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
 
 
@@ -241,8 +267,10 @@ def verify(w: Workload, call, oracle_ref):
     return ok, rel, emax
 
 
-def cpu_baseline(w: Workload, budget_s=12.0):
-    """The oracle as it stands, on the host cores, on the headline workload."""
+def cpu_baseline(w: Workload, budget_s=10.0):
+    """The oracle as it stands (the definition, one output element at a time, OpenMP over the
+    columns) on the host cores, on the whole timed workload; beside it the same function on one
+    thread and the column-blocked arrangement kept for timing, each once."""
     from oracle import w4a16_oracle
 
     x = w.host
@@ -254,10 +282,20 @@ def cpu_baseline(w: Workload, budget_s=12.0):
         Cref, _, threads = w4a16_oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, w.g, return_threads=True)
         times.append(time.perf_counter() - t0)
     med = float(np.median(times))
+    t0 = time.perf_counter()
+    w4a16_oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, w.g, threads=1)
+    one = time.perf_counter() - t0
+    w4a16_oracle.gemm(x.A, x.qweight, x.scales, x.qzeros, w.g, threads=int(threads))   # back to all threads
+    t0 = time.perf_counter()
+    w4a16_oracle.gemm_blocked(x.A, x.qweight, x.scales, x.qzeros, w.g)
+    blocked = time.perf_counter() - t0
     return Cref, {
         "value": w.bytes / med / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"full workload m={w.m} n=k={w.n}, {len(times)} calls, median {med * 1e3:.1f} ms/call, fp64 accumulation",
+        "sample": f"full workload m={w.m} n={w.n} k={w.k}, {len(times)} calls, median {med * 1e3:.1f} ms/call, fp64 accumulation",
         "ms_per_call": med * 1e3,
+        "single_thread": {"ms_per_call": one * 1e3, "GBps": w.bytes / one / 1e9, "cores": 1, "calls": 1},
+        "blocked_arrangement": {"ms_per_call": blocked * 1e3, "GBps": w.bytes / blocked / 1e9, "cores": int(threads),
+                                "calls": 1, "note": "same arithmetic in column blocks of 128 with a cached weight row"},
     }
 
 
@@ -270,6 +308,12 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--split-k", type=int, default=0, help="0 = library default")
+    ap.add_argument("--tile-cols", type=int, default=0, help="launch knob of the timed workload (0 = library default)")
+    ap.add_argument("--waves", type=int, default=0, help="launch knob of the timed workload (0 = library default)")
+    ap.add_argument("--reduce", type=int, default=0,
+                    help="reduction flavour of the timed workload, W4A16_REDUCE_* (0 = library default)")
+    ap.add_argument("--dp", action="store_true", help="time the data-parallel kernel instead of the SplitK kernel")
+    ap.add_argument("--table-steps", type=int, default=400, help="timed calls per entry of the tables")
     ap.add_argument("--shape", default="16,4096,4096",
                     help="m,n,k of the timed workload (default: the headline workload; another shape runs "
                          "without the tables, e.g. for a profile of the streaming kernel)")
@@ -295,7 +339,8 @@ def main():
     g = 128
     m, n, k = (int(x) for x in args.shape.split(","))
     width = args.bits   # field width of the timed workload
-    if (m, n, k) != (16, 4096, 4096) or width != 4:
+    knobs = bool(args.tile_cols or args.waves or args.reduce or args.dp)
+    if (m, n, k) != (16, 4096, 4096) or width != 4 or knobs:
         args.no_sweep = True   # the tables belong to the headline run
     if width != 4:
         args.no_cpu = True     # the CPU leg is the headline's
@@ -306,7 +351,8 @@ def main():
 
     log(f"[bench] device {dev_name}; building workload m={m} n={n} k={k} ({nsets(n, k)} weight sets)")
     w = Workload(m, n, k, g, nsets(n, k), seed=args.seed, bits=width)
-    plan = (binding.w4a16_plan(m, n, k, g, split_k=args.split_k) if width == 4
+    plan = (binding.w4a16_plan(m, n, k, g, dp=args.dp, split_k=args.split_k, tile_cols=args.tile_cols, waves=args.waves,
+                               reduce=args.reduce) if width == 4
             else binding.w4a16_plan_bits(width, m, n, k, g, split_k=args.split_k))
 
     # oracle: reference for the correctness gate and the CPU baseline
@@ -323,7 +369,9 @@ def main():
         Cref, cpu = cpu_baseline(w)
         log(f"[bench] oracle on {cpu['cores']} host threads: {cpu['ms_per_call']:.1f} ms/call = {cpu['value']:.2f} GB/s")
 
-    if width == 4:
+    if width == 4 and args.dp:
+        head = make_call(w, "dp", tile_cols=plan["tile_cols"], waves=plan["waves"])
+    elif width == 4:
         head = make_call(w, "splitk", split_k=plan["split_k"], tile_cols=plan["tile_cols"], waves=plan["waves"],
                          reduce=plan["reduce"])
     else:
@@ -350,7 +398,7 @@ def main():
                            "runs of the small shapes are host-bound"}
 
     # the achievable ceiling on this machine: a plain read of the packed weights alone, same protocol
-    ev_read = min(time_calls(make_call(w, "read", split_k=shape), min(args.steps, 400), 50)[1] for shape in range(5))
+    ev_read = min(time_calls(make_call(w, "read", split_k=shape), args.table_steps, 50)[1] for shape in range(5))
     packed_bytes = w.sets[0][0].numel() * 4
     extra["plain_read_of_packed_weights"] = {"bytes": packed_bytes, "us_per_launch": ev_read * 1e6,
                                              "note": "best of the probe's five launch shapes",
@@ -361,7 +409,8 @@ def main():
         f"{packed_bytes / ev_read / 1e9:.0f} GB/s; the GEMM takes {ev / ev_read:.2f}x that")
 
     if not args.no_sweep:
-        sweep_steps, sweep_warm = 400, 50
+        sweep_steps, sweep_warm = args.table_steps, 50
+        big_steps = max(20, args.table_steps // 2)
         # warm (single weight set: cache resident) figure for the headline shape
         w1 = Workload(m, n, k, g, 1, seed=args.seed)
         _, ev_warm = time_calls(make_call(w1, "splitk", split_k=plan["split_k"]), sweep_steps, sweep_warm)
@@ -374,6 +423,38 @@ def main():
             _, e = time_calls(make_call(w, "splitk", split_k=S), sweep_steps, sweep_warm)
             sk.append({"split_k": S, "us": e * 1e6, "GBps": w.bytes / e / 1e9})
         extra["split_k_sweep_m16_nk4096"] = sk
+        # configuration 1: m = 1, n = k = 1024, split_k = 4 as given, the library's own choice, and DP
+        w1k = Workload(1, 1024, 1024, g, nsets(1024, 1024), seed=args.seed)
+        _, e4 = time_calls(make_call(w1k, "splitk", split_k=4), sweep_steps, sweep_warm)
+        _, e0 = time_calls(make_call(w1k, "splitk", split_k=0), sweep_steps, sweep_warm)
+        _, edp = time_calls(make_call(w1k, "dp"), sweep_steps, sweep_warm)
+        extra["cfg1_m1_nk1024"] = {"split_k_4_us": e4 * 1e6, "library_plan_us": e0 * 1e6, "dp_us": edp * 1e6,
+                                   "plan_split_4": binding.w4a16_plan(1, 1024, 1024, g, split_k=4),
+                                   "plan_library": binding.w4a16_plan(1, 1024, 1024, g),
+                                   "GBps_split_k_4": w1k.bytes / e4 / 1e9, "speedup_over_dp": edp / e4,
+                                   "note": "0.55 MB per call: a launch-latency measurement, not a bandwidth one"}
+        log(f"[bench] m=1 n=k=1024: split_k=4 {e4 * 1e6:.2f} us, library plan {e0 * 1e6:.2f} us, dp {edp * 1e6:.2f} us")
+        del w1k
+        # The paper's own protocol for the split_k question (Section 3.3): tile, waves and everything
+        # else held fixed, only split_k varies; split_k = 1 of that launch is the data-parallel kernel
+        # of the comparison (one workgroup per 64-column tile over all of k, stored without atomics).
+        fixed_rows = []
+        for (mm, nk, splits) in ((16, 4096, (1, 2, 4, 8, 16)), (1, 4096, (1, 2, 4, 8, 16)), (16, 8192, (1, 2, 4, 8, 16, 32)),
+                                 (8, 16384, (1, 4, 16, 32))):
+            wb = w if (nk == n and mm == m) else Workload(mm, nk, nk, g, nsets(nk, nk), seed=args.seed)
+            res = []
+            for S in splits:
+                _, e = time_calls(make_call(wb, "splitk", split_k=S, tile_cols=64, waves=2), big_steps, 30)
+                res.append({"split_k": S, "us": e * 1e6, "GBps": wb.bytes / e / 1e9})
+            best = min(res, key=lambda r: r["us"])
+            fixed_rows.append({"m": mm, "n": nk, "k": nk, "tile_cols": 64, "waves": 2, "sweep": res,
+                               "best_split_k": best["split_k"], "speedup_over_split_k_1": res[0]["us"] / best["us"]})
+            log(f"[bench] fixed launch (64 columns, 2 waves) m={mm} n=k={nk}: " +
+                ", ".join(f"S={r['split_k']}: {r['us']:.2f}" for r in res) +
+                f" us; best S={best['split_k']}, x{res[0]['us'] / best['us']:.2f} over S=1")
+            if wb is not w:
+                del wb
+        extra["split_k_sweep_fixed_launch"] = fixed_rows
         # SplitK vs DP, m in {1,2,4,8,16} x n=k in {4096, 8192} (configuration 3)
         rows = []
         for nk in (4096, 8192):
@@ -401,11 +482,11 @@ def main():
             wb = Workload(mm, nk, nk, g, nsets(nk, nk), seed=args.seed)
             res = []
             for S in splits:
-                _, e = time_calls(make_call(wb, "splitk", split_k=S), 200, 30)
+                _, e = time_calls(make_call(wb, "splitk", split_k=S), big_steps, 30)
                 res.append({"split_k": S, "us": e * 1e6, "GBps": wb.bytes / e / 1e9,
                             "frac_of_peak": wb.bytes / e / 1e9 / HBM_PEAK_GBPS})
-            _, e_dp = time_calls(make_call(wb, "dp"), 200, 30)
-            e_rd = min(time_calls(make_call(wb, "read", split_k=shape), 200, 30)[1] for shape in range(5))
+            _, e_dp = time_calls(make_call(wb, "dp"), big_steps, 30)
+            e_rd = min(time_calls(make_call(wb, "read", split_k=shape), big_steps, 30)[1] for shape in range(5))
             extra[key] = {"splitk": res, "dp_us": e_dp * 1e6, "plain_read_of_packed_weights_us": e_rd * 1e6}
             best = min(res, key=lambda r: r["us"])
             log(f"[bench] m={mm} n=k={nk}: best split_k={best['split_k']} {best['us']:.2f} us "
@@ -422,9 +503,9 @@ def main():
             for mm in (1, 16):
                 wm = wb.with_m(mm)
                 pl = binding.w4a16_plan(mm, n_, k_, g)
-                _, e = time_calls(make_call(wm, "splitk", split_k=0), 200, 30)
-                _, e_dp = time_calls(make_call(wm, "dp"), 200, 30)
-                _, e_sk = time_calls(make_call(wm, "streamk"), 200, 30)
+                _, e = time_calls(make_call(wm, "splitk", split_k=0), big_steps, 30)
+                _, e_dp = time_calls(make_call(wm, "dp"), big_steps, 30)
+                _, e_sk = time_calls(make_call(wm, "streamk"), big_steps, 30)
                 rows.append({"m": mm, "n": n_, "k": k_, "plan": pl, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
                              "streamk_us": e_sk * 1e6, "speedup_over_dp": e_dp / e, "splitk_GBps": wm.bytes / e / 1e9,
                              "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
@@ -437,7 +518,7 @@ def main():
         wb = Workload(64, 8192, 8192, g, nsets(8192, 8192), seed=args.seed)
         for mm in (16, 32, 48, 64):
             wm = wb.with_m(mm)
-            _, e = time_calls(make_call(wm, "splitk", split_k=0), 200, 30)
+            _, e = time_calls(make_call(wm, "splitk", split_k=0), big_steps, 30)
             rows.append({"m": mm, "n": 8192, "k": 8192, "splitk_us": e * 1e6, "splitk_GBps": wm.bytes / e / 1e9,
                          "TFLOPs": 2.0 * mm * 8192 * 8192 / e / 1e12})
             log(f"[bench] m={mm:2d} n=k=8192: splitk {e * 1e6:7.2f} us, {wm.bytes / e / 1e9:.0f} GB/s, "
@@ -452,8 +533,8 @@ def main():
                 wb = Workload(16, nk, nk, g, max(2, -(-ROTATE_BYTES // (nk * nk * bits // 8))), seed=args.seed, bits=bits)
                 for mm in (1, 16):
                     wm = wb.with_m(mm)
-                    _, e = time_calls(make_call(wm, "splitk_bits", split_k=0), 200, 30)
-                    _, e_dp = time_calls(make_call(wm, "dp_bits"), 200, 30)
+                    _, e = time_calls(make_call(wm, "splitk_bits", split_k=0), big_steps, 30)
+                    _, e_dp = time_calls(make_call(wm, "dp_bits"), big_steps, 30)
                     rows.append({"m": mm, "n": nk, "k": nk, "bits": bits, "splitk_us": e * 1e6, "dp_us": e_dp * 1e6,
                                  "splitk_GBps": wm.bytes / e / 1e9, "frac_of_peak": wm.bytes / e / 1e9 / HBM_PEAK_GBPS})
                     log(f"[bench] {bits}-bit m={mm:2d} n=k={nk}: splitk {e * 1e6:7.2f} us, dp {e_dp * 1e6:7.2f} us, "
@@ -506,6 +587,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(m, n, k, width),
                      "kernel": "w4a16::gemm_stream_kernel (SplitK)" if plan["tile_cols"] == 256 else "w4a16::gemm_kernel (SplitK)", "algorithmic_bytes_per_launch": w.bytes},
         "cpu_baseline": cpu,
+        "kernel_source_id": kernel_source_id(),
         "extra": extra,
     }
     print(json.dumps(out), flush=True)

@@ -101,6 +101,18 @@ __device__ __forceinline__ bool fixed_finish(uint64_t* word, uint64_t old, uint6
     return true;
 }
 
+// Results and protocol words are stored write-through (the sc1 bit of a buffer store, an
+// agent-scope atomic store elsewhere).  A plain store leaves a dirty line in the die's L2 that
+// the release at the end of the kernel has to find and write back: 0.16 us per launch on the
+// headline shape for a single dirty word per workgroup, which is as much as the whole sum over
+// the waves costs.  Written through, nothing is dirty when the kernel ends.
+constexpr int kWriteThrough = 16;  // aux bits of a buffer store: sc1
+
+__device__ __forceinline__ void store_through(uint32_t* word, uint32_t value)
+{
+    __hip_atomic_store(word, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ uint32_t pack_half2(float lo, float hi)
 {
     const half2_t h = {(_Float16)lo, (_Float16)hi};  // v_cvt_f16_f32: round to nearest even
@@ -222,7 +234,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             asm volatile("" : "+v"(count_s)::"memory");
             const uint32_t now = __builtin_amdgcn_readfirstlane(count_s) + 1u;
             if (lane == 0) {
-                *my_count = now;
+                store_through(my_count, now);
                 if (slice == 0)
                     __hip_atomic_store(p.flags + origin_s, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -306,7 +318,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
                 const uint32_t now = __builtin_amdgcn_readfirstlane(count) + 1u;
                 if (lane == 0) {
                     lds_phase[0] = now;
-                    p.counts[origin * (uint32_t)p.split_k + (uint32_t)slice] = now;
+                    store_through(p.counts + origin * (uint32_t)p.split_k + (uint32_t)slice, now);
                     if (slice == 0)
                         __hip_atomic_store(p.flags + origin, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
@@ -350,6 +362,52 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
 
     if constexpr (MODE == kAtomicPkF16Phase) {
         if (wave == 0 && lane == 0) lds_phase[1] = early;
+    }
+
+    // ---- two strips per wave, four waves (the launch the plan uses): the sum over the waves and
+    // the adds into C in as few instructions as possible behind the barrier, because one wave per
+    // SIMD runs them with nothing to overlap them with.  Every wave writes its whole [16][128]
+    // tile (rows >= m hold copies of row m - 1 and are never added); thread t then owns the column
+    // pair 2 (t % 64) of rows t / 64 + 4 i, i = 0..3: eight bytes at 8 t + 2048 i of every wave's
+    // tile, so all sixteen reads share one address register, and consecutive lanes add to
+    // consecutive words of one row of C.  The offsets into C are worked out before the barrier
+    // (the asm pins them there); rows >= m and columns >= n get an offset outside the buffer.
+    if constexpr (NS == 2 && kService) {
+        if (waves == 4) {
+            constexpr int kTileBytes = 16 * BN * 4;
+            constexpr uint32_t kOutside = 0xFFFFFF00u;
+            char* mine = lds_tiles + wave * kTileBytes + ((4 * (lane >> 4)) * BN + V * (lane & 15)) * 4;
+            uint32_t their_offset = 8u * (uint32_t)tid;
+            const rsrc_t rs_c = make_rsrc(p.C, (uint32_t)m * (uint32_t)n * 2u);
+            const int col = n0 + 2 * (tid & 63);
+            uint32_t off[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (tid >> 6) + 4 * i;
+                off[i] = (row < m && col < n) ? ((uint32_t)row * (uint32_t)n + (uint32_t)col) * 2u : kOutside;
+            }
+            asm volatile("" : "+v"(off[0]), "+v"(off[1]), "+v"(off[2]), "+v"(off[3]), "+v"(their_offset));
+            const char* theirs = lds_tiles + their_offset;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                *(float4_t*)(mine + r * BN * 4) = float4_t{acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+                *(float4_t*)(mine + r * BN * 4 + 16 * V * 4) = float4_t{acc1[0][r], acc1[1][r], acc1[2][r], acc1[3][r]};
+            }
+            __syncthreads();
+            float2 part[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) part[i][q] = *(const float2*)(theirs + q * kTileBytes + i * 2048);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float sx = (part[i][0].x + part[i][1].x) + (part[i][2].x + part[i][3].x);
+                const float sy = (part[i][0].y + part[i][1].y) + (part[i][2].y + part[i][3].y);
+                const half2_t h = {(_Float16)sx, (_Float16)sy};
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(h, rs_c, off[i], 0, 0);
+            }
+            return;
+        }
     }
 
     // ---- sum the waves' tiles through LDS.  acc[j][r] is row 4*(lane/16)+r, column V*(lane%16)+j.
@@ -433,8 +491,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
     };
     auto emit_pair = [&](const Unit& xa, const float (&sa)[EPU], const Unit& xb, const float (&sb)[EPU]) {
         if constexpr (MODE == kDirect) {
-            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sa[0], sa[1]), rs_out, xa.off, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sb[0], sb[1]), rs_out, xb.off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sa[0], sa[1]), rs_out, xa.off, 0, kWriteThrough);
+            __builtin_amdgcn_raw_buffer_store_b32(pack_half2(sb[0], sb[1]), rs_out, xb.off, 0, kWriteThrough);
         } else if constexpr (MODE == kAtomicPkF16 || MODE == kAtomicPkF16Phase || MODE == kAtomicPkF16Service) {
             const half2_t ha = {(_Float16)sa[0], (_Float16)sa[1]};
             const half2_t hb = {(_Float16)sb[0], (_Float16)sb[1]};
@@ -456,8 +514,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
             for (int i = 0; i < 2; ++i) {
                 float total = 0.f;
                 const size_t idx = (size_t)xs[i]->row * n + xs[i]->col;
-                if (xs[i]->ok && fixed_finish((uint64_t*)p.scratch + idx, old[i], mine[i], p.split_k, &total))
-                    p.C[idx] = (_Float16)total;
+                if (xs[i]->ok && fixed_finish((uint64_t*)p.scratch + idx, old[i], mine[i], p.split_k, &total)) {
+                    const _Float16 h = (_Float16)total;
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(uint16_t, h), rs_out, xs[i]->off, 0, kWriteThrough);
+                }
             }
         } else if constexpr (MODE == kAtomicF32) {
             if (xa.ok)
@@ -770,7 +830,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
         // and with it the zero stores issued before it have completed
         now = __builtin_amdgcn_readfirstlane(count) + 1u;
         if (lane == 0) {
-            p.counts[origin * (uint32_t)p.split_k + (uint32_t)slice] = now;
+            store_through(p.counts + origin * (uint32_t)p.split_k + (uint32_t)slice, now);
             if (slice == 0) __hip_atomic_store(p.flags + origin, now, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         published = true;
@@ -852,7 +912,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (MODE == kDirect) {
-                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, kWriteThrough);
             } else {
                 const half2_t h = {(_Float16)v[i].x, (_Float16)v[i].y};
                 __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(h, rs_c, off[i], 0, 0);
@@ -1005,7 +1065,7 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
         if (whole_tile) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v[i].x, v[i].y), rs_c, off[i], 0, kWriteThrough);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -2172,7 +2232,8 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     a.param_shift = param_shift;
     // LDS: 16 bytes for the phase word, then one [m, tile_cols] fp32 tile per wave, for the sum
     // over the workgroup's waves
-    a.lds_wave_bytes = (m * plan.tile_cols * 4 + 15) & ~15;
+    // (two strips per wave: whole 16-row tiles whatever m is, which the four-wave epilogue indexes with constants)
+    a.lds_wave_bytes = two_strips ? 16 * 128 * 4 : (m * plan.tile_cols * 4 + 15) & ~15;
     const size_t lds_bytes = 16 + (size_t)a.lds_wave_bytes * plan.waves;
     a.flags = nullptr;
     a.counts = nullptr;
