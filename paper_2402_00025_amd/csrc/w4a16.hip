@@ -851,8 +851,76 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     }
     stream_groups<D, 0, false, MT>(ring, a_in, a, sl, lm, tensors, magic, c, g_begin, acc, last_keep);
 
-    // ---- every wave's tile -> LDS (behind the chunks); after the barrier the k parts are added
-    // and the sums leave with consecutive lanes on consecutive column pairs
+    // ---- up to 16 rows: the tiles go to LDS and come back with consecutive lanes on consecutive
+    // column pairs, in as few instructions as possible behind the barrier (one wave per SIMD
+    // runs them with nothing to overlap them with).  Every wave stores its whole [16][64] tile
+    // (rows >= m are never added); thread t owns the column pair 2 (t % 128) of the workgroup's
+    // 256 columns and the rows t / 128 + (threads / 128) i, so its LDS reads share one address
+    // register with constant offsets and its offsets into C advance by a constant.  Rows >= m
+    // lie behind the end of the buffer by themselves; columns >= n get an offset that does.
+    if constexpr (MT == 1) {
+        constexpr int kWaveTile = 16 * 64 * 4;
+        constexpr uint32_t kFarOutside = 0x80000000u;  // stays outside when the row steps are added
+        char* tiles = lds_raw + p.wk * 2 * kChunkBytes;
+        char* mine = tiles + wave * kWaveTile + ((4 * (lane >> 4)) * 64 + 4 * (lane & 15)) * 4;
+        const int cp = tid & 127;
+        const int col = tile * kStreamTileCols + 2 * cp;
+        uint32_t src = (uint32_t)((cp >> 5) * kWaveTile + 8 * (cp & 31) + (tid >> 7) * 256);
+        uint32_t off0 = col < n ? ((uint32_t)(tid >> 7) * (uint32_t)n + (uint32_t)col) * 2u : kFarOutside;
+        asm volatile("" : "+v"(src), "+v"(off0));
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            *(float4_t*)(mine + r * 256) = float4_t{acc[0][0][r], acc[0][1][r], acc[0][2][r], acc[0][3][r]};
+        if constexpr (kPhase) {
+            if (wave == 0) {
+                // wave 0 holds the barrier until this call's zeros of the tile are in memory
+                bool seen = __builtin_amdgcn_readfirstlane(sample) == now;
+                int polls = 0;
+                while (!seen && polls < p.spin_limit) {
+                    for (int i = 0; i < p.probe_delay; ++i) __builtin_amdgcn_s_sleep(1);
+                    seen = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.flags + origin, __ATOMIC_RELAXED,
+                                                                            __HIP_MEMORY_SCOPE_AGENT)) == now;
+                    ++polls;
+                }
+                if (!seen && lane == 0)
+                    phase_wait_failed(p.errors, p.err_host, rs_c, (uint32_t)tile * (uint32_t)kStreamTileCols * 2u);
+            }
+        }
+        __syncthreads();
+        const char* theirs = tiles + src;
+        auto emit = [&](float2 v, uint32_t off) {
+            if constexpr (MODE == kDirect) {
+                __builtin_amdgcn_raw_buffer_store_b32(pack_half2(v.x, v.y), rs_c, off, 0, kWriteThrough);
+            } else {
+                const half2_t h = {(_Float16)v.x, (_Float16)v.y};
+                __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_v2f16(h, rs_c, off, 0, 0);
+            }
+        };
+        if (p.wk == 1) {
+            // 256 threads: rows t / 128 + 2 i
+            const uint32_t step = 4u * (uint32_t)n;
+            float2 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = *(const float2*)(theirs + 512 * i);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) emit(v[i], off0 + (uint32_t)i * step);
+        } else {
+            // 512 threads, two k parts: rows t / 128 + 4 i, the second part's tiles 16 KiB further on
+            const uint32_t step = 8u * (uint32_t)n;
+            float2 v[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = *(const float2*)(theirs + 1024 * i);
+                w[i] = *(const float2*)(theirs + 1024 * i + kStreamStrips * kWaveTile);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) emit(float2{v[i].x + w[i].x, v[i].y + w[i].y}, off0 + (uint32_t)i * step);
+        }
+        return;
+    }
+
+    // ---- more rows: every wave's tile -> LDS (behind the chunks); after the barrier the sums
+    // leave with consecutive lanes on consecutive column pairs
     float* red_all = (float*)(lds_raw + p.wk * 2 * (MT * kChunkBytes));
     float* red = red_all + (size_t)wave * m * 64;  // [m][64]
 #pragma unroll
@@ -2077,7 +2145,8 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
     a.param_shift = group_size == 256 ? 1 : 0;
     a.spin_limit = g_spin_limit;
     a.probe_delay = g_probe_delay;
-    const size_t lds_bytes = (size_t)wk * 2 * mt * kChunkBytes + (size_t)waves * m * 64 * 4;
+    // (one row tile: whole 16-row tiles whatever m is, which the epilogue indexes with constants)
+    const size_t lds_bytes = (size_t)wk * 2 * mt * kChunkBytes + (size_t)waves * (mt == 1 ? 16 : m) * 64 * 4;
     int mode = kDirect;
     if (split_k > 1) {
         if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) {
