@@ -20,10 +20,10 @@
  * that stream and return without synchronising; results are valid once the stream is.
  *
  * Limits: m >= 1.  The paper's regime is m <= 16.  More rows are served too: the SplitK entry
- * points with group_size 128 or 256 (and, for w4a16_gemm_ex, tile_cols 0 or 256, waves 0 or 4,
- * reduce AUTO, ATOMIC_PK_F16 or ATOMIC_PK_F16_PHASE) take up to 64 rows per launch as row tiles
- * that share one pass over the weights; everything else, the data-parallel kernel included,
- * runs one launch per 16 rows, each streaming the weights again.  n a multiple of 8;
+ * points of every field width with group_size 128 or 256 (and, for w4a16_gemm_ex, tile_cols 0 or
+ * 256, waves 0 or 4, reduce AUTO, ATOMIC_PK_F16 or ATOMIC_PK_F16_PHASE) take up to 64 rows per
+ * launch as row tiles that share one pass over the weights; everything else, the data-parallel
+ * kernel included, runs one launch per 16 rows, each streaming the weights again.  n a multiple of 8;
  * g (group_size) one of 32, 64, 128, 256; k a multiple of g; k * n < 2^32.  A split_k requested from w4a16_gemm must cut k into equal
  * shares of whole groups (k / split_k a multiple of g), as Algorithm 1 has it.  The library's own
  * choice (split_k == 0) and w4a16_gemm_ex are not bound by that: they deal out k in compute
@@ -130,6 +130,10 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
  */
 int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,
                        int m, int n, int k, int group_size, int workgroups, void* stream);
+/* The same decomposition for the other field widths (bits = 8, 3, 2 with the layouts described below; 4 is
+ * w4a16_gemm_streamk itself; W4A16_ERR_UNSUPPORTED for any other width). */
+int w4a16_gemm_streamk_bits(int bits, const void* A, const void* qweight, const void* scales, const void* qzeros,
+                            void* C, int m, int n, int k, int group_size, int workgroups, void* stream);
 
 /*
  * 8-bit fields (Section 2 of the paper remarks that the method carries over to other n-bit
@@ -139,7 +143,7 @@ int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, c
  *     qzeros   int32  [k / g, n / 4]     field i of word (gi, c) is z[gi][4c + i]
  * The launch is the library's (per-wave kernel, two strips per wave or streaming kernel for SplitK;
  * 16- to 64-column tiles for the data-parallel kernel; w4a16_plan_bits reports it); more than 16
- * rows run one launch per 16.  w8a16_algorithmic_bytes: qweight + scales + qzeros + A + C for
+ * rows as described above (row tiles of the streaming kernel for SplitK).  w8a16_algorithmic_bytes: qweight + scales + qzeros + A + C for
  * this layout.
  */
 int w8a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C,

@@ -27,7 +27,7 @@ EXPORTS = (
     "w4a16_release_scratch", "w4a16_phase_timeouts", "w8a16_gemm", "w8a16_gemm_dp", "w8a16_algorithmic_bytes",
     "w2a16_gemm", "w2a16_gemm_dp", "w2a16_algorithmic_bytes", "w3a16_gemm", "w3a16_gemm_dp", "w3a16_algorithmic_bytes", "w4a16_actorder_prepare", "w4a16_gemm_actorder",
     "w4a16_read_probe", "w4a16_gemm_static", "w4a16_set_phase_spin_limit", "w4a16_workspace_bytes",
-    "w4a16_set_workspace", "w4a16_reserve_scratch",
+    "w4a16_set_workspace", "w4a16_reserve_scratch", "w4a16_gemm_streamk_bits",
 )
 
 _lib = None
@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
     L.w4a16_set_workspace.argtypes = [vp, ctypes.c_longlong, ci, vp]
     L.w4a16_reserve_scratch.argtypes = [ci]
     L.w4a16_gemm_streamk.argtypes = [vp] * 5 + [ci] * 5 + [vp]
+    L.w4a16_gemm_streamk_bits.argtypes = [ci] + [vp] * 5 + [ci] * 5 + [vp]
     L.w8a16_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
     L.w8a16_gemm_dp.argtypes = [vp] * 5 + [ci] * 4 + [vp]
     L.w8a16_algorithmic_bytes.argtypes = [ci] * 4
@@ -210,6 +211,11 @@ def w4a16_read_probe(buffer, nbytes, shape=0, stream=None) -> None:
 def w4a16_gemm_streamk(A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups=0, stream=None) -> None:
     _check(lib().w4a16_gemm_streamk(_p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size,
                                     workgroups, _stream(stream)), "w4a16_gemm_streamk")
+
+
+def w4a16_gemm_streamk_bits(bits, A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups=0, stream=None) -> None:
+    _check(lib().w4a16_gemm_streamk_bits(bits, _p(A), _p(qweight), _p(scales), _p(qzeros), _p(C), m, n, k, group_size,
+                                         workgroups, _stream(stream)), "w4a16_gemm_streamk_bits")
 
 
 def w4a16_gemm_ex(A, qweight, scales, qzeros, C, m, n, k, group_size, split_k, tile_cols=0, waves=0, reduce=0,

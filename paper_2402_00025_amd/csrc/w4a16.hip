@@ -1041,6 +1041,7 @@ gemm_stream_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* s
 // to C with packed-fp16 atomics (C zeroed by the fill kernel); a segment that is a whole tile
 // is stored.  Segments have any length >= 1; an odd one runs a phantom group more, as in
 // stream_body.
+template <int BITS>
 __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_raw, int tile, int g_begin, int G,
                                                 int groups)
 {
@@ -1052,13 +1053,14 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     const int m = p.m, n = p.n, k = p.k;
     const int n0 = (tile * kStreamStrips + strip) * 64;
 
-    const LaneMap lm = make_lane_map<4>(lane, n0, m, n, k);
+    const LaneMap lm = make_lane_map<4, BITS>(lane, n0, m, n, k);
     const uint32_t qgroups = (uint32_t)groups >> p.param_shift;
     Tensors tensors;
     tensors.A = make_rsrc(p.A, (uint32_t)m * (uint32_t)k * 2u);
-    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(k / 8) * (uint32_t)n * 4u);
+    constexpr int kFields = BITS == 3 ? 1 : 32 / BITS;  // sizes written per width, as in gemm_body
+    tensors.qweight = make_rsrc(p.qweight, (uint32_t)(BITS == 3 ? k / 32 * 3 : k / kFields) * (uint32_t)n * 4u);
     tensors.scales = make_rsrc(p.scales, qgroups * (uint32_t)n * 2u);
-    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(n / 8) * 4u);
+    tensors.qzeros = make_rsrc(p.qzeros, qgroups * (uint32_t)(BITS == 3 ? n / 32 * 3 : n / kFields) * 4u);
     tensors.m = m;
     tensors.n = n;
     tensors.k = k;
@@ -1083,9 +1085,9 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    WeightRing<D> ring;
+    WeightRing<D, BITS> ring;
     ring_prime<D, 0>(ring, lm, tensors, g_begin);
-    *(half8_t*)(sl.ring + sl.wslot) = permute_activations(a_in[0][0]);
+    *(half8_t*)(sl.ring + sl.wslot) = order_activations<BITS>(a_in[0][0]);
     __syncthreads();
     u32x4_t a[1][4];
 #pragma unroll
@@ -1093,7 +1095,7 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     float4_t acc[1][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[0][j] = float4_t{0.f, 0.f, 0.f, 0.f};
-    const uint32_t magic = magic_1024x2();
+    const uint32_t magic = unpack_magic<BITS>();
 
     // an odd count is evened out by a phantom group whose product is dropped (see stream_body)
     const int Ge = (G + 1) & ~1;
@@ -1147,6 +1149,7 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
 // Kernel entry of the StreamK variant: 4 waves (one 256-column tile wide); `workgroups` is the
 // launch's grid size (an argument, so that no launch-geometry read is needed).
 //   packed = m | param_shift << 7
+template <int BITS>
 __global__ void __launch_bounds__(kWave* kStreamStrips)
 gemm_streamk_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros,
                     _Float16* C, int packed, int n, int k, int workgroups)
@@ -1172,7 +1175,7 @@ gemm_streamk_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* 
         const int g_begin = (int)(it - (long long)tile * groups);
         const long long rest = end - it;
         const int G = rest < groups - g_begin ? (int)rest : groups - g_begin;
-        streamk_segment(p, lds_raw, tile, g_begin, G, groups);
+        streamk_segment<BITS>(p, lds_raw, tile, g_begin, G, groups);
         it += G;
         __syncthreads();  // the next segment reuses the chunks and the tile in LDS
     }
@@ -1486,8 +1489,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // wave or the streaming kernel where the rules below find them, and narrow tiles for the
         // launches that do not split k
         if (tile_cols != 0 && tile_cols != 64) return W4A16_ERR_UNSUPPORTED;
-        if (m > 16) return W4A16_ERR_UNSUPPORTED;
-        bits_choice = !dp && tile_cols == 0 && waves == 0 && split_k == 0;
+        // more than 16 rows: the streaming kernel's row tiles (a SplitK launch with the library's tile and waves)
+        if (m > 16 && (dp || tile_cols != 0 || waves != 0 || m > 16 * kStreamMaxRowTiles)) return W4A16_ERR_UNSUPPORTED;
+        bits_choice = !dp && tile_cols == 0 && waves == 0 && split_k == 0 && m <= 16;
         const bool narrow = dp && tile_cols == 0;
         tile_cols = 64;
         if (narrow) {
@@ -1517,10 +1521,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const bool fills_once = tiles64 >= 190 && tiles64 <= 256;
     // Whether the two-strip launch further down is to be had for this shape (its conditions
     // other than who is asking).
-    const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (25ll << 20) : (32ll << 20))
+    // (beyond split_k = 8: 22 MiB since the streaming kernel's epilogue was shortened; n = 8184, k = 6144, m = 4:
+    // 8.2 us with two strips, 7.7 with 256 workgroups of the streaming kernel)
+    const long long two_strip_limit = bits == 4   ? (cgroups / 4 > 8 ? (22ll << 20) : (32ll << 20))
                                       : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
                                                   : (20ll << 20);
-    const bool two_strip_ok = m >= 2 && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
+    // (from one row on since the sum over the waves was shortened: 3 % ahead of the fixed-point launch at m = 1)
+    const bool two_strip_ok = m >= (bits == 4 ? 1 : 2) && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
                               (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) &&
                               cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 &&
                               (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
@@ -1536,15 +1543,18 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const bool short_k_tiles_fill = cgroups <= 28 && tiles64 >= 130 && tiles64 <= 256;
     const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 150));
     // (4-bit fields only: n = 2880, k = 2944 is 5-7 % slower that way at the other widths)
+    // (from five rows on: n = 2304, k = 3072, m = 1 takes 4.2 us that way and 3.5 with six slices of 64-column tiles)
     const bool narrow_tiles_fill =
-        bits == 4 && cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
+        bits == 4 && m >= 5 && cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
     // (the first of them up to k = 2176 from two rows on: a grid of n = 4608..8000, k = 1792 and 2176,
     // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
     // from k = 2560 on two strips per wave win where they are to be had)
     // (the other field widths: k = 2176 on 249 tiles of 32 columns is 15-42 % slower unsplit at 3 and 8 bits)
     const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
                           (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
-                          (m >= 5 && ((cgroups <= 24 && fills_once) || (m <= 12 && cgroups <= 50 && fills_once))) ||
+                          // (up to k = 3072 only since the streaming kernel's epilogue was shortened: n = 13936,
+                          // k = 6144, m = 12 and n = 15672, k = 4992, m = 6 are 7-9 % faster with four slices of it)
+                          (m >= 5 && ((cgroups <= 24 && fills_once) || (bits != 4 && m <= 12 && cgroups <= 50 && fills_once))) ||
                           (short_k_tiles_fill && !two_strips_there) || narrow_tiles_fill ||
                           // (more than 256 tiles up to k = 1664: level or up to 25 % ahead on n = 17280..28672)
                           (cgroups <= 13 && tiles64 > 256);
@@ -1584,9 +1594,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Streaming kernel (256-column tiles, activations shared through LDS): asked for by
     // tile_cols = 256, or chosen when the activation operand is large (m >= 5) and the weight
     // matrix is too big to be requested in one burst, provided the launch has enough workgroups.
-    if (!dp && ((bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) || bits_choice)) {
+    if (!dp && ((bits == 4 && (tile_cols == kStreamTileCols || (tile_cols == 0 && waves == 0))) || bits_choice ||
+                (bits != 4 && m > 16))) {
         // more than 16 rows come here only when the streaming kernel can take them
-        const bool asked = bits == 4 && (tile_cols == kStreamTileCols || m > 16);
+        const bool asked = (bits == 4 && tile_cols == kStreamTileCols) || m > 16;
         const int stiles = (n + kStreamTileCols - 1) / kStreamTileCols;
         const bool shape_ok = group_size == 128 || group_size == 256;
         const bool reduce_ok = reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16 ||
@@ -1623,6 +1634,19 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 }
             }
         }
+        // Where the count stays under 208 and eight waves (below) are not to be had, close to two
+        // workgroups per compute unit (440-512) is the next good place: n = 23752, k = 3840, m = 12:
+        // 465 workgroups take 12.6 us, 186 take 14.1 and 372 take 13.7; n = 16624, k = 14720, m = 16:
+        // 455 take 27.3, 195 take 28.7, 520 take 33.0.
+        bool two_per_unit = false;
+        if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && stiles * S < 208) {
+            const bool eight_to_be_had = bits != 8 && cgroups % (2 * S) == 0 && cgroups / (2 * S) >= 8;
+            int s2 = 512 / stiles < 32 ? 512 / stiles : 32;
+            if (!eight_to_be_had && s2 > S && stiles * s2 >= 440 && cgroups / s2 >= 4) {
+                S = s2;
+                two_per_unit = true;
+            }
+        }
         // Eight waves with the split as chosen, where that leaves compute units idle: a grid of 105
         // launches (43-125 column tiles, 150-256 workgroups, 8-16 groups per k part, m = 1, 6, 16) has
         // eight waves 7-17 % ahead of four at 156-180 workgroups, 4-13 % at 196-198, 0-7 % at 208,
@@ -1651,11 +1675,14 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (96ll << 20);
         // (or stays under 160 while the streaming kernel's slices keep five groups or more)
         const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
-        const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256)) &&
+        const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256) || two_per_unit) &&
                                  ((m >= 3 && weights_half >= (48ll << 20)) ||
-                                  // (any row count from 40 MiB on when 224-256 workgroups are to be had: 6-13 %
-                                  // ahead of one group per wave on six shapes of 44-73 MiB at m = 1, 2, 4)
-                                  (weights_half >= (40ll << 20) && stream_waves != 2 * kStreamStrips && stiles * S >= 224) ||
+                                  // (any row count from 16 MiB on when 224-256 workgroups are to be had: 6-13 %
+                                  // ahead of one group per wave on six shapes of 44-73 MiB at m = 1, 2, 4; 2-7 % on
+                                  // n = k = 8192 at m = 1, 4 and n = 8184, k = 6144 at m = 4 since the epilogue was shortened)
+                                  (weights_half >= ((bits == 4 ? 16ll : 40ll) << 20) && stream_waves != 2 * kStreamStrips &&
+                                   stiles * S >= 224 && stiles * S <= 256) ||
+                                  (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
                                    (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
@@ -1790,7 +1817,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     }
     if (reduce < W4A16_REDUCE_ATOMIC_F32 || reduce > W4A16_REDUCE_ATOMIC_PK_F16_PHASE) return W4A16_ERR_UNSUPPORTED;
     if (reduce == W4A16_REDUCE_ATOMIC_FIXED && split_k > 64) return W4A16_ERR_UNSUPPORTED;
-    if (reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE && !phase_split_ok(split_k)) return W4A16_ERR_UNSUPPORTED;
+    // (a launch that does not split k stores directly: whatever reduction is named is not used,
+    // so a plan that this function reported can be passed back as it is)
+    if (split_k > 1 && reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE && !phase_split_ok(split_k)) return W4A16_ERR_UNSUPPORTED;
     out->split_k = split_k;
     out->tile_cols = tile_cols;
     out->waves = waves;
@@ -2105,6 +2134,18 @@ static int launch_stream_tiles(const StreamArgs& a, size_t lds_bytes, int mode, 
     return launch_stream_mode<1, MT, BITS>(a, lds_bytes, mode, stream);
 }
 
+// mt row tiles of 16 activation rows share one pass over the weights, at every field width
+template <int BITS>
+static int launch_stream_rows(const StreamArgs& a, int mt, size_t lds_bytes, int mode, hipStream_t stream)
+{
+    switch (mt) {
+    case 1: return launch_stream_tiles<1, BITS>(a, lds_bytes, mode, stream);
+    case 2: return launch_stream_tiles<2, BITS>(a, lds_bytes, mode, stream);
+    case 3: return launch_stream_tiles<3, BITS>(a, lds_bytes, mode, stream);
+    default: return launch_stream_tiles<4, BITS>(a, lds_bytes, mode, stream);
+    }
+}
+
 // tile_cols = 256; waves = 4 * (k parts per workgroup), 4 or 8.  group_size 128 or 256.
 // m <= 64; more than 16 rows need waves = 4.
 static int run_stream(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
@@ -2112,7 +2153,6 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
                       int scratch_kind = kScratchLibrary)
 {
     if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
-    if (bits != 4 && m > 16) return W4A16_ERR_UNSUPPORTED;  // the other field widths: one row tile
     if (waves == 0) waves = kStreamStrips;
     if (waves != kStreamStrips && waves != 2 * kStreamStrips) return W4A16_ERR_UNSUPPORTED;
     const int wk = waves / kStreamStrips;
@@ -2170,14 +2210,11 @@ static int run_stream(const void* A, const void* qweight, const void* scales, co
             mode = kAtomicPkF16;
         }
     }
-    if (bits == 8) return launch_stream_tiles<1, 8>(a, lds_bytes, mode, stream);
-    if (bits == 3) return launch_stream_tiles<1, 3>(a, lds_bytes, mode, stream);
-    if (bits == 2) return launch_stream_tiles<1, 2>(a, lds_bytes, mode, stream);
-    switch (mt) {
-    case 1: return launch_stream_tiles<1>(a, lds_bytes, mode, stream);
-    case 2: return launch_stream_tiles<2>(a, lds_bytes, mode, stream);
-    case 3: return launch_stream_tiles<3>(a, lds_bytes, mode, stream);
-    default: return launch_stream_tiles<4>(a, lds_bytes, mode, stream);
+    switch (bits) {
+    case 8: return launch_stream_rows<8>(a, mt, lds_bytes, mode, stream);
+    case 3: return launch_stream_rows<3>(a, mt, lds_bytes, mode, stream);
+    case 2: return launch_stream_rows<2>(a, mt, lds_bytes, mode, stream);
+    default: return launch_stream_rows<4>(a, mt, lds_bytes, mode, stream);
     }
 }
 
@@ -2193,10 +2230,10 @@ static bool stream_rows_ok(int group_size, bool dp, int tile_cols, int waves, in
 // StreamK variant: `workgroups` persistent workgroups (0 = one per compute unit, the best count
 // in sweeps; capped by the number of iterations).  group_size 128 or 256; m <= 16 per launch.
 static int run_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
-                       int n, int k, int group_size, int workgroups, hipStream_t stream)
+                       int n, int k, int group_size, int workgroups, hipStream_t stream, int bits = 4)
 {
     if (group_size != 128 && group_size != 256) return W4A16_ERR_UNSUPPORTED;
-    if ((unsigned long long)k * (unsigned long long)n / 2 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
+    if ((unsigned long long)k * (unsigned long long)n * (unsigned)bits / 8 >= (1ull << 31)) return W4A16_ERR_UNSUPPORTED;
     const int groups = k / 128;
     const int tiles = (n + kStreamTileCols - 1) / kStreamTileCols;
     const long long total = (long long)tiles * groups;
@@ -2213,9 +2250,17 @@ static int run_streamk(const void* A, const void* qweight, const void* scales, c
     }
     const int packed = m | (group_size == 256 ? 1 : 0) << 7;
     const size_t lds_bytes = 2 * kChunkBytes + (size_t)kStreamStrips * m * 64 * 4;
-    hipLaunchKernelGGL(gemm_streamk_kernel, dim3((unsigned)workgroups), dim3(kStreamStrips * kWave), lds_bytes, stream,
-                       (const _Float16*)A, (const uint32_t*)qweight, (const _Float16*)scales,
-                       (const uint32_t*)qzeros, (_Float16*)C, packed, n, k, workgroups);
+    auto launch = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3((unsigned)workgroups), dim3(kStreamStrips * kWave), lds_bytes, stream,
+                           (const _Float16*)A, (const uint32_t*)qweight, (const _Float16*)scales,
+                           (const uint32_t*)qzeros, (_Float16*)C, packed, n, k, workgroups);
+    };
+    switch (bits) {
+    case 8: launch(gemm_streamk_kernel<8>); break;
+    case 3: launch(gemm_streamk_kernel<3>); break;
+    case 2: launch(gemm_streamk_kernel<2>); break;
+    default: launch(gemm_streamk_kernel<4>); break;
+    }
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -2255,8 +2300,7 @@ static int run_gemm(const void* A, const void* qweight, const void* scales, cons
     // row tiles of one launch, so the weights stream once per 64 rows; whatever it does not
     // cover (data-parallel kernel, group sizes below 128, the other tile widths and reductions)
     // runs as one launch per 16 rows.
-    const int rows_per_launch =
-        bits == 4 && stream_rows_ok(group_size, dp, tile_cols, waves, reduce) ? 16 * kStreamMaxRowTiles : 16;
+    const int rows_per_launch = stream_rows_ok(group_size, dp, tile_cols, waves, reduce) ? 16 * kStreamMaxRowTiles : 16;
     if (m > rows_per_launch) {
         for (int r = 0; r < m; r += rows_per_launch) {
             const int mm = m - r < rows_per_launch ? m - r : rows_per_launch;
@@ -2400,23 +2444,32 @@ int w4a16_gemm_dp(const void* A, const void* qweight, const void* scales, const 
                            true, stream);
 }
 
-int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
-                       int n, int k, int group_size, int workgroups, void* stream)
+int w4a16_gemm_streamk_bits(int bits, const void* A, const void* qweight, const void* scales, const void* qzeros,
+                            void* C, int m, int n, int k, int group_size, int workgroups, void* stream)
 {
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return W4A16_ERR_UNSUPPORTED;
     if (!A || !qweight || !scales || !qzeros || !C) return W4A16_ERR_NULL;
     w4a16::read_tuning_env();
     int rc = w4a16::check_args(m, n, k, group_size, 1);
     if (rc != W4A16_OK) return rc;
+    if ((bits == 2 && (n % 16) != 0) || (bits == 3 && (n % 32) != 0)) return W4A16_ERR_SHAPE;
     if (!w4a16::aligned16(A) || !w4a16::aligned16(qweight) || !w4a16::aligned16(scales) || !w4a16::aligned16(qzeros) ||
         !w4a16::aligned16(C))
         return W4A16_ERR_UNSUPPORTED;
     for (int r = 0; r < m; r += 16) {
         const int mm = m - r < 16 ? m - r : 16;
         rc = w4a16::run_streamk((const _Float16*)A + (size_t)r * k, qweight, scales, qzeros,
-                                (_Float16*)C + (size_t)r * n, mm, n, k, group_size, workgroups, (hipStream_t)stream);
+                                (_Float16*)C + (size_t)r * n, mm, n, k, group_size, workgroups, (hipStream_t)stream,
+                                bits);
         if (rc != W4A16_OK) return rc;
     }
     return W4A16_OK;
+}
+
+int w4a16_gemm_streamk(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m,
+                       int n, int k, int group_size, int workgroups, void* stream)
+{
+    return w4a16_gemm_streamk_bits(4, A, qweight, scales, qzeros, C, m, n, k, group_size, workgroups, stream);
 }
 
 int w8a16_gemm(const void* A, const void* qweight, const void* scales, const void* qzeros, void* C, int m, int n,
@@ -2565,8 +2618,9 @@ int w4a16_plan_bits(int bits, int m, int n, int k, int group_size, int dp, int* 
     if (rc != W4A16_OK) return rc;
     if ((bits == 2 && n % 16 != 0) || (bits == 3 && n % 32 != 0)) return W4A16_ERR_SHAPE;
     w4a16::Plan plan;
-    // more than 16 rows: the plan of each launch of 16
-    rc = w4a16::make_plan(m < 16 ? m : 16, n, k, group_size, dp != 0, dp ? 1 : req, 0, 0, W4A16_REDUCE_AUTO, &plan, bits);
+    // more rows than one launch takes (64 for SplitK with group_size 128 or 256, else 16): the plan of each launch
+    const int rows = w4a16::stream_rows_ok(group_size, dp != 0, 0, 0, W4A16_REDUCE_AUTO) ? 16 * w4a16::kStreamMaxRowTiles : 16;
+    rc = w4a16::make_plan(m < rows ? m : rows, n, k, group_size, dp != 0, dp ? 1 : req, 0, 0, W4A16_REDUCE_AUTO, &plan, bits);
     if (rc != W4A16_OK) return rc;
     if (split_k) *split_k = plan.split_k;
     if (tile_cols) *tile_cols = plan.tile_cols;

@@ -83,6 +83,9 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1000, 128, 0, None) == b.ERR_SHAPE
     assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1024, 64, 0, None) == b.ERR_UNSUPPORTED   # group_size
     assert L.w4a16_gemm_streamk(p, p, p, p, p, 1, 1024, 1024, 128, -2, None) == b.ERR_UNSUPPORTED  # workgroups
+    assert L.w4a16_gemm_streamk_bits(5, p, p, p, p, p, 1, 1024, 1024, 128, 0, None) == b.ERR_UNSUPPORTED   # width
+    assert L.w4a16_gemm_streamk_bits(3, p, p, p, p, p, 1, 1040, 1024, 128, 0, None) == b.ERR_SHAPE         # n % 32
+    assert L.w4a16_gemm_streamk_bits(2, p, None, p, p, p, 1, 1024, 1024, 128, 0, None) == b.ERR_NULL
     assert L.w8a16_gemm(p, p, None, p, p, 1, 1024, 1024, 128, 4, None) == b.ERR_NULL
     assert L.w8a16_gemm(p, p, p, p, p, 1, 1020, 1024, 128, 4, None) == b.ERR_SHAPE
     assert L.w8a16_gemm(p, p, p, p, p, 1, 1024, 1024, 128, 3, None) == b.ERR_SPLIT
@@ -118,6 +121,19 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_set_phase_spin_limit(0) == b.OK
 
 
+def test_reported_plans_can_be_passed_back():
+    """Whatever launch w4a16_plan reports for a shape is accepted, unchanged, when it is given
+    explicitly (a data-parallel shaped launch names a reduction it does not use)."""
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for _ in range(1500):
+        m = int(rng.integers(1, 17))
+        n = int(rng.integers(1, 3600)) * 8
+        k = int(rng.integers(1, 120)) * 128
+        pl = b.w4a16_plan(m, n, k, 128)
+        assert b.w4a16_plan(m, n, k, 128, **pl) == pl, (m, n, k, pl)
+
+
 def test_workspace_size():
     """w4a16_workspace_bytes: 0 for a bad n_max, otherwise the documented layout (head, tickets,
     phase levels of split_k 2..64, fp32 sums and fixed-point words for sixteen rows)."""
@@ -144,7 +160,7 @@ def test_plan_is_consistent():
                 kparts = pl["waves"] // 4 if pl["tile_cols"] == 256 else pl["waves"]
                 assert (groups // pl["split_k"]) % kparts == 0
                 if pl["tile_cols"] == 256:
-                    assert not dp and nk >= 8192 and (m >= 8 or nk >= 16384)
+                    assert not dp and nk >= 8192
                 if dp:
                     assert pl["split_k"] == 1
     # a requested split is kept

@@ -651,6 +651,105 @@ def test_8bit_full_size(oracle):
     assert_parity(p.result(), Cref, "8-bit dp 4096^2")
 
 
+# ------------------------------------------------------------------ more than 16 rows at the other field widths
+def _case_and_ref(oracle, bits, m, n, k, g, seed):
+    if bits == 3:
+        A, qw, s, qz = random_case_3bit(m, n, k, g, seed=seed)
+        return A, qw, s, qz, oracle.gemm_3bit(A, qw, s, qz, g)[0]
+    A, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=seed)
+    return A, qw, s, qz, oracle.gemm_bits(A, qw, s, qz, g, bits)[0]
+
+
+@pytest.mark.parametrize("bits", [8, 3, 2])
+@pytest.mark.parametrize("m,n,k,g,split_k", [
+    (17, 288, 1024, 128, 0),      # two row tiles, the second with one row; ragged last column tile
+    (40, 544, 2048, 128, 4),      # three row tiles
+    (64, 288, 1408, 128, 0),      # four row tiles, 11 groups (uneven shares)
+    (33, 320, 1024, 256, 2),      # group_size 256
+    (150, 288, 1024, 128, 2),     # three launches of 64, 64 and 22 rows
+    (48, 288, 512, 64, 2),        # group_size 64: one launch per 16 rows
+])
+def test_row_tiles_other_field_widths(oracle, bits, m, n, k, g, split_k):
+    """Up to 64 rows share one pass over the weights (row tiles of the streaming kernel) at 8-, 3-
+    and 2-bit fields as well; each width against its own oracle function."""
+    A, qw, s, qz, Cref = _case_and_ref(oracle, bits, m, n, k, g, seed=1300 + bits + m)
+    p = DeviceProblem(A, qw, s, qz, g)
+    gemm = {8: b.w8a16_gemm, 3: b.w3a16_gemm, 2: b.w2a16_gemm}[bits]
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        gemm(*p.args(), split_k)
+        assert_parity(p.result(), Cref, f"{bits}-bit m={m} n={n} k={k} g={g} S={split_k} call {call}")
+    pl = b.w4a16_plan_bits(bits, m, n, k, g, split_k=split_k)
+    assert pl["tile_cols"] == (256 if g >= 128 else 64)     # the plan of one launch: row tiles where the streaming kernel takes them
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("bits", [8, 3, 2])
+def test_row_tiles_other_field_widths_one_hot_bit_exact(bits):
+    """One non-zero term per row, 64 rows at a time, swept over all k: the row tiles' operands, the
+    field order and the parameters of every width, bit for bit."""
+    import torch
+    m, n, k, g = 64, 288, 1024, 128
+    if bits == 3:
+        _, qw, s, qz = random_case_3bit(m, n, k, g, seed=77)
+        W = np_dense_weight_3bit(qw, s, qz, g)
+    else:
+        _, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=77)
+        W = np_dense_weight_bits(qw, s, qz, g, bits)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    gemm = {8: b.w8a16_gemm, 3: b.w3a16_gemm, 2: b.w2a16_gemm}[bits]
+    for base in range(0, k, m):
+        rows = [(base + 5 * i) % k for i in range(m)]
+        A = np.zeros((m, k), np.float16)
+        for i, r in enumerate(rows):
+            A[i, r] = 1.0
+        p.A.copy_(torch.from_numpy(A))
+        gemm(*p.args(), 4)
+        got = p.result()
+        assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), (bits, base)
+
+
+# ------------------------------------------------------------------ StreamK at the other field widths
+@pytest.mark.parametrize("bits", [8, 3, 2])
+@pytest.mark.parametrize("m,n,k,g,workgroups", [
+    (16, 544, 1024, 128, 0),      # library default (capped by the iterations)
+    (5, 544, 1408, 128, 7),       # segments across tiles, odd group counts
+    (16, 288, 2048, 256, 3),      # group_size 256
+    (20, 800, 1024, 128, 24),     # two launches of 16 and 4 rows; ragged last tile
+    (1, 288, 512, 128, 2),        # whole tiles per workgroup: no fill launch
+])
+def test_streamk_other_field_widths(oracle, bits, m, n, k, g, workgroups):
+    A, qw, s, qz, Cref = _case_and_ref(oracle, bits, m, n, k, g, seed=1400 + bits + m)
+    p = DeviceProblem(A, qw, s, qz, g)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm_streamk_bits(bits, *p.args(), workgroups)
+        assert_parity(p.result(), Cref, f"streamk {bits}-bit m={m} n={n} k={k} g={g} W={workgroups} call {call}")
+
+
+@pytest.mark.parametrize("bits", [8, 3, 2])
+def test_streamk_other_field_widths_one_hot_bit_exact(bits):
+    import torch
+    m, n, k, g = 16, 544, 1024, 128
+    if bits == 3:
+        _, qw, s, qz = random_case_3bit(m, n, k, g, seed=78)
+        W = np_dense_weight_3bit(qw, s, qz, g)
+    else:
+        _, qw, s, qz = random_case_bits(m, n, k, g, bits, seed=78)
+        W = np_dense_weight_bits(qw, s, qz, g, bits)
+    p = DeviceProblem(np.zeros((m, k), np.float16), qw, s, qz, g)
+    for workgroups in (5, 16):
+        for base in range(0, k, m):
+            rows = [(base + 7 * i) % k for i in range(m)]
+            A = np.zeros((m, k), np.float16)
+            for i, r in enumerate(rows):
+                A[i, r] = 1.0
+            p.A.copy_(torch.from_numpy(A))
+            b.w4a16_gemm_streamk_bits(bits, *p.args(), workgroups)
+            got = p.result()
+            assert np.array_equal(got.view(np.uint16), W[rows, :].astype(np.float16).view(np.uint16)), (bits, workgroups, base)
+
+
 # ------------------------------------------------------------------ 2-bit fields
 TWO_BIT = [
     # m, n, k, g, split_k   (n a multiple of 16)

@@ -53,7 +53,8 @@ def test_static_entry_two_calls_second_smaller(oracle):
     _pair(oracle, 16, 4096, 4096, 0, 0, exact=False)
     _pair(oracle, 16, 1032, 2048, 4, 1, exact=False)
     # up to four rows: fixed-point words in the static array
-    _pair(oracle, 1, 4096, 4096, 0, 2, exact=True)
+    _pair(oracle, 1, 4096, 4096, 4, 2, exact=True)     # a given split: 64-column tiles, fixed-point words
+    _pair(oracle, 1, 4096, 4096, 0, 6, exact=False)    # the library's split: two strips per wave at one row as well
     _pair(oracle, 3, 1024, 1024, 4, 3, exact=True)
     # the streaming kernel's protocol (a larger matrix), then a small one again
     _pair(oracle, 8, 8192, 8192, 0, 4, exact=False)
