@@ -1544,14 +1544,21 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 150));
     // (4-bit fields only: n = 2880, k = 2944 is 5-7 % slower that way at the other widths)
     // (from five rows on: n = 2304, k = 3072, m = 1 takes 4.2 us that way and 3.5 with six slices of 64-column tiles)
+    // (the same on 170-256 tiles of 32 columns up to k = 3200: a grid of n = 5600..8000, k = 2304..3200 where k / 128
+    // is no multiple of four, m = 6, 16 has eight waves per tile 5-32 % ahead of what was chosen before, and within
+    // 3 % of the best launch except at n = 5600, m = 16 from k = 2816 on, 6-7 %)
     const bool narrow_tiles_fill =
-        bits == 4 && m >= 5 && cgroups <= 26 && dp_cols == 16 && dp_tiles >= 130 && dp_tiles <= 256 && !two_strip_ok;
+        bits == 4 && m >= 5 && dp_tiles <= 256 && !two_strip_ok &&
+        ((dp_cols == 16 && cgroups <= 26 && dp_tiles >= 130) || (dp_cols == 32 && cgroups <= (m <= 12 ? 25 : 22) && dp_tiles >= 170));
     // (the first of them up to k = 2176 from two rows on: a grid of n = 4608..8000, k = 1792 and 2176,
     // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
     // from k = 2560 on two strips per wave win where they are to be had)
     // (the other field widths: k = 2176 on 249 tiles of 32 columns is 15-42 % slower unsplit at 3 and 8 bits)
     const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
-                          (cgroups <= 17 && tiles64 >= 130 && tiles64 <= 256) ||
+                          // (from 120 tiles on: n = 8216, k = 1920, m = 4, 16: 129 tiles unsplit are 17 % ahead of two slices)
+                          (cgroups <= 17 && tiles64 >= 120 && tiles64 <= 256) ||
+                          // (k up to 1408 from 100 narrow tiles on: n = 1704..2000, m = 1..16: 27-45 % ahead of two slices)
+                          (cgroups <= 11 && dp_tiles >= 100 && dp_tiles <= 256) ||
                           // (up to k = 3072 only since the streaming kernel's epilogue was shortened: n = 13936,
                           // k = 6144, m = 12 and n = 15672, k = 4992, m = 6 are 7-9 % faster with four slices of it)
                           (m >= 5 && ((cgroups <= 24 && fills_once) || (bits != 4 && m <= 12 && cgroups <= 50 && fills_once))) ||
@@ -1562,7 +1569,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // the launch of the data-parallel kernel (the other field widths as well: on 36 random shapes
         // with k up to 3712 their launches became 3-5 % faster on average, up to 35 % on narrow tiles)
         const int tc = dp_cols;
-        const int wv = tc < 64 && m <= 12 ? 8 : 4;
+        // (eight waves per narrow tile beyond twelve rows too once k is long: 3-5 % at k = 2304..2816, m = 16)
+        const int wv = tc < 64 && (m <= 12 || cgroups >= 18) ? 8 : 4;
         out->split_k = 1;
         out->tile_cols = tc;
         out->waves = cgroups < wv ? largest_wave_split(cgroups, 1, wv) : wv;
@@ -1616,11 +1624,12 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 S *= 2;
             // A split_k that is no power of two fills the machine where the powers of two leave it
             // under-filled or spill over it: the largest one with at most 256 workgroups, if that
-            // gives 200 or more and runs of four groups or more (n = 5120, k = 13824: 12 slices, 240
-            // workgroups, 11.6 us against 12.8 with 8 slices).
+            // gives 192 or more and runs of two groups or more (n = 5120, k = 13824: 12 slices, 240
+            // workgroups, 11.6 us against 12.8 with 8 slices; n = 4800, k = 4864, m = 8: 12 slices of
+            // three groups, 6.7 us, against 7.2 from the per-wave kernel).
             const int s_fill = 256 / stiles < 32 ? 256 / stiles : 32;
             const bool fill = s_fill >= 3 && (s_fill & (s_fill - 1)) != 0 && stiles * s_fill >= 192 &&
-                              (stiles * S < 224 || stiles * S > 256) && cgroups / s_fill >= 4;
+                              (stiles * S < 224 || stiles * S > 256) && cgroups / s_fill >= 2;
             if (fill) S = s_fill;
             // Where that count sits badly on 256 compute units (under 200 or over 256), 128-192
             // workgroups of eight waves do better, if each of their two k parts gets a long run
@@ -1635,14 +1644,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             }
         }
         // Where the count stays under 208 and eight waves (below) are not to be had, close to two
-        // workgroups per compute unit (440-512) is the next good place: n = 23752, k = 3840, m = 12:
-        // 465 workgroups take 12.6 us, 186 take 14.1 and 372 take 13.7; n = 16624, k = 14720, m = 16:
-        // 455 take 27.3, 195 take 28.7, 520 take 33.0.
+        // workgroups per compute unit (416-512) is the next good place, from 40 MiB of packed weights on:
+        // n = 23752, k = 3840, m = 12: 465 workgroups take 12.6 us, 186 take 14.1 and 372 take 13.7;
+        // n = 16624, k = 14720, m = 16: 455 take 27.3, 195 take 28.7, 520 take 33.0; n = 22232, k = 7808
+        // or 11136, m = 4..16: 435 are 10 % ahead of 174.  (n = 16960, k = 4352, 35 MiB, m = 12: 469 take
+        // 12.5 us, 201 take 11.4.)
         bool two_per_unit = false;
-        if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && stiles * S < 208) {
+        if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && stiles * S < 208 &&
+            weights_half >= (40ll << 20)) {
             const bool eight_to_be_had = bits != 8 && cgroups % (2 * S) == 0 && cgroups / (2 * S) >= 8;
             int s2 = 512 / stiles < 32 ? 512 / stiles : 32;
-            if (!eight_to_be_had && s2 > S && stiles * s2 >= 440 && cgroups / s2 >= 4) {
+            if (!eight_to_be_had && s2 > S && stiles * s2 >= 416 && cgroups / s2 >= 4) {
                 S = s2;
                 two_per_unit = true;
             }
@@ -1672,7 +1684,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         const int pw_blocks = tiles64 * (pw_parts >= 4 ? pw_parts / 4 : 1);
         // (one group per wave: below 96 MiB; n = 21192, k = 11264, 113 MiB, m = 1, 2: 7300 workgroups
         // of it take 28-29 us, 249 of the streaming kernel 23.6)
-        const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (96ll << 20);
+        // (below 40 MiB since the streaming epilogue was shortened: n = 23064, k = 8192, 90 MiB, m = 1: 22.6 us
+        // against 19.9 with 182 workgroups of eight waves; n = 25112, k = 4096, 49 MiB, m = 2: 14.7 against
+        // 12.5; n = 12288, k = 4096, 24 MiB, m = 1 is the largest shape seen where one group per wave leads)
+        const bool pw_one_group = bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && weights_half < (40ll << 20);
         // (or stays under 160 while the streaming kernel's slices keep five groups or more)
         const bool pw_bad = (pw_blocks > 256 || (pw_blocks < g_stream_min_blocks && cgroups / S >= 5)) && !pw_one_group;
         const bool few_rows_ok = (stream_waves == 2 * kStreamStrips || (stiles * S >= 192 && stiles * S <= 256) || two_per_unit) &&
@@ -1680,7 +1695,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                   // (any row count from 16 MiB on when 224-256 workgroups are to be had: 6-13 %
                                   // ahead of one group per wave on six shapes of 44-73 MiB at m = 1, 2, 4; 2-7 % on
                                   // n = k = 8192 at m = 1, 4 and n = 8184, k = 6144 at m = 4 since the epilogue was shortened)
-                                  (weights_half >= ((bits == 4 ? 16ll : 40ll) << 20) && stream_waves != 2 * kStreamStrips &&
+                                  // (from three rows on below 40 MiB: at one row the fixed-point launches stay 1-9 % ahead)
+                                  (weights_half >= ((bits == 4 && m >= 3 ? 16ll : 40ll) << 20) && stream_waves != 2 * kStreamStrips &&
                                    stiles * S >= 224 && stiles * S <= 256) ||
                                   (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
@@ -1756,6 +1772,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         int parts = 1;  // k parts of a column tile = split_k * waves
         if (packed_bytes <= (8ll << 20)) {
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
+            // one group per wave where that fits although no power of two gets there (n = 2304, k = 3072,
+            // m = 1: six slices of four waves take 3.5 us, four slices with two groups per wave 4.3)
+            if (cgroups % 4 == 0 && tiles * cgroups <= 2048) parts = cgroups;
         } else {
             // four waves per workgroup and the fewest k slices that give 160 workgroups
             // (group sizes below 128 make the groups short and the parameter traffic large: sweeps
@@ -1780,7 +1799,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             const int blocks = tiles * (parts >= 4 ? parts / 4 : 1);
             if (group_size < 128) {
                 // as chosen above
-            } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (96ll << 20) &&
+            } else if (bits == 4 && m <= 4 && cgroups % 4 == 0 && cgroups / 4 <= 64 && packed_bytes < (40ll << 20) &&
                        (blocks < 200 || blocks > 256)) {
                 parts = cgroups;
             } else if (blocks > 256) {

@@ -159,6 +159,8 @@ def main(argv=None):
              "# launch = S<split_k>/t<tile_cols>/w<waves>/r<reduce>"]
     ratios = []
     for (m, n, k) in shapes:
+        if m < 1 or n < 8 or n % 8 or k < 128 or k % 128:
+            raise SystemExit(f"shape {m},{n},{k}: need m >= 1, n a multiple of 8, k a multiple of 128")
         p = Problem(torch, m, n, k)
         plan = binding.w4a16_plan(m, n, k, 128)
         cands = candidates(binding, m, n, k)
