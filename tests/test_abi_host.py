@@ -335,3 +335,27 @@ def test_input_generator_shapes_and_determinism():
     assert 0.001 <= float(x.scales.min()) and float(x.scales.max()) <= 0.01
     z = inputs.make_inputs(3, 64, 256, 128, seed=6)
     assert z.qweight.tobytes() != x.qweight.tobytes()
+
+
+def test_large_shape_parity_cases_cover_every_launch_kind():
+    """The full-size parity cases (seeded random shapes plus the shapes that moved a plan rule)
+    reach every kind of launch the plan can choose."""
+    import numpy as np
+    rng = np.random.Generator(np.random.Philox(77))
+    shapes = []
+    while len(shapes) < 20:
+        n = int(rng.integers(128, 3600)) * 8
+        k = int(rng.integers(8, 120)) * 128
+        m = int(rng.choice([1, 2, 4, 6, 8, 12, 16]))
+        if n * k <= (1 << 27):
+            shapes.append((m, n, k))
+    shapes += [(2, 25112, 4096), (8, 22232, 7808), (1, 2304, 3072), (6, 7216, 2304), (16, 8216, 1920),
+               (4, 1864, 1408), (12, 4248, 2688), (1, 23064, 8192)]
+    kinds = set()
+    for (m, n, k) in shapes:
+        pl = b.w4a16_plan(m, n, k, 128)
+        kinds.add((pl["tile_cols"], pl["waves"], pl["split_k"] > 1, pl["reduce"] if pl["split_k"] > 1 else 0))
+    assert {kd[0] for kd in kinds} >= {16, 32, 64, 128, 256}, kinds
+    assert (256, 8, True, b.REDUCE_ATOMIC_PK_F16_PHASE) in kinds, kinds
+    assert (64, 4, True, b.REDUCE_ATOMIC_FIXED) in kinds, kinds
+    assert any(kd[0] == 64 and not kd[2] for kd in kinds), kinds

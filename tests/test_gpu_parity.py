@@ -1114,6 +1114,60 @@ def test_random_shapes_library_plan(oracle, m, n, k, g):
     assert b.w4a16_phase_timeouts() == 0
 
 
+def _random_large_shapes(count, seed):
+    """Shapes of the size the plan's rules are about (n up to 28800, k up to 15232, up to 64 MiB
+    of packed weights so that the oracle stays at about a second per shape)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    out = []
+    while len(out) < count:
+        n = int(rng.integers(128, 3600)) * 8
+        k = int(rng.integers(8, 120)) * 128
+        m = int(rng.choice([1, 2, 4, 6, 8, 12, 16]))
+        if n * k <= (1 << 27):
+            out.append((m, n, k))
+    return out
+
+
+# shapes on which an audit of the plan moved a rule: eight-wave streaming workgroups at two rows,
+# close to two workgroups per compute unit, six slices of one group per wave, unsplit 32- and
+# 64-column tiles with a long k, 129 tiles
+_PLAN_RULE_SHAPES = [(2, 25112, 4096), (8, 22232, 7808), (1, 2304, 3072), (6, 7216, 2304), (16, 8216, 1920),
+                     (4, 1864, 1408), (12, 4248, 2688), (1, 23064, 8192)]
+
+
+@pytest.mark.parametrize("m,n,k", _random_large_shapes(20, seed=77) + _PLAN_RULE_SHAPES)
+def test_random_large_shapes_library_plan(oracle, m, n, k):
+    """The launch the library picks at full-size shapes (every branch of the plan: narrow unsplit
+    tiles, 64-column tiles with fixed-point adds, two strips, the streaming kernel with four and
+    eight waves) against the oracle, twice in a row (the in-kernel zeroing counts calls)."""
+    A, qw, s, qz = random_case(m, n, k, 128, seed=m + n + k)
+    Cref, _ = oracle.gemm(A, qw, s, qz, 128)
+    p = DeviceProblem(A, qw, s, qz, 128)
+    plan = b.w4a16_plan(m, n, k, 128)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        b.w4a16_gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"m={m} n={n} k={k} call {call} plan {plan}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
+@pytest.mark.parametrize("bits", [8, 3, 2])
+@pytest.mark.parametrize("m,n,k", [(m, n // 32 * 32, k) for (m, n, k) in _random_large_shapes(8, seed=78)] +   # a zero-point word holds 32 / bits columns
+                         [(16, 15392, 2048), (9, 8192, 8192), (20, 13312, 4096)])
+def test_random_large_shapes_other_field_widths(oracle, bits, m, n, k):
+    """The same at 8-, 3- and 2-bit fields, whose plans have their own bounds; each width against its
+    own oracle function."""
+    A, qw, s, qz, Cref = _case_and_ref(oracle, bits, m, n, k, 128, seed=bits + m + n + k)
+    p = DeviceProblem(A, qw, s, qz, 128)
+    gemm = {8: b.w8a16_gemm, 3: b.w3a16_gemm, 2: b.w2a16_gemm}[bits]
+    plan = b.w4a16_plan_bits(bits, m, n, k, 128)
+    for call in range(2):
+        p.C.fill_(float("nan"))
+        gemm(*p.args(), 0)
+        assert_parity(p.result(), Cref, f"{bits}-bit m={m} n={n} k={k} call {call} plan {plan}")
+    assert b.w4a16_phase_timeouts() == 0
+
+
 @pytest.mark.parametrize("m,n,k,split_k,tile_cols,waves", [
     (16, 8192, 2048, 0, 0, 0),       # two strips per wave by the plan, split_k 4
     (8, 16400, 1024, 0, 0, 0),       # two strips, split_k 2, ragged last tile
