@@ -359,3 +359,32 @@ def test_large_shape_parity_cases_cover_every_launch_kind():
     assert (256, 8, True, b.REDUCE_ATOMIC_PK_F16_PHASE) in kinds, kinds
     assert (64, 4, True, b.REDUCE_ATOMIC_FIXED) in kinds, kinds
     assert any(kd[0] == 64 and not kd[2] for kd in kinds), kinds
+
+
+def test_plan_invariants_on_random_shapes():
+    """Properties every launch the library chooses has, over 6000 random shapes and all field
+    widths: the split fits k and the reduction's limits, two strips come with one group per wave,
+    fixed-point adds only up to four rows, and the streaming kernel's workgroup count stays where
+    the measurements put it (at most 256, or close to two per compute unit), never just above 256."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for _ in range(6000):
+        bits = int(rng.choice([4, 4, 8, 3, 2]))
+        m = int(rng.integers(1, 65))
+        n = int(rng.integers(1, 3600)) * 32
+        k = int(rng.integers(1, 120)) * 128
+        pl = b.w4a16_plan(m, n, k, 128) if bits == 4 else b.w4a16_plan_bits(bits, m, n, k, 128)
+        what = (bits, m, n, k, pl)
+        groups = k // 128
+        S, tc, w, r = pl["split_k"], pl["tile_cols"], pl["waves"], pl["reduce"]
+        assert 1 <= S <= min(groups, 64) and tc in (16, 32, 64, 128, 256) and 1 <= w <= 16, what
+        kparts = w // 4 if tc == 256 else w
+        assert S * kparts <= groups, what
+        workgroups = -(-n // tc) * S
+        if tc == 256 and S > 1:
+            assert workgroups <= 256 or 416 <= workgroups <= 512, what
+        if tc == 128:
+            assert w == 4 and S * 4 == groups, what
+        if S > 1:
+            assert r in (b.REDUCE_ATOMIC_PK_F16, b.REDUCE_ATOMIC_FIXED, b.REDUCE_ATOMIC_PK_F16_PHASE), what
+            assert r != b.REDUCE_ATOMIC_FIXED or m <= 4, what
