@@ -136,7 +136,7 @@ __device__ __forceinline__ void phase_wait_failed(uint32_t* errors, uint32_t* er
 }
 
 // One workgroup = WAVES wavefronts that share one output tile [m, 16 V] and divide the
-// workgroup's k range between them; blockIdx.x = slice * tiles + tile.
+// workgroup's k range between them; blockIdx = (tile, slice), dispatched as slice * tiles + tile.
 //
 // MODE kDirect       the workgroup owns the tile alone (data-parallel kernel, or split_k == 1):
 //                    its sum is rounded once to fp16 and stored.
@@ -208,10 +208,14 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p)
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // uniform: keeps offsets scalar
     const int waves = nthreads / kWave;
-    const int tile = blockIdx.x % p.tiles;
-    const int slice = blockIdx.x / p.tiles;
+    // grid = (tiles, split_k): the same dispatch order as slice * tiles + tile, without a division
+    // at the head of every wave
+    const int tile = blockIdx.x;
+    const int slice = blockIdx.y;
     const int n0 = tile * BN;
     const int m = p.m, n = p.n, k = p.k;
+    // (the host has checked the shape: divisions by constants become single shifts)
+    __builtin_assume(m > 0 && n > 0 && k > 0);
 
     if constexpr (kService) {
         if (wave == waves) {
@@ -690,7 +694,7 @@ gemm_kernel(const _Float16* A, const uint32_t* qweight, const _Float16* scales, 
 }
 
 // Streaming SplitK kernel: the four column strips of a workgroup share their activations
-// through LDS (see w4a16_stream.hpp).  blockIdx.x = tile * split_k + slice: consecutive
+// through LDS (see w4a16_stream.hpp).  blockIdx = (slice, tile), dispatched as tile * split_k + slice: consecutive
 // workgroups go to consecutive compute dies, so with split_k a multiple of 8 every die reads
 // only its own k slices of A.
 //
@@ -716,9 +720,13 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
     const int nthreads = kStreamStrips * p.wk * kWave;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int slice = blockIdx.x % p.split_k;
-    const int tile = blockIdx.x / p.split_k;
+    // grid = (split_k, tiles): the same dispatch order as tile * split_k + slice, without a division
+    // at the head of every wave
+    const int slice = blockIdx.x;
+    const int tile = blockIdx.y;
     const int m = p.m, n = p.n, k = p.k;
+    // (the host has checked the shape: divisions by constants become single shifts)
+    __builtin_assume(m > 0 && n > 0 && k > 0);
 
     const int strip = wave & (kStreamStrips - 1);
     const int kpart = wave / kStreamStrips;
@@ -777,7 +785,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p)
             a_in[h][rt] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff[rt],
                                                                 sl.a_soff0 + (uint32_t)h * 256u, 0);
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
+    // (the bare barrier: nothing in LDS is handed over here, and the fence of __syncthreads would
+    // wait for every scalar load in flight, the second batch of kernel arguments among them)
+    __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     WeightRing<D, BITS> ring;
     ring_prime<D, 0>(ring, lm, tensors, g_begin);
@@ -1051,6 +1061,8 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     const int lane = tid & (kWave - 1);
     const int strip = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int m = p.m, n = p.n, k = p.k;
+    // (the host has checked the shape: divisions by constants become single shifts)
+    __builtin_assume(m > 0 && n > 0 && k > 0);
     const int n0 = (tile * kStreamStrips + strip) * 64;
 
     const LaneMap lm = make_lane_map<4, BITS>(lane, n0, m, n, k);
@@ -1083,7 +1095,9 @@ __device__ __forceinline__ void streamk_segment(const StreamArgs& p, char* lds_r
     for (int h = 0; h < D; ++h)
         a_in[h][0] = __builtin_amdgcn_raw_buffer_load_b128(tensors.A, sl.a_voff[0], sl.a_soff0 + (uint32_t)h * 256u, 0);
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
+    // (the bare barrier: nothing in LDS is handed over here, and the fence of __syncthreads would
+    // wait for every scalar load in flight, the second batch of kernel arguments among them)
+    __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     WeightRing<D, BITS> ring;
     ring_prime<D, 0>(ring, lm, tensors, g_begin);
@@ -1983,10 +1997,10 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
                                            (int)lds_bytes)))
             return W4A16_ERR_HIP;
     }
-    const unsigned grid = (unsigned)(a.tiles * a.split_k);
     const unsigned threads = (unsigned)(waves + (MODE == kAtomicPkF16Service ? 1 : 0)) * kWave;
+    // (the second grid dimension holds at most 65535)
     if (a.m > 31 || a.param_shift > 3 || a.waves > 31 || a.groups_base >= (1 << 20) || a.tiles >= (1 << 20) ||
-        a.groups_rem >= (1 << 11))
+        a.groups_rem >= (1 << 11) || a.split_k < 1 || a.split_k >= (1 << 16))
         return W4A16_ERR_UNSUPPORTED;
     const int packed = a.m | a.param_shift << 5 | a.waves << 7 | (int)((unsigned)a.groups_base << 12);
     const int tiles_rem = a.tiles | a.groups_rem << 20;
@@ -2001,8 +2015,8 @@ static int launch_bound(const GemmArgs& a, int waves, size_t lds_bytes, hipStrea
     rest.lds_wave_bytes = a.lds_wave_bytes;
     rest.spin_limit = a.spin_limit;
     rest.probe_delay = a.probe_delay;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, stream, a.A, a.qweight, a.scales, a.qzeros, a.C,
-                       packed, a.n, a.k, tiles_rem, rest);
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.tiles, (unsigned)a.split_k), dim3(threads), lds_bytes, stream, a.A,
+                       a.qweight, a.scales, a.qzeros, a.C, packed, a.n, a.k, tiles_rem, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
 
@@ -2119,9 +2133,9 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
                                            (int)lds_bytes)))
             return W4A16_ERR_HIP;
     }
-    const unsigned grid = (unsigned)(a.tiles * a.split_k);
-    if (a.m > 16 * MT || (MT > 1 && a.wk != 1) || a.wk > 2 || a.groups_base >= (1 << 20) || a.split_k >= (1 << 16) ||
-        a.groups_rem >= (1 << 15))
+    // (the second grid dimension holds at most 65535)
+    if (a.m > 16 * MT || (MT > 1 && a.wk != 1) || a.wk > 2 || a.groups_base >= (1 << 20) || a.split_k < 1 ||
+        a.split_k >= (1 << 16) || a.groups_rem >= (1 << 15) || a.tiles < 1 || a.tiles >= (1 << 16))
         return W4A16_ERR_UNSUPPORTED;
     const int packed = a.m | a.param_shift << 7 | a.wk << 9 | (int)((unsigned)a.groups_base << 12);
     const int split_rem = a.split_k | a.groups_rem << 16;
@@ -2132,7 +2146,7 @@ static int launch_stream_one(const StreamArgs& a, size_t lds_bytes, hipStream_t 
     rest.err_host = a.err_host;
     rest.spin_limit = a.spin_limit;
     rest.probe_delay = a.probe_delay;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a.A,
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.split_k, (unsigned)a.tiles), dim3((unsigned)(kStreamStrips * a.wk) * kWave), lds_bytes, stream, a.A,
                        a.qweight, a.scales, a.qzeros, a.C, packed, a.n, a.k, split_rem, rest);
     return W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;
 }
