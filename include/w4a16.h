@@ -67,7 +67,8 @@ extern "C" {
 #define W4A16_ERR_SHAPE (-2)       /* m < 1, n % 8, bad group_size, k % group_size */
 #define W4A16_ERR_SPLIT (-3)       /* split_k < 0; w4a16_gemm: k % split_k, (k / split_k) % group_size; _ex: more
                                       k parts than compute groups, uneven parts where they must be equal */
-#define W4A16_ERR_UNSUPPORTED (-4) /* group_size not in {32,64,128,256}, misaligned pointer, bad tuning value */
+#define W4A16_ERR_UNSUPPORTED (-4) /* group_size not in {32,64,128,256}, misaligned pointer, bad tuning value,
+                                      split_k above 65535 (the grid's second dimension) */
 #define W4A16_ERR_HIP (-5)         /* a HIP runtime call failed (allocation, launch) */
 #define W4A16_ERR_STATE (-6)       /* an earlier wait of the in-kernel zeroing ran out on this device (see above), or
                                       scratch would have to be allocated during a stream capture */
