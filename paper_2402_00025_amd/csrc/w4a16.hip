@@ -1545,6 +1545,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                               (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) &&
                               cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 &&
                               (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
+                              // (not just over one workgroup per compute unit where the per-wave kernel with its
+                              // service wavefront fills the machine once: n = 2560, k = 8192: 320 workgroups of
+                              // two strips take 5.1-5.7 us, six slices of 40 tiles 4.7-5.3)
+                              !(bits == 4 && m >= 5 && tiles64 <= 48 && (long long)((n + 127) / 128) * (cgroups / 4) > 256 &&
+                                (long long)((n + 127) / 128) * (cgroups / 4) < 352) &&
                               (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins;
     // A fourth audit (40 random shapes, then grids around its misses) added two more cases of no
     // split.  130-256 tiles of 64 columns up to k = 3584: one workgroup per tile over all of k
@@ -1736,7 +1741,15 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             if (bits == 2) width_ok = width_ok && S >= 3 && (m >= 5 || weights_half < (64ll << 20));
             if (bits == 8 && m < 5) width_ok = width_ok && weights_half >= (24ll << 20);
         }
-        const bool worth = S <= cgroups && width_ok &&
+        // Few column tiles (n up to 2560, up to 3072 with at most eight rows) with five rows or more stay
+        // with the per-wave kernel: its slices are 64 columns wide, so a quarter of the streaming kernel's
+        // split fills the machine (a quarter of the atomic requests), and with the zeroing protocol in a
+        // service wavefront its longer runs no longer lose: n = 1536, k = 12288, m = 6: 4.6 us with ten
+        // slices against 6.3 with the streaming kernel's 32; n = 2048, k = 16384, m = 16: 7.3 against 8.9;
+        // level from n = 3072 (m = 16) or 4096 (m = 6) on.
+        // (and up to n = 4096 while k stays at 9216 or below: n = 3776, k = 8448, m = 16: 6.9 us against 7.6)
+        const bool few_tiles = bits == 4 && m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72));
+        const bool worth = S <= cgroups && width_ok && !few_tiles &&
                            ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
@@ -1784,7 +1797,21 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // resident waves, every load of the launch in flight at once) or a long run of them
         // (few workgroups, about one per compute unit); runs of two to four groups lose to both.
         int parts = 1;  // k parts of a column tile = split_k * waves
-        if (packed_bytes <= (8ll << 20)) {
+        if (bits == 4 && m >= 5 && group_size >= 128 && tiles <= 128 && cgroups >= 8) {
+            // Five rows or more (packed-fp16 adds, zeroing protocol in a service wavefront): about one
+            // workgroup of four waves per compute unit, whatever run length that gives the waves, never
+            // less than one group each (n = 1024, k = 16384: 16 slices, 4.4-4.7 us, against 4.8-5.7 with
+            // 32; n = k = 4096 without two strips: four slices of two groups per wave 4.65 us, eight
+            // slices of one group 5.03).
+            int s = 256 / tiles < 64 ? 256 / tiles : 64;
+            while (s > 1 && 4 * s > cgroups) --s;
+            // ... and of the splits with the same longest run, the smallest that still gives 160 workgroups
+            // (k = 12288 on 16 tiles: twelve slices of two groups per wave take 4.2-4.7 us, sixteen slices,
+            // half of whose waves take two groups and half one, 4.8-5.6)
+            const int longest = (cgroups + 4 * s - 1) / (4 * s);
+            while (s > 1 && tiles * (s - 1) >= 160 && (cgroups + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
+            parts = 4 * s;
+        } else if (packed_bytes <= (8ll << 20)) {
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
             // one group per wave where that fits although no power of two gets there (n = 2304, k = 3072,
             // m = 1: six slices of four waves take 3.5 us, four slices with two groups per wave 4.3)
@@ -2031,6 +2058,12 @@ static int launch_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_
                 if constexpr (MODE == kAtomicPkF16Phase)
                     return launch_bound<V, IPG, kAtomicPkF16Service, 4, 1>(a, waves, lds_bytes, stream);
                 return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
+            }
+            // (longer runs too: run inside wave 0, the protocol puts a wait for the second batch of kernel
+            // arguments and the zero stores ahead of every wave's first load)
+            if constexpr (MODE == kAtomicPkF16Phase) {
+                if (a.groups_base >= 2) return launch_bound<V, IPG, kAtomicPkF16Service, 4, 2>(a, waves, lds_bytes, stream);
+                return launch_bound<V, IPG, kAtomicPkF16Service, 4, 0>(a, waves, lds_bytes, stream);
             }
             if (a.groups_base >= 2) return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
         }
