@@ -1566,18 +1566,26 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // (the same on 170-256 tiles of 32 columns up to k = 3200: a grid of n = 5600..8000, k = 2304..3200 where k / 128
     // is no multiple of four, m = 6, 16 has eight waves per tile 5-32 % ahead of what was chosen before, and within
     // 3 % of the best launch except at n = 5600, m = 16 from k = 2816 on, 6-7 %)
-    const bool narrow_tiles_fill =
+    // Since the per-wave kernel's zeroing protocol runs in a service wavefront, its split launches beat the
+    // unsplit narrow tiles with five rows or more from ten groups on (n = 1704, k = 1280, m = 8, 16: 3.2-3.5 us
+    // against 3.45-3.9; n = 7000, k = 2176, m = 16: 5.0 against 6.1; n = 3072, k = 3328, m = 16: 4.6 against 6.3):
+    // the rules on narrow tiles below then hold for up to four rows, and for 8-, 3- and 2-bit fields.
+    const bool narrow_ok = !(bits == 4 && m >= 5 && cgroups >= 10 && group_size >= 128);
+    const bool narrow_tiles_fill = narrow_ok &&
         bits == 4 && m >= 5 && dp_tiles <= 256 && !two_strip_ok &&
-        ((dp_cols == 16 && cgroups <= 26 && dp_tiles >= 130) || (dp_cols == 32 && cgroups <= (m <= 12 ? 25 : 22) && dp_tiles >= 170));
+        // (the 32-column case only up to k = 2176 since the per-wave kernel's zeroing protocol runs in a service
+        // wavefront: from k = 2304 on two slices of 64-column tiles are 9-26 % ahead on the same grid)
+        ((dp_cols == 16 && cgroups <= 26 && dp_tiles >= 130) || (dp_cols == 32 && cgroups <= 17 && dp_tiles >= 170));
     // (the first of them up to k = 2176 from two rows on: a grid of n = 4608..8000, k = 1792 and 2176,
     // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
     // from k = 2560 on two strips per wave win where they are to be had)
     // (the other field widths: k = 2176 on 249 tiles of 32 columns is 15-42 % slower unsplit at 3 and 8 bits)
-    const bool no_split = cgroups <= 8 || (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256) ||
+    const bool no_split = cgroups <= 8 ||
+                          (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256 && (narrow_ok || dp_cols == 64)) ||
                           // (from 120 tiles on: n = 8216, k = 1920, m = 4, 16: 129 tiles unsplit are 17 % ahead of two slices)
                           (cgroups <= 17 && tiles64 >= 120 && tiles64 <= 256) ||
                           // (k up to 1408 from 100 narrow tiles on: n = 1704..2000, m = 1..16: 27-45 % ahead of two slices)
-                          (cgroups <= 11 && dp_tiles >= 100 && dp_tiles <= 256) ||
+                          (cgroups <= 11 && dp_tiles >= 100 && dp_tiles <= 256 && (narrow_ok || dp_cols == 64)) ||
                           // (up to k = 3072 only since the streaming kernel's epilogue was shortened: n = 13936,
                           // k = 6144, m = 12 and n = 15672, k = 4992, m = 6 are 7-9 % faster with four slices of it)
                           (m >= 5 && ((cgroups <= 24 && fills_once) || (bits != 4 && m <= 12 && cgroups <= 50 && fills_once))) ||
@@ -1719,7 +1727,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                    stiles * S >= 224 && stiles * S <= 256) ||
                                   (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
-                                   (stream_waves == 2 * kStreamStrips || stiles * S >= 208)));
+                                   (stream_waves == 2 * kStreamStrips || stiles * S >= 200)));  // (200: n = 16984, k = 3200, m = 4: 201 workgroups take 9.5 us, 266 unsplit tiles 11.9)
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
         // The other field widths, from same-box sweeps against their per-wave launches (11 chosen
@@ -1748,7 +1756,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // slices against 6.3 with the streaming kernel's 32; n = 2048, k = 16384, m = 16: 7.3 against 8.9;
         // level from n = 3072 (m = 16) or 4096 (m = 6) on.
         // (and up to n = 4096 while k stays at 9216 or below: n = 3776, k = 8448, m = 16: 6.9 us against 7.6)
-        const bool few_tiles = bits == 4 && m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72));
+        // (and up to n = 8192 while k stays at 4096 or below: n = 6016, k = 3712, m = 12: two slices 5.9 us against 6.6)
+        const bool few_tiles = bits == 4 && m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72) ||
+                                                       (stiles <= 32 && cgroups <= 40));
         const bool worth = S <= cgroups && width_ok && !few_tiles &&
                            ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
@@ -1797,20 +1807,34 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // resident waves, every load of the launch in flight at once) or a long run of them
         // (few workgroups, about one per compute unit); runs of two to four groups lose to both.
         int parts = 1;  // k parts of a column tile = split_k * waves
+        int own_waves = 4;
         if (bits == 4 && m >= 5 && group_size >= 128 && tiles <= 128 && cgroups >= 8) {
             // Five rows or more (packed-fp16 adds, zeroing protocol in a service wavefront): about one
             // workgroup of four waves per compute unit, whatever run length that gives the waves, never
             // less than one group each (n = 1024, k = 16384: 16 slices, 4.4-4.7 us, against 4.8-5.7 with
             // 32; n = k = 4096 without two strips: four slices of two groups per wave 4.65 us, eight
             // slices of one group 5.03).
-            int s = 256 / tiles < 64 ? 256 / tiles : 64;
+            const int s_max = 256 / tiles < 64 ? 256 / tiles : 64;
+            int s = s_max;
             while (s > 1 && 4 * s > cgroups) --s;
-            // ... and of the splits with the same longest run, the smallest that still gives 160 workgroups
-            // (k = 12288 on 16 tiles: twelve slices of two groups per wave take 4.2-4.7 us, sixteen slices,
-            // half of whose waves take two groups and half one, 4.8-5.6)
-            const int longest = (cgroups + 4 * s - 1) / (4 * s);
-            while (s > 1 && tiles * (s - 1) >= 160 && (cgroups + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
-            parts = 4 * s;
+            if (tiles * s < 160) {
+                // a short k leaves that launch under-filled: two waves per slice with about three groups
+                // for the pair (n = 2048, k = 2816: six slices of two waves 3.7 us, five of four 4.3)
+                // (one group per wave up to twelve groups: n = 1704, k = 1280: five slices 3.2-3.6 us, four 3.9-4.3)
+                const int s2_want = cgroups <= 12 ? cgroups / 2 : (cgroups + 2) / 3;
+                const int s2 = s_max < s2_want ? s_max : s2_want;
+                if (s2 > s) {
+                    s = s2;
+                    own_waves = 2;
+                }
+            } else {
+                // ... and of the splits with the same longest run, the smallest that still gives 160 workgroups
+                // (k = 12288 on 16 tiles: twelve slices of two groups per wave take 4.2-4.7 us, sixteen slices,
+                // half of whose waves take two groups and half one, 4.8-5.6)
+                const int longest = (cgroups + 4 * s - 1) / (4 * s);
+                while (s > 1 && tiles * (s - 1) >= 160 && (cgroups + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
+            }
+            parts = own_waves * s;
         } else if (packed_bytes <= (8ll << 20)) {
             while (parts * 2 <= cgroups && tiles * parts * 2 <= 2048) parts *= 2;
             // one group per wave where that fits although no power of two gets there (n = 2304, k = 3072,
@@ -1847,7 +1871,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 while (parts * 2 <= cgroups && cgroups / (parts * 2) >= 4) parts *= 2;
             }
         }
-        int w = waves != 0 ? waves : parts < 4 ? parts : 4;
+        int w = waves != 0 ? waves : parts < own_waves ? parts : own_waves;
         if (w > parts) w = parts;
         split_k = parts / w;
         // The library's own choice stays where the reduction is accurate: every packed-fp16 add
