@@ -1757,8 +1757,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // level from n = 3072 (m = 16) or 4096 (m = 6) on.
         // (and up to n = 4096 while k stays at 9216 or below: n = 3776, k = 8448, m = 16: 6.9 us against 7.6)
         // (and up to n = 8192 while k stays at 4096 or below: n = 6016, k = 3712, m = 12: two slices 5.9 us against 6.6)
-        const bool few_tiles = bits == 4 && m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72) ||
-                                                       (stiles <= 32 && cgroups <= 40));
+        // (every field width: n = 2048, k = 16384, m = 16: 8-bit fields 9.0 us against 10.0, 2-bit 6.1 against 7.2)
+        const bool few_tiles = m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72) ||
+                                          (stiles <= 32 && cgroups <= 40));
         const bool worth = S <= cgroups && width_ok && !few_tiles &&
                            ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
@@ -1808,12 +1809,14 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // (few workgroups, about one per compute unit); runs of two to four groups lose to both.
         int parts = 1;  // k parts of a column tile = split_k * waves
         int own_waves = 4;
-        if (bits == 4 && m >= 5 && group_size >= 128 && tiles <= 128 && cgroups >= 8) {
+        if (m >= 5 && group_size >= 128 && tiles <= 128 && cgroups >= 8) {
             // Five rows or more (packed-fp16 adds, zeroing protocol in a service wavefront): about one
             // workgroup of four waves per compute unit, whatever run length that gives the waves, never
             // less than one group each (n = 1024, k = 16384: 16 slices, 4.4-4.7 us, against 4.8-5.7 with
             // 32; n = k = 4096 without two strips: four slices of two groups per wave 4.65 us, eight
-            // slices of one group 5.03).
+            // slices of one group 5.03).  The other field widths alike (44 seeded shapes with n up to 9600 at
+            // m = 6 and 16: 8-bit fields 4-6 % faster in the geometric mean over the shapes this changes, 3-bit
+            // and 2-bit fields 12-17 %).
             const int s_max = 256 / tiles < 64 ? 256 / tiles : 64;
             int s = s_max;
             while (s > 1 && 4 * s > cgroups) --s;
@@ -1823,7 +1826,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 // (one group per wave up to twelve groups: n = 1704, k = 1280: five slices 3.2-3.6 us, four 3.9-4.3)
                 const int s2_want = cgroups <= 12 ? cgroups / 2 : (cgroups + 2) / 3;
                 const int s2 = s_max < s2_want ? s_max : s2_want;
-                if (s2 > s) {
+                // (not where every wave of the four has exactly one group and there are 100 workgroups or more:
+                // n = 1408, k = 2560, m = 16: five slices of four waves 3.4 us, seven of two 3.8; 3-bit fields
+                // 3.5 against 4.3; n = 1024, k = 4096: eight slices of four 3.6 us, eleven of two 4.05)
+                const bool one_each = 4 * s == cgroups && tiles * s >= 100;
+                if (s2 > s && !one_each) {
                     s = s2;
                     own_waves = 2;
                 }
@@ -1831,8 +1838,14 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 // ... and of the splits with the same longest run, the smallest that still gives 160 workgroups
                 // (k = 12288 on 16 tiles: twelve slices of two groups per wave take 4.2-4.7 us, sixteen slices,
                 // half of whose waves take two groups and half one, 4.8-5.6)
-                const int longest = (cgroups + 4 * s - 1) / (4 * s);
-                while (s > 1 && tiles * (s - 1) >= 160 && (cgroups + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
+                // (one or two groups beyond an even share do not count as a longer run: the one or two waves that
+                // have them finish while the machine empties.  k = 12416 (97 groups) on 29 or 32 tiles: eight
+                // slices 4.9-5.2 us at m = 6 and 5.8-6.0 at m = 16, seven slices, where every workgroup has a
+                // wave with four groups, 5.2-5.5 and 6.25-6.6; k = 8320 (65 groups) on 16 tiles, m = 16: sixteen
+                // slices 4.6 us, ten 5.05)
+                const int counted = cgroups > 3 ? cgroups - 2 : 1;
+                const int longest = (counted + 4 * s - 1) / (4 * s);
+                while (s > 1 && tiles * (s - 1) >= 160 && (counted + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
             }
             parts = own_waves * s;
         } else if (packed_bytes <= (8ll << 20)) {
@@ -2128,8 +2141,10 @@ template <int IPG, int MODE, int BITS>
 static int launchn_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_t stream)
 {
     if (waves > 4) return W4A16_ERR_UNSUPPORTED;
-    if (a.groups_base >= 2) return launch_bound<4, IPG, MODE, 4, 2, BITS>(a, waves, lds_bytes, stream);
-    return launch_bound<4, IPG, MODE, 4, 0, BITS>(a, waves, lds_bytes, stream);
+    // (groups of 128: the phase protocol in a wavefront of its own, as for 4-bit fields)
+    constexpr int kMode = MODE == kAtomicPkF16Phase && IPG == 4 ? kAtomicPkF16Service : MODE;
+    if (a.groups_base >= 2) return launch_bound<4, IPG, kMode, 4, 2, BITS>(a, waves, lds_bytes, stream);
+    return launch_bound<4, IPG, kMode, 4, 0, BITS>(a, waves, lds_bytes, stream);
 }
 
 template <int IPG, int BITS>
