@@ -1544,7 +1544,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     const bool two_strip_ok = m >= (bits == 4 ? 1 : 2) && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
                               (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) &&
                               cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 &&
-                              (long long)((n + 127) / 128) * (cgroups / 4) >= 160 &&
+                              // (from 132 workgroups on: 140-144 of them are 10-22 % ahead of the single-strip launches
+                              // on n = 6144, k = 1536; n = 4608, k = 2048; n = 3584, k = 2560; n = 2304, k = 4096 at
+                              // m = 2..16; with 120-128 the single-strip launch with one group per wave is 3-7 % ahead)
+                              (long long)((n + 127) / 128) * (cgroups / 4) >= 132 &&
                               // (not just over one workgroup per compute unit where the per-wave kernel with its
                               // service wavefront fills the machine once: n = 2560, k = 8192: 320 workgroups of
                               // two strips take 5.1-5.7 us, six slices of 40 tiles 4.7-5.3)
@@ -1560,7 +1563,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // to k = 3328 where two strips are not to be had: eight waves per 16-column tile beat the
     // split launches by 4-46 % (most at five to twelve rows).
     const bool short_k_tiles_fill = cgroups <= 28 && tiles64 >= 130 && tiles64 <= 256;
-    const bool two_strips_there = two_strip_ok && !(tiles64 >= 170 || (m <= 8 && tiles64 >= 150));
+    // (a later grid, n = 9728..12288 x k = 1536..3072: two strips 3-15 % ahead up to 168 tiles at m = 2, 6 and,
+    // from k = 2048 on, 3-13 % ahead up to 192 tiles at m = 16; level or behind at 176 tiles and more with few rows)
+    const bool two_strips_there = two_strip_ok && (tiles64 < 170 || (m > 8 && cgroups >= 16));
     // (4-bit fields only: n = 2880, k = 2944 is 5-7 % slower that way at the other widths)
     // (from five rows on: n = 2304, k = 3072, m = 1 takes 4.2 us that way and 3.5 with six slices of 64-column tiles)
     // (the same on 170-256 tiles of 32 columns up to k = 3200: a grid of n = 5600..8000, k = 2304..3200 where k / 128
@@ -1569,8 +1574,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // Since the per-wave kernel's zeroing protocol runs in a service wavefront, its split launches beat the
     // unsplit narrow tiles with five rows or more from ten groups on (n = 1704, k = 1280, m = 8, 16: 3.2-3.5 us
     // against 3.45-3.9; n = 7000, k = 2176, m = 16: 5.0 against 6.1; n = 3072, k = 3328, m = 16: 4.6 against 6.3):
-    // the rules on narrow tiles below then hold for up to four rows, and for 8-, 3- and 2-bit fields.
-    const bool narrow_ok = !(bits == 4 && m >= 5 && cgroups >= 10 && group_size >= 128);
+    // the rules on narrow tiles below then hold for up to four rows.  The other field widths, whose per-wave
+    // launches use the same wavefront, from sixteen groups on (n = 8192, k = 2048, m = 16: two slices 4.3-5.8 us
+    // against 5.4-6.6 unsplit on 32-column tiles; at k = 1536 the unsplit tiles are 2-9 % ahead).
+    const bool narrow_ok = !(m >= 5 && cgroups >= (bits == 4 ? 10 : 16) && group_size >= 128);
     const bool narrow_tiles_fill = narrow_ok &&
         bits == 4 && m >= 5 && dp_tiles <= 256 && !two_strip_ok &&
         // (the 32-column case only up to k = 2176 since the per-wave kernel's zeroing protocol runs in a service
@@ -1580,10 +1587,17 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
     // m = 2..16 has eight waves per 32-column tile 2-10 % ahead at m = 2, 4 and 18-35 % at m = 8, 16;
     // from k = 2560 on two strips per wave win where they are to be had)
     // (the other field widths: k = 2176 on 249 tiles of 32 columns is 15-42 % slower unsplit at 3 and 8 bits)
+    // (two strips per wave first where they are to be had, as above: n = 6144..8192, k = 1536 or 2048, m = 2:
+    // 3.55-4.2 us against 3.95-4.65 on unsplit 32-column tiles; n = 9216, k = 1536, m = 2..16: 3.8-4.3 against
+    // 4.25-4.9 on unsplit 64-column tiles)
+    const bool strips_first = two_strips_there && (bits == 4 || cgroups / 4 >= 4);
     const bool no_split = cgroups <= 8 ||
-                          (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256 && (narrow_ok || dp_cols == 64)) ||
+                          (cgroups <= (m >= 2 && bits == 4 ? 17 : 12) && dp_tiles >= 130 && dp_tiles <= 256 && (narrow_ok || dp_cols == 64) &&
+                           !strips_first) ||
                           // (from 120 tiles on: n = 8216, k = 1920, m = 4, 16: 129 tiles unsplit are 17 % ahead of two slices)
-                          (cgroups <= 17 && tiles64 >= 120 && tiles64 <= 256) ||
+                          // (where that launch would use narrow tiles, only while those are in use: n = 8192,
+                          // k = 2048, m = 16: 256 tiles of 32 columns unsplit 5.5 us, two strips in four slices 4.5)
+                          (cgroups <= 17 && tiles64 >= 120 && tiles64 <= 256 && (narrow_ok || dp_cols == 64) && !strips_first) ||
                           // (k up to 1408 from 100 narrow tiles on: n = 1704..2000, m = 1..16: 27-45 % ahead of two slices)
                           (cgroups <= 11 && dp_tiles >= 100 && dp_tiles <= 256 && (narrow_ok || dp_cols == 64)) ||
                           // (up to k = 3072 only since the streaming kernel's epilogue was shortened: n = 13936,
@@ -1730,25 +1744,13 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                    (stream_waves == 2 * kStreamStrips || stiles * S >= 200)));  // (200: n = 16984, k = 3200, m = 4: 201 workgroups take 9.5 us, 266 unsplit tiles 11.9)
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
-        // The other field widths, from same-box sweeps against their per-wave launches (11 chosen
-        // and 2 x 36 random shapes at m = 2..16): not where the 4-bit plan does not split (one
-        // workgroup per 64-column tile over all of k fills the machine; n = 15392, k = 2048 at 8
-        // bits: +25 %; n = 13280, k = 3584, m = 16 at 2 bits: +12 %), not below k = 2560 (n = 28768,
-        // k = 1408 at 8 bits: +14-18 %), and from
-        // 12 Mi x 2 weights on (below, many short slices lose 6-15 %).  3-bit fields: a lane fetches two word rows
-        // per step of which it needs one and a half, so the address path binds sooner; the
-        // streaming kernel gains 4-10 % only from nine rows on, on 32 Mi x 2 weights or more with
-        // k >= 8192 and three slices or more, and loses 4-14 % elsewhere.  2-bit fields: not with two slices (+9-20 % at
-        // n >= 23520), and with few rows only below 64 Mi x 2 weights (+4-10 % above).  8-bit fields
-        // with few rows: from 24 Mi x 2 weights on (+4-5 % below).
-        bool width_ok = true;
-        if (bits != 4) {
-            width_ok = !no_split && !(fills_once && cgroups <= 50) && cgroups >= 20 && weights_half > (12ll << 20);
-            if (bits == 3)
-                width_ok = width_ok && m >= 9 && weights_half >= (32ll << 20) && cgroups >= 64 && S >= 3;
-            if (bits == 2) width_ok = width_ok && S >= 3 && (m >= 5 || weights_half < (64ll << 20));
-            if (bits == 8 && m < 5) width_ok = width_ok && weights_half >= (24ll << 20);
-        }
+        // The other field widths take the same rules: with the streaming kernel allowed wherever the 4-bit
+        // plan allows it, 102 shapes per width (n = 8192..28672 x k = 2048..16384 at m = 2, 6, 16 and 30
+        // seeded random ones) are within 0.6-1.1 % (geometric mean) of the best per-wave launch with an
+        // explicit split_k, and the shapes this changes are 14-16 % faster on average than under the narrower
+        // rules fitted to earlier versions of the two kernels (3-bit fields, n = 16896, k = 12288, m = 6:
+        // 23.5 us against 32.4; 2-bit fields, n = 28672, k = 4096, m = 16: 14.0 against 20.3); behind by more
+        // than 3 % only at m = 2 (four shapes, up to 7 %) and on n = 22304, k = 3200, m = 6 at 2 bits (5 %).
         // Few column tiles (n up to 2560, up to 3072 with at most eight rows) with five rows or more stay
         // with the per-wave kernel: its slices are 64 columns wide, so a quarter of the streaming kernel's
         // split fills the machine (a quarter of the atomic requests), and with the zeroing protocol in a
@@ -1760,7 +1762,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // (every field width: n = 2048, k = 16384, m = 16: 8-bit fields 9.0 us against 10.0, 2-bit 6.1 against 7.2)
         const bool few_tiles = m >= 5 && (stiles <= 10 || (stiles <= 12 && m <= 8) || (stiles <= 16 && cgroups <= 72) ||
                                           (stiles <= 32 && cgroups <= 40));
-        const bool worth = S <= cgroups && width_ok && !few_tiles &&
+        // (3-bit fields, whose lanes fetch two word rows per step of which they need one and a half: not with
+        // up to eight rows where the 64-column tiles alone give 190-256 workgroups: n = 14144, k = 15488, m = 2, 6:
+        // 24.5 us unsplit against 26.7; n = k = 16384: 25.8-26.0 against 27.0-27.1; level at m = 16)
+        const bool width_ok = !(bits == 3 && m <= 8 && fills_once);
+        const bool worth = S <= cgroups && !few_tiles && width_ok &&
                            ((m >= 5 && weights_half > (8ll << 20) && stiles * S >= min_blocks) || few_rows_ok);
         if (asked || (shape_ok && reduce_ok && worth)) {
             if (!shape_ok || !reduce_ok) return W4A16_ERR_UNSUPPORTED;
@@ -1845,7 +1851,21 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                 // slices 4.6 us, ten 5.05)
                 const int counted = cgroups > 3 ? cgroups - 2 : 1;
                 const int longest = (counted + 4 * s - 1) / (4 * s);
+                const int s_top = s;
                 while (s > 1 && tiles * (s - 1) >= 160 && (counted + 4 * (s - 1) - 1) / (4 * (s - 1)) == longest) --s;
+                // ... but first the largest split with at least 128 workgroups whose waves all get the same count, give
+                // or take two groups (k = 6272, 49 groups, on 24 tiles: six slices, two groups per wave and one wave
+                // with three, 4.2-4.6 us; seven to ten slices 4.4-5.1; k = 4096 on 36 tiles: four slices 4.1 us, five 4.35)
+                // (runs of up to three groups only: with longer ones a group more or less weighs little and the
+                // number of workgroups decides: k = 3968 on 65 tiles at 8, 3 and 2 bits: three slices 4.6-6.3 us,
+                // two slices of four groups per wave 5.3-7.4)
+                for (int e = s_top; e >= 2 && tiles * e >= 128; --e) {
+                    const int over = cgroups % (4 * e);
+                    if ((over <= 2 || over >= 4 * e - 3) && (cgroups + 2) / (4 * e) <= 3) {
+                        s = e;
+                        break;
+                    }
+                }
             }
             parts = own_waves * s;
         } else if (packed_bytes <= (8ll << 20)) {

@@ -5,6 +5,11 @@ chooses.  This is the measurement the plan's rules are fitted to and checked aga
 
     python -m paper_2402_00025_amd.plan_audit --random 40 --seed 1 --out profiles/plan_audit_seed1.txt
     python -m paper_2402_00025_amd.plan_audit --shapes 16,4096,4096 8,11008,4096
+    python -m paper_2402_00025_amd.plan_audit --bits 8 --random 20 --seed 3
+
+With --bits 8, 3 or 2 the candidates are the launches the entry points of that width expose: the
+per-wave kernel with every split_k that divides k into whole groups (an explicit split_k never
+selects the two-strip or the streaming kernel there), so the table bounds the plan from one side only.
 
 Timing protocol: calls captured in a HIP graph over a rotation of weight sets (at least 512 MiB, so
 the weights come from HBM), replayed 12 times, median of the HIP-event time per call.  The
@@ -58,20 +63,34 @@ def candidates(binding, m, n, k, g=128):
     return out
 
 
+def candidates_bits(binding, bits, m, n, k, g=128):
+    """The other field widths: every explicit split_k their entry points accept, as dicts."""
+    out = []
+    for s in (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 27, 32, 48, 64):
+        try:
+            pl = binding.w4a16_plan_bits(bits, m, n, k, g, split_k=s)
+        except binding.W4A16Error:
+            continue
+        if 96 <= -(-n // pl["tile_cols"]) * pl["split_k"] <= 1100:
+            out.append(dict(pl, ask=s))
+    return out
+
+
 class Problem:
-    def __init__(self, torch, m, n, k, g=128, seed=0):
-        per = n * k // 2
+    def __init__(self, torch, m, n, k, g=128, seed=0, bits=4):
+        per = n * k * bits // 8
         sets = max(2, -(-ROTATE_BYTES // per))
         gen = torch.Generator(device="cuda").manual_seed(seed)
         self.A = torch.randn((m, k), device="cuda", dtype=torch.float16, generator=gen)
         self.C = torch.empty((m, n), device="cuda", dtype=torch.float16)
         self.sets = []
         for _ in range(sets):
-            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (k // 8, n), device="cuda", dtype=torch.int32, generator=gen)
+            # (every bit pattern is a valid word at every width)
+            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (k * bits // 32, n), device="cuda", dtype=torch.int32, generator=gen)
             sc = (torch.rand((k // g, n), device="cuda", generator=gen) * 0.009 + 0.001).to(torch.float16)
-            qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (k // g, n // 8), device="cuda", dtype=torch.int32, generator=gen)
+            qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (k // g, n * bits // 32), device="cuda", dtype=torch.int32, generator=gen)
             self.sets.append((qw, sc, qz))
-        self.m, self.n, self.k, self.g = m, n, k, g
+        self.m, self.n, self.k, self.g, self.bits = m, n, k, g, bits
 
 
 def time_launch(torch, binding, p: Problem, pl, replays=12):
@@ -82,8 +101,12 @@ def time_launch(torch, binding, p: Problem, pl, replays=12):
     ptrs = [tuple(vp(t.data_ptr()) for t in s) for s in p.sets]
     count = max(len(ptrs), 32)
 
+    gemm_bits = {4: None, 8: L.w8a16_gemm, 3: L.w3a16_gemm, 2: L.w2a16_gemm}[p.bits]
+
     def call(i, stream):
         qw, sc, qz = ptrs[i % len(ptrs)]
+        if gemm_bits is not None:  # `ask`: the split_k argument (0 = the library's plan)
+            return gemm_bits(A, qw, sc, qz, C, p.m, p.n, p.k, p.g, pl["ask"], vp(stream.cuda_stream))
         return L.w4a16_gemm_ex(A, qw, sc, qz, C, p.m, p.n, p.k, p.g, pl["split_k"], pl["tile_cols"], pl["waves"],
                                pl["reduce"], vp(stream.cuda_stream))
 
@@ -141,6 +164,7 @@ def main(argv=None):
     ap.add_argument("--structured", action="store_true", help="the square and decoder-projection shapes of the bench")
     ap.add_argument("--random", type=int, default=0, help="number of random shapes")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--bits", type=int, default=4, choices=(2, 3, 4, 8), help="width of the packed fields")
     ap.add_argument("--out", default=None, help="write the table here as well")
     args = ap.parse_args(argv)
 
@@ -153,17 +177,25 @@ def main(argv=None):
     if args.structured:
         shapes += STRUCTURED
     shapes += random_shapes(args.random, args.seed)
-    lines = [f"# plan audit: {len(shapes)} shapes, group_size 128, 4-bit fields; us per call (cold weights, median of 12 graph replays)",
+    bits = args.bits
+    lines = [f"# plan audit: {len(shapes)} shapes, group_size 128, {bits}-bit fields; us per call (cold weights, median of 12 graph replays)",
              f"# command: python -m paper_2402_00025_amd.plan_audit {' '.join(sys.argv[1:] if argv is None else argv)}",
              "# shape m,n,k | plan launch, us | best launch, us | plan/best | every candidate: launch=us",
+             *(["# candidates: the per-wave kernel at every explicit split_k this width's entry point accepts"] if bits != 4 else []),
              "# launch = S<split_k>/t<tile_cols>/w<waves>/r<reduce>"]
     ratios = []
     for (m, n, k) in shapes:
+        if bits != 4:
+            n = -(-n // 32) * 32  # (3-bit fields need whole streams of 32 columns; kept for all three so that they share shapes)
         if m < 1 or n < 8 or n % 8 or k < 128 or k % 128:
             raise SystemExit(f"shape {m},{n},{k}: need m >= 1, n a multiple of 8, k a multiple of 128")
-        p = Problem(torch, m, n, k)
-        plan = binding.w4a16_plan(m, n, k, 128)
-        cands = candidates(binding, m, n, k)
+        p = Problem(torch, m, n, k, bits=bits)
+        if bits == 4:
+            plan = binding.w4a16_plan(m, n, k, 128)
+            cands = candidates(binding, m, n, k)
+        else:
+            plan = dict(binding.w4a16_plan_bits(bits, m, n, k, 128), ask=0)
+            cands = candidates_bits(binding, bits, m, n, k)
         if all(fmt(c) != fmt(plan) for c in cands):
             cands.append(plan)
         res = []

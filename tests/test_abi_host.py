@@ -296,10 +296,18 @@ def test_plan_of_the_other_field_widths():
         assert b.w4a16_plan_bits(bits, 16, 4096, 4096, 128, split_k=4)["tile_cols"] == 64   # a requested split
         assert b.w4a16_plan_bits(bits, 16, 4096, 4096, 128, dp=True)["split_k"] == 1
     assert b.w4a16_plan_bits(2, 16, 11008, 4096, 128)["tile_cols"] == 128
-    assert b.w4a16_plan_bits(3, 16, 11008, 4096, 128)["tile_cols"] == 64
+    assert b.w4a16_plan_bits(3, 16, 11008, 4096, 128)["tile_cols"] == 256
     assert b.w4a16_plan_bits(8, 16, 11008, 4096, 128)["tile_cols"] == 256
-    assert b.w4a16_plan_bits(3, 8, 8192, 8192, 128)["tile_cols"] == 64       # 3-bit streaming from nine rows on
-    assert b.w4a16_plan_bits(8, 3, 16384, 16384, 128)["tile_cols"] == 256    # few rows on a large matrix
+    for bits in (8, 3, 2):
+        # the streaming kernel under the 4-bit rules at every width
+        assert b.w4a16_plan_bits(bits, 8, 8192, 8192, 128) == b.w4a16_plan(8, 8192, 8192, 128)
+        # few rows on a large matrix (3-bit fields: not where 256 tiles of 64 columns fill the machine once)
+        assert b.w4a16_plan_bits(bits, 3, 16384, 16384, 128)["tile_cols"] == (64 if bits == 3 else 256)
+        assert b.w4a16_plan_bits(bits, 16, 16384, 16384, 128)["tile_cols"] == 256
+        assert b.w4a16_plan_bits(bits, 6, 28672, 4096, 128)["tile_cols"] == 256
+        # short k: unsplit narrow tiles up to fifteen groups, a split from sixteen on
+        assert b.w4a16_plan_bits(bits, 6, 8192, 1536, 128) == dict(split_k=1, tile_cols=32, waves=8, reduce=5)
+        assert b.w4a16_plan_bits(bits, 16, 8192, 2048, 128)["split_k"] > 1
     assert b.w4a16_plan_bits(4, 16, 4096, 4096, 128) == b.w4a16_plan(16, 4096, 4096, 128)
     L = b.lib()
     assert L.w4a16_plan_bits(5, 16, 4096, 4096, 128, 0, None, None, None, None) == b.ERR_UNSUPPORTED
