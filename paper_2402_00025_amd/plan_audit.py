@@ -165,6 +165,7 @@ def main(argv=None):
     ap.add_argument("--random", type=int, default=0, help="number of random shapes")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--bits", type=int, default=4, choices=(2, 3, 4, 8), help="width of the packed fields")
+    ap.add_argument("--keep", type=int, default=8, help="candidates listed per shape, fastest first")
     ap.add_argument("--out", default=None, help="write the table here as well")
     args = ap.parse_args(argv)
 
@@ -180,7 +181,7 @@ def main(argv=None):
     bits = args.bits
     lines = [f"# plan audit: {len(shapes)} shapes, group_size 128, {bits}-bit fields; us per call (cold weights, median of 12 graph replays)",
              f"# command: python -m paper_2402_00025_amd.plan_audit {' '.join(sys.argv[1:] if argv is None else argv)}",
-             "# shape m,n,k | plan launch, us | best launch, us | plan/best | every candidate: launch=us",
+             "# shape m,n,k | plan launch, us | best launch, us | plan/best | the fastest candidates: launch=us",
              *(["# candidates: the per-wave kernel at every explicit split_k this width's entry point accepts"] if bits != 4 else []),
              "# launch = S<split_k>/t<tile_cols>/w<waves>/r<reduce>"]
     ratios = []
@@ -210,7 +211,8 @@ def main(argv=None):
         best_t, best = res[0]
         ratios.append(t_plan / min(best_t, t_plan))
         line = (f"{m},{n},{k} | {fmt(plan)} {t_plan:.2f} | {fmt(best)} {best_t:.2f} | {t_plan / min(best_t, t_plan):.3f} | " +
-                " ".join(f"{fmt(c)}={t:.2f}" for (t, c) in res))
+                " ".join(f"{fmt(c)}={t:.2f}" for (t, c) in res[:args.keep]) +
+                (f" (+{len(res) - args.keep} slower)" if len(res) > args.keep else ""))
         lines.append(line)
         print(line[:200], flush=True)
         del p

@@ -1132,7 +1132,10 @@ def _random_large_shapes(count, seed):
 # close to two workgroups per compute unit, six slices of one group per wave, unsplit 32- and
 # 64-column tiles with a long k, 129 tiles
 _PLAN_RULE_SHAPES = [(2, 25112, 4096), (8, 22232, 7808), (1, 2304, 3072), (6, 7216, 2304), (16, 8216, 1920),
-                     (4, 1864, 1408), (12, 4248, 2688), (1, 23064, 8192)]
+                     (4, 1864, 1408), (12, 4248, 2688), (1, 23064, 8192),
+                     # two strips on 144 workgroups, one group per wave kept over a two-wave split, a nearly even
+                     # split (97 and 49 groups), two strips ahead of unsplit tiles
+                     (6, 6144, 1536), (16, 1024, 4096), (12, 1856, 12416), (6, 1536, 6272), (2, 8192, 2048), (16, 11264, 2560)]
 
 
 @pytest.mark.parametrize("m,n,k", _random_large_shapes(20, seed=77) + _PLAN_RULE_SHAPES)
@@ -1153,7 +1156,10 @@ def test_random_large_shapes_library_plan(oracle, m, n, k):
 
 @pytest.mark.parametrize("bits", [8, 3, 2])
 @pytest.mark.parametrize("m,n,k", [(m, n // 32 * 32, k) for (m, n, k) in _random_large_shapes(8, seed=78)] +   # a zero-point word holds 32 / bits columns
-                         [(16, 15392, 2048), (9, 8192, 8192), (20, 13312, 4096)])
+                         [(16, 15392, 2048), (9, 8192, 8192), (20, 13312, 4096),
+                          # runs of several groups per wave with the service wavefront (even and ragged), the streaming
+                          # kernel at six rows, two slices of it on a wide matrix, a split of short k
+                          (6, 1536, 12288), (16, 928, 11776), (6, 16896, 4096), (12, 27712, 5632), (16, 8192, 2048)])
 def test_random_large_shapes_other_field_widths(oracle, bits, m, n, k):
     """The same at 8-, 3- and 2-bit fields, whose plans have their own bounds; each width against its
     own oracle function."""
