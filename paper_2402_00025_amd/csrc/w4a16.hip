@@ -1551,7 +1551,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                               // (not just over one workgroup per compute unit where the per-wave kernel with its
                               // service wavefront fills the machine once: n = 2560, k = 8192: 320 workgroups of
                               // two strips take 5.1-5.7 us, six slices of 40 tiles 4.7-5.3)
-                              !(bits == 4 && m >= 5 && tiles64 <= 48 && (long long)((n + 127) / 128) * (cgroups / 4) > 256 &&
+                              // (with five to twelve rows up to 128 tiles: nine shapes with 264-320 such workgroups, e.g. n = 5120,
+                              // k = 4096: the per-wave launch 3-10 % ahead at m = 6, 8 (4.64 us against 5.12) and 1-8 % at
+                              // m = 12; from -5 to +6 % at m = 16, two strips ahead at m = 2)
+                              !(bits == 4 && m >= 5 && (tiles64 <= 48 || (m <= 12 && tiles64 <= 128)) &&
+                                (long long)((n + 127) / 128) * (cgroups / 4) > 256 &&
                                 (long long)((n + 127) / 128) * (cgroups / 4) < 352) &&
                               (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins;
     // A fourth audit (40 random shapes, then grids around its misses) added two more cases of no
@@ -1710,7 +1714,10 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         if (bits != 8 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && S >= 1 &&
             cgroups % (2 * S) == 0) {
             const int part_groups = cgroups / (2 * S);
-            if (part_groups >= 8 && (stiles * S <= 208 || (stiles * S <= 220 && part_groups >= 12)))
+            // (up to 224 with sixteen groups or more per part: n = 28672, k = 8192, m = 16: 23.6 us against 24.9-25.4;
+            // n = 28256, k = 11264, m = 1: 28.5 against 30.2)
+            if (part_groups >= 8 && (stiles * S <= 208 || (stiles * S <= 220 && part_groups >= 12) ||
+                                     (stiles * S <= 224 && part_groups >= 16)))
                 stream_waves = 2 * kStreamStrips;
         }
         const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
@@ -1737,11 +1744,18 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                   // ahead of one group per wave on six shapes of 44-73 MiB at m = 1, 2, 4; 2-7 % on
                                   // n = k = 8192 at m = 1, 4 and n = 8184, k = 6144 at m = 4 since the epilogue was shortened)
                                   // (from three rows on below 40 MiB: at one row the fixed-point launches stay 1-9 % ahead)
-                                  (weights_half >= ((bits == 4 && m >= 3 ? 16ll : 40ll) << 20) && stream_waves != 2 * kStreamStrips &&
-                                   stiles * S >= 224 && stiles * S <= 256) ||
+                                  // (at one or two rows as well where k / 128 is no multiple of four, so that one group per
+                                  // wave is not to be had: n = 10216, k = 4352, m = 1: 7.4 us against 8.0; n = 3352,
+                                  // k = 14592, m = 2: 8.1 against 8.8)
+                                  // (not where the 64-column tiles fill the machine once: n = 14160, k = 5504, m = 2: 10.2 us
+                                  // unsplit, 10.7 with four slices of the streaming kernel)
+                                  (weights_half >= ((bits == 4 && (m >= 3 || (cgroups % 4 != 0 && !fills_once)) ? 16ll : 40ll) << 20) &&
+                                   stream_waves != 2 * kStreamStrips && stiles * S >= 224 && stiles * S <= 256) ||
                                   (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
-                                   (stream_waves == 2 * kStreamStrips || stiles * S >= 200)));  // (200: n = 16984, k = 3200, m = 4: 201 workgroups take 9.5 us, 266 unsplit tiles 11.9)
+                                   // (n = 16984, k = 3200, m = 4: 201 workgroups take 9.5 us, 266 unsplit tiles 11.9;
+                                   // n = 16824, k = 3712, m = 1: 198 workgroups 9.6 us, 263 unsplit tiles 12.7)
+                                   (stream_waves == 2 * kStreamStrips || stiles * S >= 192)));
         // (from five rows on the per-wave kernel has to use the in-wave zeroing protocol instead
         // of the fixed-point adds, and the streaming kernel wins by up to 22 % at m = 6)
         // The other field widths take the same rules: with the streaming kernel allowed wherever the 4-bit
