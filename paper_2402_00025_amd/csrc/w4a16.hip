@@ -1749,7 +1749,7 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                   // k = 14592, m = 2: 8.1 against 8.8)
                                   // (not where the 64-column tiles fill the machine once: n = 14160, k = 5504, m = 2: 10.2 us
                                   // unsplit, 10.7 with four slices of the streaming kernel)
-                                  (weights_half >= ((bits == 4 && (m >= 3 || (cgroups % 4 != 0 && !fills_once)) ? 16ll : 40ll) << 20) &&
+                                  (weights_half >= (((m >= 3 || (cgroups % 4 != 0 && !fills_once)) ? 16ll : 40ll) << 20) &&
                                    stream_waves != 2 * kStreamStrips && stiles * S >= 224 && stiles * S <= 256) ||
                                   (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
