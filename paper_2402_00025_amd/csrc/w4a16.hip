@@ -1541,9 +1541,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                       : bits == 2 ? (cgroups / 4 > 8 ? (24ll << 20) : (32ll << 20))
                                                   : (20ll << 20);
     // (from one row on since the sum over the waves was shortened: 3 % ahead of the fixed-point launch at m = 1)
+    // (up to four rows only up to twelve slices: n = 3072, k = 8192: sixteen slices 5.5-5.6 us, one group per wave with
+    // fixed-point adds 5.0-5.3)
     const bool two_strip_ok = m >= (bits == 4 ? 1 : 2) && group_size >= 128 && !(tiles64 >= 200 && tiles64 <= 256) &&
                               (reduce == W4A16_REDUCE_AUTO || reduce == W4A16_REDUCE_ATOMIC_PK_F16_PHASE) &&
-                              cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= 16 &&
+                              cgroups % 4 == 0 && phase_split_ok(cgroups / 4) && cgroups / 4 <= (m <= 4 ? 12 : 16) &&
                               // (from 132 workgroups on: 140-144 of them are 10-22 % ahead of the single-strip launches
                               // on n = 6144, k = 1536; n = 4608, k = 2048; n = 3584, k = 2560; n = 2304, k = 4096 at
                               // m = 2..16; with 120-128 the single-strip launch with one group per wave is 3-7 % ahead)
@@ -1695,6 +1697,8 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
         // or 11136, m = 4..16: 435 are 10 % ahead of 174.  (n = 16960, k = 4352, 35 MiB, m = 12: 469 take
         // 12.5 us, 201 take 11.4.)
         bool two_per_unit = false;
+        // (not from 208 on: n = 18432, k = 7168 would gain 3-8 % with 504 workgroups instead of 216, but fifteen
+        // shapes of four audits with 208-223 lose 2-11 % that way)
         if (bits == 4 && S0 == 0 && stream_waves != 2 * kStreamStrips && waves == 0 && m <= 16 && stiles * S < 208 &&
             weights_half >= (40ll << 20)) {
             const bool eight_to_be_had = bits != 8 && cgroups % (2 * S) == 0 && cgroups / (2 * S) >= 8;
