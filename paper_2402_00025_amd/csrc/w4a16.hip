@@ -1753,7 +1753,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                                   // k = 14592, m = 2: 8.1 against 8.8)
                                   // (not where the 64-column tiles fill the machine once: n = 14160, k = 5504, m = 2: 10.2 us
                                   // unsplit, 10.7 with four slices of the streaming kernel)
-                                  (weights_half >= (((m >= 3 || (cgroups % 4 != 0 && !fills_once)) ? 16ll : 40ll) << 20) &&
+                                  // (and from 22 tiles of 256 columns on: with fewer the many slices cost more than they gain,
+                                  // n = 4096, k = 11008, m = 1: 7.2 us against 7.0; n = 5120, k = 13696, m = 2: 9.6 against 9.1)
+                                  (weights_half >= (((m >= 3 || (cgroups % 4 != 0 && !fills_once && stiles >= 22)) ? 16ll : 40ll) << 20) &&
                                    stream_waves != 2 * kStreamStrips && stiles * S >= 224 && stiles * S <= 256) ||
                                   (weights_half >= (40ll << 20) && two_per_unit) ||
                                   (weights_half > (8ll << 20) && pw_bad &&
