@@ -47,7 +47,7 @@ def candidates(binding, m, n, k, g=128):
 
     splits = [s for s in (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16, 20, 24, 27, 32, 48, 64) if s <= groups]
     for s in splits:
-        for w in (1, 2, 4):
+        for w in (1, 2, 4) + ((8, 16) if g < 128 else ()):  # (short groups: larger workgroups as well)
             if s * w <= groups:
                 add(s, 64, w)
         add(s, 256, 4)
@@ -165,6 +165,7 @@ def main(argv=None):
     ap.add_argument("--random", type=int, default=0, help="number of random shapes")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--bits", type=int, default=4, choices=(2, 3, 4, 8), help="width of the packed fields")
+    ap.add_argument("--group-size", type=int, default=128, choices=(32, 64, 128, 256), help="quantisation group size")
     ap.add_argument("--keep", type=int, default=8, help="candidates listed per shape, fastest first")
     ap.add_argument("--out", default=None, help="write the table here as well")
     args = ap.parse_args(argv)
@@ -179,7 +180,8 @@ def main(argv=None):
         shapes += STRUCTURED
     shapes += random_shapes(args.random, args.seed)
     bits = args.bits
-    lines = [f"# plan audit: {len(shapes)} shapes, group_size 128, {bits}-bit fields; us per call (cold weights, median of 12 graph replays)",
+    g = args.group_size
+    lines = [f"# plan audit: {len(shapes)} shapes, group_size {g}, {bits}-bit fields; us per call (cold weights, median of 12 graph replays)",
              f"# command: python -m paper_2402_00025_amd.plan_audit {' '.join(sys.argv[1:] if argv is None else argv)}",
              "# shape m,n,k | plan launch, us | best launch, us | plan/best | the fastest candidates: launch=us",
              *(["# candidates: the per-wave kernel at every explicit split_k this width's entry point accepts"] if bits != 4 else []),
@@ -190,13 +192,13 @@ def main(argv=None):
             n = -(-n // 32) * 32  # (3-bit fields need whole streams of 32 columns; kept for all three so that they share shapes)
         if m < 1 or n < 8 or n % 8 or k < 128 or k % 128:
             raise SystemExit(f"shape {m},{n},{k}: need m >= 1, n a multiple of 8, k a multiple of 128")
-        p = Problem(torch, m, n, k, bits=bits)
+        p = Problem(torch, m, n, k, g=g, bits=bits)
         if bits == 4:
-            plan = binding.w4a16_plan(m, n, k, 128)
-            cands = candidates(binding, m, n, k)
+            plan = binding.w4a16_plan(m, n, k, g)
+            cands = candidates(binding, m, n, k, g)
         else:
-            plan = dict(binding.w4a16_plan_bits(bits, m, n, k, 128), ask=0)
-            cands = candidates_bits(binding, bits, m, n, k)
+            plan = dict(binding.w4a16_plan_bits(bits, m, n, k, g), ask=0)
+            cands = candidates_bits(binding, bits, m, n, k, g)
         if all(fmt(c) != fmt(plan) for c in cands):
             cands.append(plan)
         res = []
