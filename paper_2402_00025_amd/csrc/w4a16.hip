@@ -2134,17 +2134,21 @@ static int launch_one(const GemmArgs& a, int waves, size_t lds_bytes, hipStream_
                 // few registers per wave: the phase protocol gets a wave of its own
                 if constexpr (MODE == kAtomicPkF16Phase)
                     return launch_bound<V, IPG, kAtomicPkF16Service, 4, 1>(a, waves, lds_bytes, stream);
-                return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
+                else
+                    return launch_bound<V, IPG, MODE, 4, 1>(a, waves, lds_bytes, stream);
             }
             // (longer runs too: run inside wave 0, the protocol puts a wait for the second batch of kernel
             // arguments and the zero stores ahead of every wave's first load)
             if constexpr (MODE == kAtomicPkF16Phase) {
                 if (a.groups_base >= 2) return launch_bound<V, IPG, kAtomicPkF16Service, 4, 2>(a, waves, lds_bytes, stream);
                 return launch_bound<V, IPG, kAtomicPkF16Service, 4, 0>(a, waves, lds_bytes, stream);
+            } else {
+                if (a.groups_base >= 2) return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
+                return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
             }
-            if (a.groups_base >= 2) return launch_bound<V, IPG, MODE, 4, 2>(a, waves, lds_bytes, stream);
+        } else {
+            return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
         }
-        return launch_bound<V, IPG, MODE, 4, 0>(a, waves, lds_bytes, stream);
     }
     if constexpr (V == 4 && IPG == 4) {
         // one group per wave needs few registers, so large workgroups lose nothing
@@ -2192,9 +2196,10 @@ static int launchn_mode(const GemmArgs& a, int waves, size_t lds_bytes, int mode
 {
     switch (mode) {
     case kDirect: return launchn_one<IPG, kDirect, BITS>(a, waves, lds_bytes, stream);
-    case kAtomicF32: return launchn_one<IPG, kAtomicF32, BITS>(a, waves, lds_bytes, stream);
+    // (the entry points of these widths take no `reduce`: the plan's three flavours only)
+    case kAtomicF32: return W4A16_ERR_UNSUPPORTED;
+    case kWorkspace: return W4A16_ERR_UNSUPPORTED;
     case kAtomicPkF16: return launchn_one<IPG, kAtomicPkF16, BITS>(a, waves, lds_bytes, stream);
-    case kWorkspace: return launchn_one<IPG, kWorkspace, BITS>(a, waves, lds_bytes, stream);
     case kAtomicFixed: return launchn_one<IPG, kAtomicFixed, BITS>(a, waves, lds_bytes, stream);
     default: return launchn_one<IPG, kAtomicPkF16Phase, BITS>(a, waves, lds_bytes, stream);
     }
