@@ -1556,7 +1556,9 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
                               // (with five to twelve rows up to 128 tiles: nine shapes with 264-320 such workgroups, e.g. n = 5120,
                               // k = 4096: the per-wave launch 3-10 % ahead at m = 6, 8 (4.64 us against 5.12) and 1-8 % at
                               // m = 12; from -5 to +6 % at m = 16, two strips ahead at m = 2)
-                              !(bits == 4 && m >= 5 && (tiles64 <= 48 || (m <= 12 && tiles64 <= 128)) &&
+                              // (where that launch gets runs of three groups or fewer: n = 6144, k = 3584, m = 8 would leave it two
+                              // slices with 3.5 groups per wave, 5.7 us against 5.2 for 336 workgroups of two strips)
+                              !(bits == 4 && m >= 5 && (tiles64 <= 48 || (m <= 12 && tiles64 <= 128 && cgroups <= 12 * (256 / tiles64))) &&
                                 (long long)((n + 127) / 128) * (cgroups / 4) > 256 &&
                                 (long long)((n + 127) / 128) * (cgroups / 4) < 352) &&
                               (long long)k * n / 2 < two_strip_limit && (size_t)n <= 16 * (size_t)kPhaseOrigins;
