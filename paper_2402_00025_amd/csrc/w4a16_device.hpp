@@ -244,6 +244,8 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes)
 // it should not displace the activations and group parameters that the other workgroups of a compute
 // die re-read from its L2 (same box, library plan, us per call: m = 8, n = k = 16384: 24.4-24.9 -> 23.2-23.5;
 // n = 28672, k = 8192, m = 16: 23.6 -> 22.6; m = 16, n = k = 8192: 9.54 -> 9.35; n = k = 4096: 4.44 -> 4.38).
+// Only on the 128-bit loads: a 16-column tile's 64 bytes of a word row share their cache line with the
+// neighbouring tile's, which then has to fetch it again (n = 3480, k = 2176, m = 4, unsplit 16-column tiles: 4.2 -> 4.5).
 constexpr int kWeightLoadAux = 2;  // the builtin's aux bit 1: `nt` on gfx950
 
 // V consecutive 32-bit words of the weight stream.
@@ -252,14 +254,14 @@ template <> struct Words<1> {
     uint32_t v[1];
     __device__ __forceinline__ void load(rsrc_t r, uint32_t voff, uint32_t soff)
     {
-        v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, kWeightLoadAux);
+        v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
     }
 };
 template <> struct Words<2> {
     uint32_t v[2];
     __device__ __forceinline__ void load(rsrc_t r, uint32_t voff, uint32_t soff)
     {
-        u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, kWeightLoadAux);
+        u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
         v[0] = t.x; v[1] = t.y;
     }
 };
