@@ -398,10 +398,10 @@ def main():
                            "runs of the small shapes are host-bound"}
 
     # the achievable ceiling on this machine: a plain read of the packed weights alone, same protocol
-    ev_read = min(time_calls(make_call(w, "read", split_k=shape), args.table_steps, 50)[1] for shape in range(5))
+    ev_read = min(time_calls(make_call(w, "read", split_k=shape), args.table_steps, 50)[1] for shape in range(10))
     packed_bytes = w.sets[0][0].numel() * 4
     extra["plain_read_of_packed_weights"] = {"bytes": packed_bytes, "us_per_launch": ev_read * 1e6,
-                                             "note": "best of the probe's five launch shapes",
+                                             "note": "best of the probe's ten launch shapes (five, with and without the non-temporal hint)",
                                              "GBps": packed_bytes / ev_read / 1e9,
                                              "frac_of_peak": packed_bytes / ev_read / 1e9 / HBM_PEAK_GBPS,
                                              "gemm_over_read": ev / ev_read}
@@ -486,7 +486,7 @@ def main():
                 res.append({"split_k": S, "us": e * 1e6, "GBps": wb.bytes / e / 1e9,
                             "frac_of_peak": wb.bytes / e / 1e9 / HBM_PEAK_GBPS})
             _, e_dp = time_calls(make_call(wb, "dp"), big_steps, 30)
-            e_rd = min(time_calls(make_call(wb, "read", split_k=shape), big_steps, 30)[1] for shape in range(5))
+            e_rd = min(time_calls(make_call(wb, "read", split_k=shape), big_steps, 30)[1] for shape in range(10))
             extra[key] = {"splitk": res, "dp_us": e_dp * 1e6, "plain_read_of_packed_weights_us": e_rd * 1e6}
             best = min(res, key=lambda r: r["us"])
             log(f"[bench] m={mm} n=k={nk}: best split_k={best['split_k']} {best['us']:.2f} us "

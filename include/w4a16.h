@@ -257,8 +257,9 @@ int w4a16_dequant(const void* qweight, const void* scales, const void* qzeros, v
  * device buffer, result discarded.  Timed like a GEMM call on the same buffers it gives the
  * ceiling that any kernel which has to read them can reach on this machine.  `shape` 0..4
  * picks one of five launch shapes (loads in flight per lane x workgroups x threads: 8 x one
- * pass x 256, 8 x 2048 x 256, 4 x 2048 x 512, 2 x 8192 x 256, 1 x 16384 x 256); which is fastest
- * depends on the size, so a bench takes the best of them.
+ * pass x 256, 8 x 2048 x 256, 4 x 2048 x 512, 2 x 8192 x 256, 1 x 16384 x 256), 5..9 the same
+ * five with the non-temporal hint on the loads; which is fastest depends on the size, so a
+ * bench takes the best of them.  Any other shape: W4A16_ERR_UNSUPPORTED.
  */
 int w4a16_read_probe(const void* buffer, long long bytes, int shape, void* stream);
 

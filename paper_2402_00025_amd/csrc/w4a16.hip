@@ -1274,21 +1274,26 @@ __global__ void actorder_gather_kernel(const _Float16* __restrict__ A, const int
 }
 
 // ---- measurement probe: a plain coalesced read of a buffer (U 16-byte loads in flight per
-// lane, grid-stride), the ceiling any kernel that has to read those bytes can reach
-template <int U>
+// lane, grid-stride), the ceiling any kernel that has to read those bytes can reach.  NT: with
+// the non-temporal hint that the GEMM kernels' weight loads carry.
+template <int U, bool NT = false>
 __global__ void __launch_bounds__(512) read_probe_kernel(const u32x4_t* __restrict__ p, size_t vecs, uint32_t* sink)
 {
+    auto fetch = [&](size_t at) {
+        if constexpr (NT) return __builtin_nontemporal_load(p + at);
+        else return p[at];
+    };
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     u32x4_t acc = {0u, 0u, 0u, 0u};
     for (; i + (U - 1) * stride < vecs; i += U * stride) {
         u32x4_t v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+        for (int u = 0; u < U; ++u) v[u] = fetch(i + u * stride);
 #pragma unroll
         for (int u = 0; u < U; ++u) acc ^= v[u];
     }
-    for (; i < vecs; i += stride) acc ^= p[i];
+    for (; i < vecs; i += stride) acc ^= fetch(i);
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && sink) sink[0] = acc.x;  // keeps the loads alive
 }
 
@@ -2831,6 +2836,17 @@ int w4a16_read_probe(const void* buffer, long long bytes, int shape, void* strea
     case 2: hipLaunchKernelGGL(w4a16::read_probe_kernel<4>, dim3(2048), dim3(512), 0, st, p, vecs, none); break;
     case 3: hipLaunchKernelGGL(w4a16::read_probe_kernel<2>, dim3(8192), dim3(256), 0, st, p, vecs, none); break;
     case 4: hipLaunchKernelGGL(w4a16::read_probe_kernel<1>, dim3(16384), dim3(256), 0, st, p, vecs, none); break;
+    // 5..9: the same five with the non-temporal hint
+    case 5: {
+        const size_t blocks = (vecs + 256 * 8 - 1) / (256 * 8);
+        hipLaunchKernelGGL((w4a16::read_probe_kernel<8, true>), dim3((unsigned)(blocks < 65535 ? blocks : 65535)), dim3(256), 0,
+                           st, p, vecs, none);
+        break;
+    }
+    case 6: hipLaunchKernelGGL((w4a16::read_probe_kernel<8, true>), dim3(2048), dim3(256), 0, st, p, vecs, none); break;
+    case 7: hipLaunchKernelGGL((w4a16::read_probe_kernel<4, true>), dim3(2048), dim3(512), 0, st, p, vecs, none); break;
+    case 8: hipLaunchKernelGGL((w4a16::read_probe_kernel<2, true>), dim3(8192), dim3(256), 0, st, p, vecs, none); break;
+    case 9: hipLaunchKernelGGL((w4a16::read_probe_kernel<1, true>), dim3(16384), dim3(256), 0, st, p, vecs, none); break;
     default: return W4A16_ERR_UNSUPPORTED;
     }
     return w4a16::W4A16_HIP(hipGetLastError()) ? W4A16_OK : W4A16_ERR_HIP;

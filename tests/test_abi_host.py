@@ -106,7 +106,7 @@ def test_gemm_rejects_before_touching_hip():
     assert L.w4a16_read_probe(None, 4096, 0, None) == b.ERR_NULL
     assert L.w4a16_read_probe(p, 4100, 0, None) == b.ERR_SHAPE
     assert L.w4a16_read_probe(odd, 4096, 0, None) == b.ERR_SHAPE
-    assert L.w4a16_read_probe(p, 4096, 9, None) == b.ERR_UNSUPPORTED
+    assert L.w4a16_read_probe(p, 4096, 10, None) == b.ERR_UNSUPPORTED
     assert L.w4a16_unpack(None, p, p, p, 1024, 1024, 128, None) == b.ERR_NULL
     assert L.w4a16_unpack(p, p, p, p, 1020, 1024, 128, None) == b.ERR_SHAPE
     assert L.w4a16_dequant(p, p, p, None, 1024, 1024, 128, None) == b.ERR_NULL
