@@ -25,6 +25,25 @@ def _gpu():
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------ probes: the plain read
+@pytest.mark.parametrize("nbytes", [16, 4096 + 16, 8 << 20])
+def test_read_probe_runs_every_launch_shape_and_writes_nothing(nbytes):
+    """The measurement probe (ten launch shapes, five of them with the non-temporal hint) reads a
+    buffer of any multiple of 16 bytes and leaves it and its surroundings as they were."""
+    import torch
+
+    guard = 256
+    buf = torch.randint(0, 255, (nbytes + 2 * guard,), dtype=torch.uint8, device="cuda")
+    before = buf.clone()
+    view = buf[guard:guard + nbytes]
+    for shape in range(10):
+        b.w4a16_read_probe(view, nbytes, shape)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    with pytest.raises(b.W4A16Error):
+        b.w4a16_read_probe(view, nbytes, 10)
+
+
 # ------------------------------------------------------------------ probes: bit-exact unpack
 @pytest.mark.parametrize("n,k,g", [(1024, 1024, 128), (200, 384, 128), (8, 32, 32), (72, 512, 64)])
 def test_unpack_bit_exact(oracle, n, k, g):
