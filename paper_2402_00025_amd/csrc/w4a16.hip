@@ -1727,8 +1727,11 @@ static int make_plan(int m, int n, int k, int group_size, bool dp, int split_k, 
             const int part_groups = cgroups / (2 * S);
             // (up to 224 with sixteen groups or more per part: n = 28672, k = 8192, m = 16: 23.6 us against 24.9-25.4;
             // n = 28256, k = 11264, m = 1: 28.5 against 30.2)
-            if (part_groups >= 8 && (stiles * S <= 208 || (stiles * S <= 220 && part_groups >= 12) ||
-                                     (stiles * S <= 224 && part_groups >= 16)))
+            // Since the weight loads carry the non-temporal hint eight waves lead further up: 57 launches with
+            // 232-256 workgroups (n = 7424..31744, m = 1, 6, 16) have them 2-11 % ahead at 232-236 (29 of 30), 0-10 % at
+            // 240 (one of twelve 1 % behind), at 248 3-9 % ahead with twelve groups per part and level or 1.5 %
+            // behind with eight, and 5-8 % behind at 256.
+            if (part_groups >= 8 && (stiles * S <= 240 || (stiles * S <= 248 && part_groups >= 12)))
                 stream_waves = 2 * kStreamStrips;
         }
         const int min_blocks = stream_waves == 2 * kStreamStrips ? 128 : g_stream_min_blocks;
